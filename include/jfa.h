@@ -1,0 +1,119 @@
+/*
+ * jfa.h -- C ABI of libjfa.so: Jagged Flash Attention for AMD MI355X (gfx950).
+ *
+ * The operation (paper Section 2: jagged tensor = one values tensor holding all samples back to
+ * back + one offsets tensor marking sample boundaries; Section 2.1: flash attention -- two matrix
+ * products and a softmax fused block by block with the online-softmax rescaling -- applied to
+ * jagged inputs with no padding; Section 2.2: forward and backward):
+ *
+ *   sample b owns rows offsets[b] .. offsets[b+1]-1 (L_b rows) of q, k, v, each [sum_B, H, D];
+ *   for every sample b and head h, with Q, K, V the L_b x D slices,
+ *       out = softmax(Q K^T / sqrt(D)) V            (non-causal, every query sees every key of
+ *       lse = logsumexp_j(Q K^T / sqrt(D))           its own sample and nothing else)
+ *   and, given dout, the gradients dq, dk, dv of sum(out * dout).
+ *   No score matrix is written to memory and no buffer is sized by B * max_len.
+ *
+ * Conventions common to every call
+ *   - Every pointer is a DEVICE pointer (HBM of the current HIP device) unless marked "host".
+ *   - Values tensors are row-major contiguous [sum_B, H, D]: element (row, h, d) at
+ *     (row * H + h) * D + d.  16-byte alignment of the base pointers is required.
+ *   - offsets is int64 [B+1] ON THE DEVICE, offsets[0] = 0, non-decreasing, offsets[B] = sum_B.
+ *     It is only read by kernels; the host never dereferences it, so calls do not synchronise.
+ *     Zero-length samples are legal and produce nothing.
+ *   - lse / delta are fp32 [H, sum_B]: element (h, row) at h * sum_B + row, sum_B = offsets[B].
+ *     lse is the natural-log logsumexp of the scaled scores.
+ *   - max_len is an upper bound on L_b (a hint that bounds nothing in addressing); results are
+ *     correct for any max_len >= max_b L_b.  L_b > max_len is undefined on the hot calls and can
+ *     be detected with jfa_check_offsets.
+ *   - stream is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
+ *     and return; outputs are ready when the stream reaches that point.
+ *   - Ownership: the caller owns every buffer it passes and must keep it alive until the enqueued
+ *     work has run.  The library keeps a small private work table per (device, stream), O(B)
+ *     bytes, see jfa_workspace_bytes; it is grown with hipMalloc on the first call that needs a
+ *     larger one (never inside later calls of the same or smaller B) and kept until process exit.
+ *   - Outputs must not alias inputs.  Rows >= sum_B of any buffer are neither read nor written.
+ *   - Supported shapes: D in {32, 64, 128}; H >= 1; 0 <= B < 2^31 / 2; sum over samples of
+ *     ceil(L_b / 64) times H below 2^31.
+ *   - Return value: JFA_OK or a negative jfa_status; jfa_last_error() describes the most recent
+ *     failure on the calling thread.  On error nothing has been enqueued.  B == 0 is JFA_OK.
+ */
+#ifndef JFA_H_
+#define JFA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    JFA_OK = 0,
+    JFA_ERR_INVALID_ARG = -1, /* null pointer with B > 0, negative size, misaligned pointer */
+    JFA_ERR_UNSUPPORTED = -2, /* D outside {32, 64, 128}, sizes beyond the stated limits */
+    JFA_ERR_ALLOC = -3,       /* the private work table could not be allocated */
+    JFA_ERR_HIP = -4          /* a HIP runtime call or kernel launch failed */
+} jfa_status;
+
+/*
+ * Forward, bf16 (Section 2.1).  q, k, v, out: bf16 [sum_B, H, D]; lse: fp32 [H, sum_B].
+ * Scores and the P V product run on bf16 MFMA with fp32 accumulation; the softmax is fp32;
+ * probabilities are rounded to bf16 before the second product; out is rounded to bf16 once.
+ */
+int jfa_forward(const void *q, const void *k, const void *v, const int64_t *offsets, int64_t B, int64_t max_len,
+                int H, int D, void *out, float *lse, void *stream);
+
+/* Forward, fp32 end to end (same operation; plain FMA arithmetic, for small-tolerance use). */
+int jfa_forward_f32(const float *q, const float *k, const float *v, const int64_t *offsets, int64_t B,
+                    int64_t max_len, int H, int D, float *out, float *lse, void *stream);
+
+/*
+ * Backward, bf16 (Section 2.2 states that every jagged operator has a backward).
+ * Inputs: q, k, v as in the forward; out and lse as produced by jfa_forward; dout bf16 [sum_B, H, D].
+ * Outputs: dq, dk, dv bf16 [sum_B, H, D]; delta fp32 [H, sum_B] = rowsum(dout * out), a
+ * caller-provided buffer that the call fills and then reads (it is an output, and the only
+ * sum_B-sized scratch of the backward).
+ */
+int jfa_backward(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
+                 const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, void *dq, void *dk, void *dv,
+                 float *delta, void *stream);
+
+/* Backward, fp32 end to end. */
+int jfa_backward_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
+                     const float *lse, const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, float *dq,
+                     float *dk, float *dv, float *delta, void *stream);
+
+/*
+ * The offsets-driven work schedule on its own (the first kernel of every call above), for
+ * inspection and tests.  For row blocks of block_rows rows it writes, on the device,
+ *   order      int32 [B]    sample ids, samples with more row blocks first
+ *   tile_start int32 [B+1]  exclusive prefix sum of ceil(L_order[p] / block_rows); tile_start[B] = T
+ * A work item w in [0, T*H) is (sample, head, row block): p = the position with
+ * tile_start[p]*H <= w < tile_start[p+1]*H, r = w - tile_start[p]*H, n = tile_start[p+1]-tile_start[p],
+ * head = r / n, block = r % n.  block_rows must be a positive multiple of 32.
+ */
+int jfa_build_schedule(const int64_t *offsets, int64_t B, int block_rows, int32_t *order, int32_t *tile_start,
+                       void *stream);
+
+/*
+ * Debug check of an offsets array; SYNCHRONISES the stream.  *host_flags (host pointer) receives a
+ * bit mask: 1 = offsets[0] != 0, 2 = decreasing somewhere, 4 = some L_b > max_len.  0 means valid.
+ */
+int jfa_check_offsets(const int64_t *offsets, int64_t B, int64_t max_len, void *stream, int *host_flags);
+
+/*
+ * Bytes of library-private device memory a call with these sizes uses (pass: 0 = forward,
+ * 1 = backward).  It depends on B only -- never on max_len or B * max_len.
+ */
+size_t jfa_workspace_bytes(int64_t B, int64_t max_len, int H, int D, int pass);
+
+/* Description of the last failure on this thread (a static, thread-local string; never freed). */
+const char *jfa_last_error(void);
+
+/* major * 10000 + minor * 100 + patch. */
+int jfa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JFA_H_ */

@@ -1,0 +1,149 @@
+"""ctypes binding of libjfa.so: argument marshalling only -- every step runs in the HIP kernels.
+
+Functions mirror the C ABI of include/jfa.h.  Tensors are torch CUDA (ROCm) tensors used purely as
+device memory; work is enqueued on torch's current stream.  A missing library raises: there is no
+CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libjfa.so")
+_lib = None
+
+JFA_OK = 0
+JFA_ERR_INVALID_ARG = -1
+JFA_ERR_UNSUPPORTED = -2
+JFA_ERR_ALLOC = -3
+JFA_ERR_HIP = -4
+
+EXPORTS = (
+    "jfa_forward", "jfa_forward_f32", "jfa_backward", "jfa_backward_f32", "jfa_build_schedule",
+    "jfa_check_offsets", "jfa_workspace_bytes", "jfa_last_error", "jfa_version",
+)
+
+
+class JfaError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"libjfa status {status}: {message}")
+        self.status = status
+
+
+def load() -> ctypes.CDLL:
+    """Load libjfa.so (built by ``python -m paper_2409_15373_amd.build``); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: run `python -m paper_2409_15373_amd.build` "
+                          "(hipcc, gfx950). There is no fallback path.")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+    lib.jfa_forward.restype = i32
+    lib.jfa_forward.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, vp]
+    lib.jfa_forward_f32.restype = i32
+    lib.jfa_forward_f32.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, vp]
+    lib.jfa_backward.restype = i32
+    lib.jfa_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp]
+    lib.jfa_backward_f32.restype = i32
+    lib.jfa_backward_f32.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp]
+    lib.jfa_build_schedule.restype = i32
+    lib.jfa_build_schedule.argtypes = [vp, i64, i32, vp, vp, vp]
+    lib.jfa_check_offsets.restype = i32
+    lib.jfa_check_offsets.argtypes = [vp, i64, i64, vp, ctypes.POINTER(ctypes.c_int)]
+    lib.jfa_workspace_bytes.restype = sz
+    lib.jfa_workspace_bytes.argtypes = [i64, i64, i32, i32, i32]
+    lib.jfa_last_error.restype = ctypes.c_char_p
+    lib.jfa_last_error.argtypes = []
+    lib.jfa_version.restype = i32
+    lib.jfa_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != JFA_OK:
+        raise JfaError(status, load().jfa_last_error().decode())
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _pick(dtype: torch.dtype, bf16_name: str):
+    lib = load()
+    if dtype == torch.bfloat16:
+        return getattr(lib, bf16_name)
+    if dtype == torch.float32:
+        return getattr(lib, bf16_name + "_f32")
+    raise TypeError(f"unsupported dtype {dtype}: bf16 or fp32")
+
+
+def jfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, offsets: torch.Tensor, max_len: int,
+                out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None
+                ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """out [sum_B, H, D] (dtype of q) and lse fp32 [H, sum_B]; dispatches on q.dtype (bf16 / fp32)."""
+    sum_B, H, D = q.shape
+    assert k.shape == q.shape and v.shape == q.shape and k.dtype == q.dtype and v.dtype == q.dtype
+    assert offsets.dtype == torch.int64 and offsets.is_cuda and offsets.dim() == 1
+    B = offsets.numel() - 1
+    if out is None:
+        out = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((H, sum_B), dtype=torch.float32, device=q.device)
+    fn = _pick(q.dtype, "jfa_forward")
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(offsets), B, max_len, H, D, _ptr(out), _ptr(lse), _stream()))
+    return out, lse
+
+
+def jfa_backward(q, k, v, out, dout, lse, offsets, max_len: int, dq=None, dk=None, dv=None, delta=None):
+    """dq, dk, dv [sum_B, H, D] (dtype of q) and delta fp32 [H, sum_B]."""
+    sum_B, H, D = q.shape
+    B = offsets.numel() - 1
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(q) if dk is None else dk
+    dv = torch.empty_like(q) if dv is None else dv
+    delta = torch.empty((H, sum_B), dtype=torch.float32, device=q.device) if delta is None else delta
+    fn = _pick(q.dtype, "jfa_backward")
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(dout), _ptr(lse), _ptr(offsets), B, max_len, H, D,
+              _ptr(dq), _ptr(dk), _ptr(dv), _ptr(delta), _stream()))
+    return dq, dk, dv, delta
+
+
+def jfa_build_schedule(offsets: torch.Tensor, block_rows: int):
+    """(order int32 [B], tile_start int32 [B+1]) as computed on the device."""
+    B = offsets.numel() - 1
+    order = torch.empty((max(B, 1),), dtype=torch.int32, device=offsets.device)
+    tile_start = torch.empty((B + 1,), dtype=torch.int32, device=offsets.device)
+    _check(load().jfa_build_schedule(_ptr(offsets), B, block_rows, _ptr(order), _ptr(tile_start), _stream()))
+    return order[:B], tile_start
+
+
+def jfa_check_offsets(offsets: torch.Tensor, max_len: int) -> int:
+    flags = ctypes.c_int(-1)
+    _check(load().jfa_check_offsets(_ptr(offsets), offsets.numel() - 1, max_len, _stream(), ctypes.byref(flags)))
+    return flags.value
+
+
+def jfa_workspace_bytes(B: int, max_len: int, H: int, D: int, backward: bool = False) -> int:
+    return int(load().jfa_workspace_bytes(B, max_len, H, D, 1 if backward else 0))
+
+
+def jfa_version() -> int:
+    return int(load().jfa_version())
+
+
+def jfa_last_error() -> str:
+    return load().jfa_last_error().decode()

@@ -1,0 +1,221 @@
+// extern "C" entry points of libjfa.so: argument validation, the private work table and the
+// sequence of kernel launches of each call.  See include/jfa.h for the contract.
+#include <map>
+#include <mutex>
+#include <stdarg.h>
+#include <stdio.h>
+#include <utility>
+
+#include "../../include/jfa.h"
+#include "jfa_common.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(jfa_status st, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return (int)st;
+}
+
+// ---- private work table: [kNumCounters counters][2 x (order[B], tile_start[B+1])] per (device, stream) ----
+struct Table {
+    char *base = nullptr;
+    size_t bytes = 0;
+};
+std::mutex g_mu;
+std::map<std::pair<int, hipStream_t>, Table> g_tables;
+std::map<int, int> g_cu_count;
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+size_t sched_bytes(int64_t B) { return align_up((size_t)(2 * B + 1) * sizeof(int32_t), 256); }
+size_t table_bytes(int64_t B) { return (size_t)jfa::kNumCounters * sizeof(int32_t) + 2 * sched_bytes(B); }
+
+struct Views {
+    int32_t *counters;
+    int32_t *order[2];
+    int32_t *tile_start[2];
+    int cus;
+};
+
+int get_table(int64_t B, hipStream_t stream, Views *v) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(JFA_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    std::lock_guard<std::mutex> lock(g_mu);
+    auto cu = g_cu_count.find(dev);
+    if (cu == g_cu_count.end()) {
+        int n = 0;
+        e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess || n <= 0) return fail(JFA_ERR_HIP, "cannot read the compute-unit count: %s", hipGetErrorString(e));
+        cu = g_cu_count.emplace(dev, n).first;
+    }
+    Table &t = g_tables[std::make_pair(dev, stream)];
+    const size_t need = table_bytes(B);
+    if (t.bytes < need) {
+        // Grow.  The old table may still be in use by work enqueued earlier on this stream.
+        if (t.base) {
+            e = hipStreamSynchronize(stream);
+            if (e != hipSuccess) return fail(JFA_ERR_HIP, "hipStreamSynchronize: %s", hipGetErrorString(e));
+            (void)hipFree(t.base);
+            t.base = nullptr;
+            t.bytes = 0;
+        }
+        void *p = nullptr;
+        e = hipMalloc(&p, need);
+        if (e != hipSuccess) return fail(JFA_ERR_ALLOC, "hipMalloc(%zu) for the work table: %s", need, hipGetErrorString(e));
+        t.base = (char *)p;
+        t.bytes = need;
+    }
+    // Views are laid out for the table's capacity in bytes, not for this call's B: recompute from B.
+    v->counters = (int32_t *)t.base;
+    char *p = t.base + (size_t)jfa::kNumCounters * sizeof(int32_t);
+    for (int i = 0; i < 2; ++i) {
+        v->order[i] = (int32_t *)p;
+        v->tile_start[i] = v->order[i] + B;
+        p += sched_bytes(B);
+    }
+    v->cus = cu->second;
+    return JFA_OK;
+}
+
+bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+
+int check_common(const char *fn, int64_t B, int64_t max_len, int H, int D, const void *const *ptrs, int n_ptrs) {
+    if (B < 0) return fail(JFA_ERR_INVALID_ARG, "%s: B = %lld is negative", fn, (long long)B);
+    if (max_len < 0) return fail(JFA_ERR_INVALID_ARG, "%s: max_len = %lld is negative", fn, (long long)max_len);
+    if (H <= 0) return fail(JFA_ERR_INVALID_ARG, "%s: H = %d must be positive", fn, H);
+    if (D != 32 && D != 64 && D != 128) return fail(JFA_ERR_UNSUPPORTED, "%s: D = %d is not one of 32, 64, 128", fn, D);
+    if (B >= (int64_t)1 << 30) return fail(JFA_ERR_UNSUPPORTED, "%s: B = %lld is too large", fn, (long long)B);
+    if (B == 0) return JFA_OK;
+    for (int i = 0; i < n_ptrs; ++i) {
+        if (!ptrs[i]) return fail(JFA_ERR_INVALID_ARG, "%s: pointer argument %d is null", fn, i);
+        if (misaligned(ptrs[i])) return fail(JFA_ERR_INVALID_ARG, "%s: pointer argument %d is not 16-byte aligned", fn, i);
+    }
+    return JFA_OK;
+}
+
+int hip_fail(const char *what, hipError_t e) { return fail(JFA_ERR_HIP, "%s: %s", what, hipGetErrorString(e)); }
+
+// Persistent grid: enough workgroups to fill every compute unit at the kernels' occupancy.
+int persistent_grid(int cus, int per_cu) { return cus * per_cu; }
+
+}  // namespace
+
+extern "C" {
+
+const char *jfa_last_error(void) { return g_err; }
+int jfa_version(void) { return 100; }
+
+size_t jfa_workspace_bytes(int64_t B, int64_t max_len, int H, int D, int pass) {
+    (void)max_len; (void)H; (void)D; (void)pass;
+    return B > 0 ? table_bytes(B) : 0;
+}
+
+int jfa_build_schedule(const int64_t *offsets, int64_t B, int block_rows, int32_t *order, int32_t *tile_start,
+                       void *stream) {
+    if (B < 0 || B >= (int64_t)1 << 30) return fail(JFA_ERR_INVALID_ARG, "jfa_build_schedule: bad B");
+    if (block_rows <= 0 || block_rows % 32) return fail(JFA_ERR_INVALID_ARG, "jfa_build_schedule: block_rows = %d must be a positive multiple of 32", block_rows);
+    if (!offsets || !tile_start || (B > 0 && !order)) return fail(JFA_ERR_INVALID_ARG, "jfa_build_schedule: null pointer");
+    Views v;
+    int st = get_table(B, (hipStream_t)stream, &v);
+    if (st != JFA_OK) return st;
+    hipError_t e = jfa::launch_schedule(offsets, (int)B, block_rows, order, tile_start, v.counters, jfa::kNumCounters, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail("schedule kernel", e);
+    return JFA_OK;
+}
+
+int jfa_check_offsets(const int64_t *offsets, int64_t B, int64_t max_len, void *stream, int *host_flags) {
+    if (!host_flags) return fail(JFA_ERR_INVALID_ARG, "jfa_check_offsets: host_flags is null");
+    if (B < 0 || B >= (int64_t)1 << 30) return fail(JFA_ERR_INVALID_ARG, "jfa_check_offsets: bad B");
+    if (!offsets) return fail(JFA_ERR_INVALID_ARG, "jfa_check_offsets: offsets is null");
+    Views v;
+    int st = get_table(B, (hipStream_t)stream, &v);
+    if (st != JFA_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    int *flag = v.counters + jfa::kNumCounters - 1;
+    hipError_t e = hipMemsetAsync(flag, 0, sizeof(int), s);
+    if (e != hipSuccess) return hip_fail("hipMemsetAsync", e);
+    e = jfa::launch_check_offsets(offsets, (int)B, max_len, flag, s);
+    if (e != hipSuccess) return hip_fail("check kernel", e);
+    e = hipMemcpyAsync(host_flags, flag, sizeof(int), hipMemcpyDeviceToHost, s);
+    if (e != hipSuccess) return hip_fail("hipMemcpyAsync", e);
+    e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return hip_fail("hipStreamSynchronize", e);
+    return JFA_OK;
+}
+
+int jfa_forward_f32(const float *q, const float *k, const float *v, const int64_t *offsets, int64_t B,
+                    int64_t max_len, int H, int D, float *out, float *lse, void *stream) {
+    const void *ptrs[] = {q, k, v, offsets, out, lse};
+    int st = check_common("jfa_forward_f32", B, max_len, H, D, ptrs, 6);
+    if (st != JFA_OK || B == 0) return st;
+    hipStream_t s = (hipStream_t)stream;
+    Views w;
+    if ((st = get_table(B, s, &w)) != JFA_OK) return st;
+    hipError_t e = jfa::launch_schedule(offsets, (int)B, jfa::kF32BlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s);
+    if (e != hipSuccess) return hip_fail("schedule kernel", e);
+    jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
+    e = jfa::launch_fwd_f32(q, k, v, offsets, (int)B, H, D, sc, out, lse, persistent_grid(w.cus, 2), s);
+    if (e != hipSuccess) return hip_fail("fp32 forward kernel", e);
+    return JFA_OK;
+}
+
+int jfa_backward_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
+                     const float *lse, const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, float *dq,
+                     float *dk, float *dv, float *delta, void *stream) {
+    const void *ptrs[] = {q, k, v, out, dout, lse, offsets, dq, dk, dv, delta};
+    int st = check_common("jfa_backward_f32", B, max_len, H, D, ptrs, 11);
+    if (st != JFA_OK || B == 0) return st;
+    hipStream_t s = (hipStream_t)stream;
+    Views w;
+    if ((st = get_table(B, s, &w)) != JFA_OK) return st;
+    hipError_t e = jfa::launch_schedule(offsets, (int)B, jfa::kF32BlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s);
+    if (e != hipSuccess) return hip_fail("schedule kernel", e);
+    jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
+    jfa::Schedule s_dkv{w.order[0], w.tile_start[0], w.counters + 1};
+    e = jfa::launch_bwd_f32(q, k, v, out, dout, lse, offsets, (int)B, H, D, s_dq, s_dkv, dq, dk, dv, delta, persistent_grid(w.cus, 2), s);
+    if (e != hipSuccess) return hip_fail("fp32 backward kernels", e);
+    return JFA_OK;
+}
+
+int jfa_forward(const void *q, const void *k, const void *v, const int64_t *offsets, int64_t B, int64_t max_len,
+                int H, int D, void *out, float *lse, void *stream) {
+    const void *ptrs[] = {q, k, v, offsets, out, lse};
+    int st = check_common("jfa_forward", B, max_len, H, D, ptrs, 6);
+    if (st != JFA_OK || B == 0) return st;
+    hipStream_t s = (hipStream_t)stream;
+    Views w;
+    if ((st = get_table(B, s, &w)) != JFA_OK) return st;
+    hipError_t e = jfa::launch_schedule(offsets, (int)B, jfa::kFwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s);
+    if (e != hipSuccess) return hip_fail("schedule kernel", e);
+    jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
+    e = jfa::launch_fwd_bf16(q, k, v, offsets, (int)B, H, D, sc, out, lse, persistent_grid(w.cus, 2), s);
+    if (e != hipSuccess) return hip_fail("bf16 forward kernel", e);
+    return JFA_OK;
+}
+
+int jfa_backward(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
+                 const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, void *dq, void *dk, void *dv,
+                 float *delta, void *stream) {
+    const void *ptrs[] = {q, k, v, out, dout, lse, offsets, dq, dk, dv, delta};
+    int st = check_common("jfa_backward", B, max_len, H, D, ptrs, 11);
+    if (st != JFA_OK || B == 0) return st;
+    hipStream_t s = (hipStream_t)stream;
+    Views w;
+    if ((st = get_table(B, s, &w)) != JFA_OK) return st;
+    hipError_t e = jfa::launch_schedule(offsets, (int)B, jfa::kBwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s);
+    if (e != hipSuccess) return hip_fail("schedule kernel", e);
+    e = jfa::launch_delta(out, dout, offsets, (int)B, H, D, true, delta, persistent_grid(w.cus, 8), s);
+    if (e != hipSuccess) return hip_fail("delta kernel", e);
+    jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
+    jfa::Schedule s_dkv{w.order[0], w.tile_start[0], w.counters + 1};
+    e = jfa::launch_bwd_bf16(q, k, v, dout, lse, delta, offsets, (int)B, H, D, s_dq, s_dkv, dq, dk, dv, persistent_grid(w.cus, 2), s);
+    if (e != hipSuccess) return hip_fail("bf16 backward kernels", e);
+    return JFA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,79 @@
+// Internal declarations shared by the HIP translation units of libjfa.so (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace jfa {
+
+// Number of int32 work counters at the head of the private work table.
+constexpr int kNumCounters = 64;
+// Histogram bins of the scheduler's counting sort (samples with >= kSchedBins-1 row blocks share the top bin).
+constexpr int kSchedBins = 1024;
+
+// Device view of one work schedule (see jfa_build_schedule in jfa.h for the meaning of the arrays).
+struct Schedule {
+    const int32_t *order;       // [B]
+    const int32_t *tile_start;  // [B+1]
+    int32_t *counter;           // one zeroed work counter, bumped by the persistent workgroups
+};
+
+// One decoded work item.
+struct Work {
+    int sample;   // sample id b
+    int head;     // head h
+    int block;    // row-block index inside the sample
+    int64_t row0; // offsets[b]
+    int len;      // L_b
+};
+
+// Largest p in [0, B) with tile_start[p] * H <= w, for w < tile_start[B] * H.
+__device__ inline int find_position(const int32_t *tile_start, int B, int H, int64_t w) {
+    int lo = 0, hi = B;  // invariant: tile_start[lo]*H <= w < tile_start[hi]*H
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if ((int64_t)tile_start[mid] * H <= w) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+__device__ inline Work decode_work(const Schedule &s, const int64_t *offsets, int B, int H, int64_t w) {
+    Work t;
+    const int p = find_position(s.tile_start, B, H, w);
+    const int t0 = s.tile_start[p];
+    const int n = s.tile_start[p + 1] - t0;
+    const int r = (int)(w - (int64_t)t0 * H);
+    t.sample = s.order[p];
+    t.head = r / n;
+    t.block = r - t.head * n;
+    t.row0 = offsets[t.sample];
+    t.len = (int)(offsets[t.sample + 1] - t.row0);
+    return t;
+}
+
+// ---- launchers (each enqueues on `stream` and returns the launch status) ----
+
+// Scheduler: fills order / tile_start for the given row-block size and zeroes `n_counters` counters.
+hipError_t launch_schedule(const int64_t *offsets, int B, int block_rows, int32_t *order, int32_t *tile_start,
+                           int32_t *counters, int n_counters, hipStream_t stream);
+hipError_t launch_check_offsets(const int64_t *offsets, int B, int64_t max_len, int *flags, hipStream_t stream);
+
+constexpr int kF32BlockRows = 64;
+hipError_t launch_fwd_f32(const float *q, const float *k, const float *v, const int64_t *offsets, int B, int H, int D,
+                          Schedule s, float *out, float *lse, int grid, hipStream_t stream);
+hipError_t launch_bwd_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
+                          const float *lse, const int64_t *offsets, int B, int H, int D, Schedule s_dq,
+                          Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int grid,
+                          hipStream_t stream);
+// delta[h, row] = sum_d dout * out, for T = float or bf16 (is_bf16)
+hipError_t launch_delta(const void *out, const void *dout, const int64_t *offsets, int B, int H, int D, bool is_bf16,
+                        float *delta, int grid, hipStream_t stream);
+
+constexpr int kFwdBlockRows = 128;
+constexpr int kBwdBlockRows = 128;
+hipError_t launch_fwd_bf16(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H, int D,
+                           Schedule s, void *out, float *lse, int grid, hipStream_t stream);
+hipError_t launch_bwd_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
+                           const float *delta, const int64_t *offsets, int B, int H, int D, Schedule s_dq,
+                           Schedule s_dkv, void *dq, void *dk, void *dv, int grid, hipStream_t stream);
+
+}  // namespace jfa

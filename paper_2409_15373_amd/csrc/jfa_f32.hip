@@ -1,0 +1,292 @@
+// fp32 jagged attention, forward and backward, in plain FMA arithmetic (no matrix cores): the
+// small-tolerance path.  Same structure as the bf16 kernels -- persistent workgroups pull
+// (sample, head, row-block) tiles from the offsets-driven schedule, stream the sample's keys
+// through LDS and keep an online softmax in registers (paper Section 2.1) -- but one row is owned
+// by four neighbouring lanes, each holding every fourth element of the row.
+#include "jfa_common.h"
+
+namespace jfa {
+
+constexpr int kRows = kF32BlockRows;  // rows (queries or keys) per tile
+// streamed rows per LDS stage: two [cols][D] fp32 stages stay within 32 KB
+template <int D> constexpr int cols_for() { return 4096 / D < 64 ? 4096 / D : 64; }
+constexpr int kThreads = kRows * 4;
+
+__device__ inline float quad_sum(float x) {
+    x += __shfl_xor(x, 1, 64);
+    x += __shfl_xor(x, 2, 64);
+    return x;
+}
+
+// Copy `n` rows (row0 .. row0+n-1, head h) of a [*, H, D] fp32 tensor into LDS [n][D].
+template <int D>
+__device__ inline void stage_rows(float *dst, const float *__restrict__ src, int64_t row0, int n, int h, int H) {
+    constexpr int kVec = D / 4;
+    for (int i = threadIdx.x; i < n * kVec; i += kThreads) {
+        const int r = i / kVec, c = i - r * kVec;
+        const float4 x = *reinterpret_cast<const float4 *>(src + ((row0 + r) * H + h) * (int64_t)D + c * 4);
+        *reinterpret_cast<float4 *>(dst + r * D + c * 4) = x;
+    }
+}
+
+__device__ inline int fetch_work(int32_t *counter, int *slot) {
+    __syncthreads();
+    if (threadIdx.x == 0) *slot = atomicAdd(counter, 1);
+    __syncthreads();
+    return *slot;
+}
+
+template <int D>
+__global__ __launch_bounds__(kThreads) void fwd_f32_kernel(const float *__restrict__ q, const float *__restrict__ k,
+                                                           const float *__restrict__ v,
+                                                           const int64_t *__restrict__ offsets, int B, int H,
+                                                           Schedule s, float *__restrict__ out,
+                                                           float *__restrict__ lse) {
+    constexpr int kPer = D / 4;
+    constexpr int kCols = cols_for<D>();
+    __shared__ float Ks[kCols * D];
+    __shared__ float Vs[kCols * D];
+    __shared__ int slot;
+    const int r = threadIdx.x >> 2, c = threadIdx.x & 3;
+    const float scale = 1.0f / sqrtf((float)D);
+    const int64_t total = (int64_t)s.tile_start[B] * H;
+    const int64_t sum_B = offsets[B];
+
+    for (int64_t w = fetch_work(s.counter, &slot); w < total; w = fetch_work(s.counter, &slot)) {
+        const Work t = decode_work(s, offsets, B, H, w);
+        const int i = t.block * kRows + r;                    // query index inside the sample
+        const int iq = i < t.len ? i : t.len - 1;             // rows past the end recompute the last row
+        float qr[kPer], acc[kPer];
+        for (int e = 0; e < kPer; ++e) {
+            qr[e] = q[((t.row0 + iq) * H + t.head) * (int64_t)D + 4 * e + c];
+            acc[e] = 0.0f;
+        }
+        float m = -INFINITY, l = 0.0f;
+        for (int j0 = 0; j0 < t.len; j0 += kCols) {
+            const int n = t.len - j0 < kCols ? t.len - j0 : kCols;
+            __syncthreads();
+            stage_rows<D>(Ks, k, t.row0 + j0, n, t.head, H);
+            stage_rows<D>(Vs, v, t.row0 + j0, n, t.head, H);
+            __syncthreads();
+            for (int j = 0; j < n; ++j) {
+                float part = 0.0f;
+                for (int e = 0; e < kPer; ++e) part = fmaf(qr[e], Ks[j * D + 4 * e + c], part);
+                const float sc = quad_sum(part) * scale;
+                const float m_new = fmaxf(m, sc);
+                const float a = expf(m - m_new);              // exp(-inf) = 0 on the first key
+                const float p = expf(sc - m_new);
+                l = fmaf(l, a, p);
+                for (int e = 0; e < kPer; ++e) acc[e] = fmaf(acc[e], a, p * Vs[j * D + 4 * e + c]);
+                m = m_new;
+            }
+        }
+        if (i < t.len) {
+            const float inv = 1.0f / l;
+            for (int e = 0; e < kPer; ++e) out[((t.row0 + i) * H + t.head) * (int64_t)D + 4 * e + c] = acc[e] * inv;
+            if (c == 0) lse[(int64_t)t.head * sum_B + t.row0 + i] = m + logf(l);
+        }
+    }
+}
+
+// dQ: tile = 64 queries, stream the sample's keys.
+template <int D>
+__global__ __launch_bounds__(kThreads) void dq_f32_kernel(const float *__restrict__ q, const float *__restrict__ k,
+                                                          const float *__restrict__ v,
+                                                          const float *__restrict__ dout,
+                                                          const float *__restrict__ lse,
+                                                          const float *__restrict__ delta,
+                                                          const int64_t *__restrict__ offsets, int B, int H,
+                                                          Schedule s, float *__restrict__ dq) {
+    constexpr int kPer = D / 4;
+    constexpr int kCols = cols_for<D>();
+    __shared__ float Ks[kCols * D];
+    __shared__ float Vs[kCols * D];
+    __shared__ int slot;
+    const int r = threadIdx.x >> 2, c = threadIdx.x & 3;
+    const float scale = 1.0f / sqrtf((float)D);
+    const int64_t total = (int64_t)s.tile_start[B] * H;
+    const int64_t sum_B = offsets[B];
+
+    for (int64_t w = fetch_work(s.counter, &slot); w < total; w = fetch_work(s.counter, &slot)) {
+        const Work t = decode_work(s, offsets, B, H, w);
+        const int i = t.block * kRows + r;
+        const int iq = i < t.len ? i : t.len - 1;
+        float qr[kPer], dor[kPer], acc[kPer];
+        for (int e = 0; e < kPer; ++e) {
+            const int64_t idx = ((t.row0 + iq) * H + t.head) * (int64_t)D + 4 * e + c;
+            qr[e] = q[idx];
+            dor[e] = dout[idx];
+            acc[e] = 0.0f;
+        }
+        const float lse_i = lse[(int64_t)t.head * sum_B + t.row0 + iq];
+        const float delta_i = delta[(int64_t)t.head * sum_B + t.row0 + iq];
+        for (int j0 = 0; j0 < t.len; j0 += kCols) {
+            const int n = t.len - j0 < kCols ? t.len - j0 : kCols;
+            __syncthreads();
+            stage_rows<D>(Ks, k, t.row0 + j0, n, t.head, H);
+            stage_rows<D>(Vs, v, t.row0 + j0, n, t.head, H);
+            __syncthreads();
+            for (int j = 0; j < n; ++j) {
+                float ps = 0.0f, pd = 0.0f;
+                for (int e = 0; e < kPer; ++e) {
+                    ps = fmaf(qr[e], Ks[j * D + 4 * e + c], ps);
+                    pd = fmaf(dor[e], Vs[j * D + 4 * e + c], pd);
+                }
+                const float p = expf(quad_sum(ps) * scale - lse_i);
+                const float ds = p * (quad_sum(pd) - delta_i);
+                for (int e = 0; e < kPer; ++e) acc[e] = fmaf(ds, Ks[j * D + 4 * e + c], acc[e]);
+            }
+        }
+        if (i < t.len)
+            for (int e = 0; e < kPer; ++e) dq[((t.row0 + i) * H + t.head) * (int64_t)D + 4 * e + c] = acc[e] * scale;
+    }
+}
+
+// dK, dV: tile = 64 keys, stream the sample's queries (with their dO, lse, delta).
+template <int D>
+__global__ __launch_bounds__(kThreads) void dkv_f32_kernel(const float *__restrict__ q, const float *__restrict__ k,
+                                                           const float *__restrict__ v,
+                                                           const float *__restrict__ dout,
+                                                           const float *__restrict__ lse,
+                                                           const float *__restrict__ delta,
+                                                           const int64_t *__restrict__ offsets, int B, int H,
+                                                           Schedule s, float *__restrict__ dk,
+                                                           float *__restrict__ dv) {
+    constexpr int kPer = D / 4;
+    constexpr int kCols = cols_for<D>();
+    __shared__ float Qs[kCols * D];
+    __shared__ float Os[kCols * D];
+    __shared__ float lse_s[kCols];
+    __shared__ float delta_s[kCols];
+    __shared__ int slot;
+    const int r = threadIdx.x >> 2, c = threadIdx.x & 3;
+    const float scale = 1.0f / sqrtf((float)D);
+    const int64_t total = (int64_t)s.tile_start[B] * H;
+    const int64_t sum_B = offsets[B];
+
+    for (int64_t w = fetch_work(s.counter, &slot); w < total; w = fetch_work(s.counter, &slot)) {
+        const Work t = decode_work(s, offsets, B, H, w);
+        const int j = t.block * kRows + r;
+        const int jk = j < t.len ? j : t.len - 1;
+        float kr[kPer], vr[kPer], acck[kPer], accv[kPer];
+        for (int e = 0; e < kPer; ++e) {
+            const int64_t idx = ((t.row0 + jk) * H + t.head) * (int64_t)D + 4 * e + c;
+            kr[e] = k[idx];
+            vr[e] = v[idx];
+            acck[e] = 0.0f;
+            accv[e] = 0.0f;
+        }
+        for (int i0 = 0; i0 < t.len; i0 += kCols) {
+            const int n = t.len - i0 < kCols ? t.len - i0 : kCols;
+            __syncthreads();
+            stage_rows<D>(Qs, q, t.row0 + i0, n, t.head, H);
+            stage_rows<D>(Os, dout, t.row0 + i0, n, t.head, H);
+            if (threadIdx.x < n) {
+                lse_s[threadIdx.x] = lse[(int64_t)t.head * sum_B + t.row0 + i0 + threadIdx.x];
+                delta_s[threadIdx.x] = delta[(int64_t)t.head * sum_B + t.row0 + i0 + threadIdx.x];
+            }
+            __syncthreads();
+            for (int i = 0; i < n; ++i) {
+                float ps = 0.0f, pd = 0.0f;
+                for (int e = 0; e < kPer; ++e) {
+                    ps = fmaf(Qs[i * D + 4 * e + c], kr[e], ps);
+                    pd = fmaf(Os[i * D + 4 * e + c], vr[e], pd);
+                }
+                const float p = expf(quad_sum(ps) * scale - lse_s[i]);
+                const float ds = p * (quad_sum(pd) - delta_s[i]);
+                for (int e = 0; e < kPer; ++e) {
+                    accv[e] = fmaf(p, Os[i * D + 4 * e + c], accv[e]);
+                    acck[e] = fmaf(ds, Qs[i * D + 4 * e + c], acck[e]);
+                }
+            }
+        }
+        if (j < t.len)
+            for (int e = 0; e < kPer; ++e) {
+                const int64_t idx = ((t.row0 + j) * H + t.head) * (int64_t)D + 4 * e + c;
+                dk[idx] = acck[e] * scale;
+                dv[idx] = accv[e];
+            }
+    }
+}
+
+// delta[h, row] = sum_d dout[row, h, d] * out[row, h, d]; one group of D*sizeof(T)/16 lanes per (row, head).
+template <bool kBf16>
+__global__ __launch_bounds__(256) void delta_kernel(const void *__restrict__ out, const void *__restrict__ dout,
+                                                    const int64_t *__restrict__ offsets, int B, int H, int D,
+                                                    float *__restrict__ delta) {
+    const int64_t sum_B = offsets[B];
+    const int lanes = kBf16 ? D / 8 : D / 4;  // 16 bytes per lane; a power of two in [4, 32]
+    const int groups_per_block = 256 / lanes;
+    const int g = threadIdx.x / lanes, ln = threadIdx.x - g * lanes;
+    const int64_t n_pairs = sum_B * H;
+    for (int64_t pair = (int64_t)blockIdx.x * groups_per_block + g; pair < n_pairs;
+         pair += (int64_t)gridDim.x * groups_per_block) {
+        float acc = 0.0f;
+        if (kBf16) {
+            const uint4 a = reinterpret_cast<const uint4 *>(out)[pair * lanes + ln];
+            const uint4 b = reinterpret_cast<const uint4 *>(dout)[pair * lanes + ln];
+            const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+            for (int e = 0; e < 4; ++e) {
+                acc = fmaf(__uint_as_float(aw[e] << 16), __uint_as_float(bw[e] << 16), acc);
+                acc = fmaf(__uint_as_float(aw[e] & 0xffff0000u), __uint_as_float(bw[e] & 0xffff0000u), acc);
+            }
+        } else {
+            const float4 a = reinterpret_cast<const float4 *>(out)[pair * lanes + ln];
+            const float4 b = reinterpret_cast<const float4 *>(dout)[pair * lanes + ln];
+            acc = fmaf(a.x, b.x, fmaf(a.y, b.y, fmaf(a.z, b.z, a.w * b.w)));
+        }
+        for (int d = 1; d < lanes; d <<= 1) acc += __shfl_xor(acc, d, 64);
+        if (ln == 0) {
+            const int64_t row = pair / H;
+            const int h = (int)(pair - row * H);
+            delta[(int64_t)h * sum_B + row] = acc;
+        }
+    }
+}
+
+hipError_t launch_delta(const void *out, const void *dout, const int64_t *offsets, int B, int H, int D, bool is_bf16,
+                        float *delta, int grid, hipStream_t stream) {
+    if (is_bf16)
+        hipLaunchKernelGGL(delta_kernel<true>, dim3(grid), dim3(256), 0, stream, out, dout, offsets, B, H, D, delta);
+    else
+        hipLaunchKernelGGL(delta_kernel<false>, dim3(grid), dim3(256), 0, stream, out, dout, offsets, B, H, D, delta);
+    return hipGetLastError();
+}
+
+hipError_t launch_fwd_f32(const float *q, const float *k, const float *v, const int64_t *offsets, int B, int H, int D,
+                          Schedule s, float *out, float *lse, int grid, hipStream_t stream) {
+#define JFA_CASE(DD)                                                                                              \
+    case DD:                                                                                                      \
+        hipLaunchKernelGGL(fwd_f32_kernel<DD>, dim3(grid), dim3(kThreads), 0, stream, q, k, v, offsets, B, H, s, \
+                           out, lse);                                                                             \
+        break;
+    switch (D) {
+        JFA_CASE(32) JFA_CASE(64) JFA_CASE(128)
+        default: return hipErrorInvalidValue;
+    }
+#undef JFA_CASE
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
+                          const float *lse, const int64_t *offsets, int B, int H, int D, Schedule s_dq,
+                          Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int grid,
+                          hipStream_t stream) {
+    hipError_t e = launch_delta(out, dout, offsets, B, H, D, false, delta, grid, stream);
+    if (e != hipSuccess) return e;
+#define JFA_CASE(DD)                                                                                               \
+    case DD:                                                                                                       \
+        hipLaunchKernelGGL(dq_f32_kernel<DD>, dim3(grid), dim3(kThreads), 0, stream, q, k, v, dout, lse, delta,   \
+                           offsets, B, H, s_dq, dq);                                                               \
+        hipLaunchKernelGGL(dkv_f32_kernel<DD>, dim3(grid), dim3(kThreads), 0, stream, q, k, v, dout, lse, delta,  \
+                           offsets, B, H, s_dkv, dk, dv);                                                          \
+        break;
+    switch (D) {
+        JFA_CASE(32) JFA_CASE(64) JFA_CASE(128)
+        default: return hipErrorInvalidValue;
+    }
+#undef JFA_CASE
+    return hipGetLastError();
+}
+
+}  // namespace jfa

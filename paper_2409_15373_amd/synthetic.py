@@ -119,14 +119,27 @@ def lengths_for(recipe: str, B: int, max_len: int, rng: np.random.Generator) -> 
     return np.asarray(L, dtype=np.int64)
 
 
+_CHUNK = 1 << 20
+
+
 def _draw(rng: np.random.Generator, shape, sigma: float, dtype: str):
-    x = rng.standard_normal(size=shape, dtype=np.float32)
-    if sigma != 1.0:
-        x = (x * np.float32(sigma)).astype(np.float32)
-    if dtype == "bf16":
-        bits = round_to_bf16_bits(x)
-        return bf16_bits_to_f32(bits), bits
-    return x, None
+    """N(0, sigma^2) float32 draws; for bf16 also the rounded bit patterns.  Works through the tensor in
+    cache-sized chunks (the stream of draws is the same as one big call: samples are produced in order)."""
+    n = int(np.prod(shape))
+    x = np.empty(n, dtype=np.float32)
+    bits = np.empty(n, dtype=np.uint16) if dtype == "bf16" else None
+    sig = np.float32(sigma)
+    for a in range(0, n, _CHUNK):
+        c = x[a:a + _CHUNK]
+        rng.standard_normal(size=c.shape[0], dtype=np.float32, out=c)
+        if sigma != 1.0:
+            c *= sig
+        if bits is not None:
+            u = c.view(np.uint32)
+            u += ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)      # round to nearest even
+            bits[a:a + _CHUNK] = u >> np.uint32(16)
+            u &= np.uint32(0xFFFF0000)                                           # the bf16 value, widened
+    return x.reshape(shape), (bits.reshape(shape) if bits is not None else None)
 
 
 def make_custom(name: str, lengths, H: int, D: int, dtype: str = "bf16", sigma: float = 1.0,

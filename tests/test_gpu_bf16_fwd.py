@@ -1,0 +1,98 @@
+"""bf16 MFMA forward vs the fp64 oracle on the same seeded bf16 inputs.
+
+Gate (both must hold, per output tensor): max |gpu - oracle| <= 2e-2 and max |gpu - oracle| / max |oracle| <= 1e-2.
+Small cases are compared element by element; the full-size configurations are compared on sampled
+(sample, head) pairs the oracle can compute one by one (always including the longest and the shortest
+sample), plus properties that hold at any size: every valid row finite, guard rows untouched.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2409_15373_amd.synthetic import make_custom, make_workload
+from helpers import f64, gate_bf16, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_forward(w, pad_rows=2):
+    from paper_2409_15373_amd import binding
+    d = to_device(w, names=("q", "k", "v"), pad_rows=pad_rows)
+    n = w.sum_B
+    out = torch.full_like(d["q"], 777.0)
+    lse = torch.full((w.H, n), 777.0, dtype=torch.float32, device="cuda")
+    binding.jfa_forward(d["q"], d["k"], d["v"], d["offsets"], w.max_len, out=out, lse=lse)
+    torch.cuda.synchronize()
+    assert (out[n:] == 777.0).all(), "guard rows of out were written"
+    return out[:n], lse
+
+
+def sample_pairs(w, n_random, seed):
+    rng = np.random.default_rng(seed)
+    order = np.argsort(w.lengths)
+    picks = {(int(order[-1]), 0), (int(order[0]), w.H - 1), (int(order[len(order) // 2]), 0)}
+    while len(picks) < n_random + 3:
+        picks.add((int(rng.integers(0, w.B)), int(rng.integers(0, w.H))))
+    return sorted(picks)
+
+
+def compare_pairs(w, out, lse, ref_out, ref_lse, pairs):
+    rows = np.concatenate([np.arange(w.offsets[b], w.offsets[b + 1]) for b, _ in pairs])
+    heads = np.concatenate([np.full(int(w.lengths[b]), h) for b, h in pairs])
+    g_out = f64(out)[rows, heads]; r_out = ref_out[rows, heads]
+    g_lse = f64(lse)[heads, rows]; r_lse = ref_lse[heads, rows]
+    assert np.isfinite(r_out).all()
+    return gate_bf16("out", g_out, r_out), gate_bf16("lse", g_lse, r_lse)
+
+
+@pytest.mark.parametrize("D", [32, 64, 128])
+@pytest.mark.parametrize("H", [1, 3])
+def test_bf16_forward_small_ragged(oracle, D, H):
+    # several 128-query tiles and 64-key stages, ragged tails of every kind, zero-length and length-1 samples
+    w = make_custom("ragged", [300, 1, 0, 129, 128, 127, 64, 33, 257, 2, 65, 0], H, D, dtype="bf16", seed=100 + D + H, dout=False)
+    out, lse = gpu_forward(w)
+    ref_out, ref_lse = oracle.forward(w.q, w.k, w.v, w.offsets)
+    gate_bf16("out", f64(out), ref_out)
+    gate_bf16("lse", f64(lse), ref_lse)
+
+
+def test_bf16_forward_length_one_returns_v(oracle):
+    w = make_custom("ones", [1] * 37, 2, 64, dtype="bf16", seed=5, dout=False)
+    out, lse = gpu_forward(w)
+    np.testing.assert_array_equal(f64(out), w.v.astype(np.float64))            # exact: p = 1, one product, bf16 value
+
+
+def test_bf16_forward_large_scores_stay_finite(oracle):
+    w = make_custom("hot", [200, 70], 2, 128, dtype="bf16", sigma=4.0, seed=6, dout=False)   # |scores| up to ~ hundreds
+    out, lse = gpu_forward(w)
+    ref_out, ref_lse = oracle.forward(w.q, w.k, w.v, w.offsets)
+    assert np.isfinite(f64(out)).all()
+    # near-one-hot softmax: compare with the bf16 gate scaled to the output magnitude
+    gate_bf16("out", f64(out), ref_out, abs_tol=2e-2 * max(1.0, np.abs(ref_out).max()))
+    gate_bf16("lse", f64(lse), ref_lse, abs_tol=2e-2 * max(1.0, np.abs(ref_lse).max() / 4))
+
+
+def test_config2_full(oracle):
+    w = make_workload("c2_geom_bf16")
+    out, lse = gpu_forward(w)
+    ref_out, ref_lse = oracle.forward(w.q, w.k, w.v, w.offsets)
+    gate_bf16("out", f64(out), ref_out)
+    gate_bf16("lse", f64(lse), ref_lse)
+
+
+@pytest.mark.parametrize("name,n_random", [("c3_zipf_bf16", 24), ("c4_bimodal_bf16", 10), ("c5_uniform_bf16", 16)])
+def test_full_size_configs_on_sampled_pairs(oracle, name, n_random):
+    w = make_workload(name, with_dout=False)
+    out, lse = gpu_forward(w)
+    assert torch.isfinite(out.float()).all() and torch.isfinite(lse).all()
+    pairs = sample_pairs(w, n_random, seed=1)
+    ref_out, ref_lse = oracle.forward(w.q, w.k, w.v, w.offsets, pairs=pairs)
+    compare_pairs(w, out, lse, ref_out, ref_lse, pairs)
+
+
+def test_forward_is_deterministic_and_schedule_independent():
+    """Two runs give bit-identical results although tiles are handed out dynamically."""
+    w = make_workload("c2_geom_bf16")
+    a, la = gpu_forward(w)
+    b, lb = gpu_forward(w)
+    assert torch.equal(a, b) and torch.equal(la, lb)

@@ -1,0 +1,85 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, and rejects bad arguments
+before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2409_15373_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2409_15373_amd import build
+        build.build()
+    return binding.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "jfa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(jfa_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    from paper_2409_15373_amd import binding
+    names = declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_version_and_workspace_depend_on_B_only(lib):
+    from paper_2409_15373_amd import binding
+    assert binding.jfa_version() >= 100
+    a = binding.jfa_workspace_bytes(512, 4096, 8, 128)
+    assert a == binding.jfa_workspace_bytes(512, 1 << 20, 1, 32, backward=True)     # no max_len / H / D term
+    assert a <= 64 * 4 + 2 * (2 * 512 + 1) * 4 + 1024
+    assert binding.jfa_workspace_bytes(0, 10, 1, 32) == 0
+
+
+@pytest.mark.parametrize("fn", ["jfa_forward", "jfa_forward_f32"])
+def test_forward_argument_errors(lib, fn):
+    from paper_2409_15373_amd import binding
+    f = getattr(lib, fn)
+    assert f(None, None, None, None, -1, 8, 1, 32, None, None, None) == binding.JFA_ERR_INVALID_ARG
+    assert "negative" in binding.jfa_last_error()
+    assert f(None, None, None, None, 1, -8, 1, 32, None, None, None) == binding.JFA_ERR_INVALID_ARG
+    assert f(None, None, None, None, 1, 8, 0, 32, None, None, None) == binding.JFA_ERR_INVALID_ARG
+    assert f(None, None, None, None, 1, 8, 1, 48, None, None, None) == binding.JFA_ERR_UNSUPPORTED
+    assert "D = 48" in binding.jfa_last_error()
+    assert f(None, None, None, None, 1, 8, 1, 64, None, None, None) == binding.JFA_ERR_INVALID_ARG
+    assert "null" in binding.jfa_last_error()
+    assert f(16, 16, 16, 16, 1, 8, 1, 64, 16, 8, None) == binding.JFA_ERR_INVALID_ARG      # lse misaligned
+    assert "aligned" in binding.jfa_last_error()
+    assert f(None, None, None, None, 0, 8, 1, 64, None, None, None) == binding.JFA_OK        # B == 0: nothing to do
+
+
+@pytest.mark.parametrize("fn", ["jfa_backward", "jfa_backward_f32"])
+def test_backward_argument_errors(lib, fn):
+    from paper_2409_15373_amd import binding
+    f = getattr(lib, fn)
+    n = [None] * 7
+    assert f(*n, -1, 8, 1, 32, None, None, None, None, None) == binding.JFA_ERR_INVALID_ARG
+    assert f(*n, 1, 8, 1, 96, None, None, None, None, None) == binding.JFA_ERR_UNSUPPORTED
+    assert f(*n, 1, 8, 1, 128, None, None, None, None, None) == binding.JFA_ERR_INVALID_ARG
+    assert f(*n, 0, 8, 1, 128, None, None, None, None, None) == binding.JFA_OK
+
+
+def test_schedule_and_check_argument_errors(lib):
+    from paper_2409_15373_amd import binding
+    assert lib.jfa_build_schedule(None, 4, 128, None, None, None) == binding.JFA_ERR_INVALID_ARG
+    assert lib.jfa_build_schedule(16, 4, 100, 16, 16, None) == binding.JFA_ERR_INVALID_ARG
+    assert "multiple of 32" in binding.jfa_last_error()
+    assert lib.jfa_check_offsets(16, 4, 10, None, None) == binding.JFA_ERR_INVALID_ARG
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    from paper_2409_15373_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        binding.load()
