@@ -78,11 +78,11 @@ static void forward_one(const float *q, const float *k, const float *v, int64_t 
     scores_one(q, k, s, L, h, H, D, S, m, l);
     for (int64_t i = 0; i < L; ++i) {
         for (int64_t j = 0; j < L; ++j) S[i * L + j] = exp(S[i * L + j] - m[i]) / l[i];
-        for (int d = 0; d < D; ++d) {
-            double acc = 0.0;
-            for (int64_t j = 0; j < L; ++j) acc += S[i * L + j] * (double)v[at(s + j, h, d, H, D)];
-            out[at(s + i, h, d, H, D)] = acc;
-        }
+        /* O_i = sum_j P_ij V_j, accumulated row by row of V (unit-stride inner loop) */
+        double *o = &out[at(s + i, h, 0, H, D)];
+        for (int d = 0; d < D; ++d) o[d] = 0.0;
+        for (int64_t j = 0; j < L; ++j)
+            for (int d = 0; d < D; ++d) o[d] += S[i * L + j] * (double)v[at(s + j, h, d, H, D)];
         lse[(size_t)h * (size_t)sum_B + (size_t)(s + i)] = m[i] + log(l[i]);
     }
     if (probs) memcpy(probs, S, sizeof(double) * (size_t)L * (size_t)L);
@@ -101,44 +101,47 @@ static void backward_one(const float *q, const float *k, const float *v, const f
     scores_one(q, k, s, L, h, H, D, P, m, l);
     for (int64_t i = 0; i < L; ++i)
         for (int64_t j = 0; j < L; ++j) P[i * L + j] = exp(P[i * L + j] - m[i]) / l[i];
-    /* delta_i = dO_i . O_i with O_i = sum_j P_ij V_j */
-    for (int64_t i = 0; i < L; ++i) {
-        double acc = 0.0;
+    /* All sums below run with the feature index d innermost (unit stride); the gradient rows of this
+       (sample, head) are zeroed first and then accumulated term by term. */
+    for (int64_t i = 0; i < L; ++i)
         for (int d = 0; d < D; ++d) {
-            double o = 0.0;
-            for (int64_t j = 0; j < L; ++j) o += P[i * L + j] * (double)v[at(s + j, h, d, H, D)];
-            acc += (double)dout[at(s + i, h, d, H, D)] * o;
+            dq[at(s + i, h, d, H, D)] = 0.0;
+            dk[at(s + i, h, d, H, D)] = 0.0;
+            dv[at(s + i, h, d, H, D)] = 0.0;
         }
+    double *o = (double *)malloc(sizeof(double) * (size_t)D);
+    for (int64_t i = 0; i < L; ++i) {
+        /* delta_i = dO_i . O_i with O_i = sum_j P_ij V_j */
+        for (int d = 0; d < D; ++d) o[d] = 0.0;
+        for (int64_t j = 0; j < L; ++j)
+            for (int d = 0; d < D; ++d) o[d] += P[i * L + j] * (double)v[at(s + j, h, d, H, D)];
+        double acc = 0.0;
+        for (int d = 0; d < D; ++d) acc += (double)dout[at(s + i, h, d, H, D)] * o[d];
         dl[i] = acc;
         if (delta) delta[(size_t)h * (size_t)sum_B + (size_t)(s + i)] = acc;
     }
-    /* dV_jd = sum_i P_ij dO_id */
-    for (int64_t j = 0; j < L; ++j)
-        for (int d = 0; d < D; ++d) {
-            double acc = 0.0;
-            for (int64_t i = 0; i < L; ++i) acc += P[i * L + j] * (double)dout[at(s + i, h, d, H, D)];
-            dv[at(s + j, h, d, H, D)] = acc;
-        }
-    /* dS_ij = P_ij (dP_ij - delta_i), dP_ij = dO_i . V_j ; overwrite P with dS */
+    free(o);
     for (int64_t i = 0; i < L; ++i)
         for (int64_t j = 0; j < L; ++j) {
+            const double p = P[i * L + j];
+            /* dV_jd += P_ij dO_id ;  dP_ij = dO_i . V_j */
             double dp = 0.0;
-            for (int d = 0; d < D; ++d)
+            for (int d = 0; d < D; ++d) {
+                dv[at(s + j, h, d, H, D)] += p * (double)dout[at(s + i, h, d, H, D)];
                 dp += (double)dout[at(s + i, h, d, H, D)] * (double)v[at(s + j, h, d, H, D)];
-            P[i * L + j] = P[i * L + j] * (dp - dl[i]);
+            }
+            /* dS_ij = P_ij (dP_ij - delta_i) ;  dQ_id += dS_ij K_jd ;  dK_jd += dS_ij Q_id */
+            const double ds = p * (dp - dl[i]);
+            for (int d = 0; d < D; ++d) {
+                dq[at(s + i, h, d, H, D)] += ds * (double)k[at(s + j, h, d, H, D)];
+                dk[at(s + j, h, d, H, D)] += ds * (double)q[at(s + i, h, d, H, D)];
+            }
         }
-    /* dQ_id = scale sum_j dS_ij K_jd ; dK_jd = scale sum_i dS_ij Q_id */
+    /* the 1/sqrt(D) of the scaled scores */
     for (int64_t i = 0; i < L; ++i)
         for (int d = 0; d < D; ++d) {
-            double acc = 0.0;
-            for (int64_t j = 0; j < L; ++j) acc += P[i * L + j] * (double)k[at(s + j, h, d, H, D)];
-            dq[at(s + i, h, d, H, D)] = acc * inv_sqrt_d;
-        }
-    for (int64_t j = 0; j < L; ++j)
-        for (int d = 0; d < D; ++d) {
-            double acc = 0.0;
-            for (int64_t i = 0; i < L; ++i) acc += P[i * L + j] * (double)q[at(s + i, h, d, H, D)];
-            dk[at(s + j, h, d, H, D)] = acc * inv_sqrt_d;
+            dq[at(s + i, h, d, H, D)] *= inv_sqrt_d;
+            dk[at(s + i, h, d, H, D)] *= inv_sqrt_d;
         }
     free(P); free(m); free(l); free(dl);
 }
