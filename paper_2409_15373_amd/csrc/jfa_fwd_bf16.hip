@@ -22,7 +22,7 @@ constexpr int kFwdThreads = 256;
 constexpr int kFwdBN = 64;  // keys per LDS stage
 
 template <int D>
-struct FwdSmem {
+struct alignas(16) FwdSmem {
     static constexpr int kStrideK = D * 2 + 16;  // bytes per K row: conflict-free 16-byte row reads
     static constexpr int kStrideV = D * 2 + 32;  // bytes per V row: conflict-free transposing reads
     char k[kFwdBN * kStrideK];

@@ -1,0 +1,77 @@
+"""bf16 MFMA backward vs the fp64 oracle on the same seeded bf16 inputs.
+
+The backward consumes the GPU forward's own out and lse (as a training step would).  Gates as in the
+forward test: per tensor, max |gpu - oracle| <= 2e-2 and max |gpu - oracle| / max |oracle| <= 1e-2.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2409_15373_amd.synthetic import make_custom, make_workload
+from helpers import f64, gate_bf16, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def gpu_forward_backward(w, pad_rows=2):
+    from paper_2409_15373_amd import binding
+    d = to_device(w, pad_rows=pad_rows)
+    n = w.sum_B
+    out = torch.full_like(d["q"], 777.0)
+    lse = torch.full((w.H, n), 777.0, dtype=torch.float32, device="cuda")
+    binding.jfa_forward(d["q"], d["k"], d["v"], d["offsets"], w.max_len, out=out, lse=lse)
+    g = {x: torch.full_like(d["q"], 777.0) for x in ("dq", "dk", "dv")}
+    delta = torch.full((w.H, n), 777.0, dtype=torch.float32, device="cuda")
+    binding.jfa_backward(d["q"], d["k"], d["v"], out, d["dout"], lse, d["offsets"], w.max_len,
+                         dq=g["dq"], dk=g["dk"], dv=g["dv"], delta=delta)
+    torch.cuda.synchronize()
+    for name, t in g.items():
+        assert (t[n:] == 777.0).all(), f"guard rows of {name} were written"
+    return g["dq"][:n], g["dk"][:n], g["dv"][:n], delta
+
+
+@pytest.mark.parametrize("D", [32, 64, 128])
+@pytest.mark.parametrize("H", [1, 3])
+def test_bf16_backward_small_ragged(oracle, D, H):
+    w = make_custom("ragged", [300, 1, 0, 129, 128, 127, 64, 33, 257, 2, 65, 0], H, D, dtype="bf16", seed=200 + D + H)
+    dq, dk, dv, delta = gpu_forward_backward(w)
+    rdq, rdk, rdv, rdelta = oracle.backward(w.q, w.k, w.v, w.dout, w.offsets)
+    gate_bf16("delta", f64(delta), rdelta, abs_tol=4e-2)       # |delta| reaches ~15: bf16 rounding of out dominates
+    gate_bf16("dq", f64(dq), rdq)
+    gate_bf16("dk", f64(dk), rdk)
+    gate_bf16("dv", f64(dv), rdv)
+
+
+def test_bf16_backward_length_one(oracle):
+    w = make_custom("ones", [1] * 21, 2, 64, dtype="bf16", seed=7)
+    dq, dk, dv, _ = gpu_forward_backward(w)
+    np.testing.assert_array_equal(f64(dv), w.dout.astype(np.float64))          # P = 1 exactly
+    assert np.abs(f64(dq)).max() <= 1e-2 and np.abs(f64(dk)).max() <= 1e-2     # dS = P (dP - delta) ~ 0
+
+
+def test_config5_backward_on_sampled_pairs(oracle):
+    w = make_workload("c5_uniform_bf16")
+    dq, dk, dv, delta = gpu_forward_backward(w)
+    for t in (dq, dk, dv):
+        assert torch.isfinite(t.float()).all()
+    order = np.argsort(w.lengths)
+    rng = np.random.default_rng(2)
+    pairs = {(int(order[-1]), 0), (int(order[0]), w.H - 1), (int(order[len(order) // 2]), 1)}
+    while len(pairs) < 16:
+        pairs.add((int(rng.integers(0, w.B)), int(rng.integers(0, w.H))))
+    pairs = sorted(pairs)
+    rdq, rdk, rdv, rdelta = oracle.backward(w.q, w.k, w.v, w.dout, w.offsets, pairs=pairs)
+    rows = np.concatenate([np.arange(w.offsets[b], w.offsets[b + 1]) for b, _ in pairs])
+    heads = np.concatenate([np.full(int(w.lengths[b]), h) for b, h in pairs])
+    gate_bf16("dq", f64(dq)[rows, heads], rdq[rows, heads])
+    gate_bf16("dk", f64(dk)[rows, heads], rdk[rows, heads])
+    gate_bf16("dv", f64(dv)[rows, heads], rdv[rows, heads])
+    gate_bf16("delta", f64(delta)[heads, rows], rdelta[heads, rows], abs_tol=4e-2)
+
+
+def test_backward_is_deterministic():
+    w = make_custom("det", [700, 90, 1, 333], 2, 128, dtype="bf16", seed=3)
+    a = gpu_forward_backward(w)
+    b = gpu_forward_backward(w)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
