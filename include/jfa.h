@@ -107,6 +107,17 @@ int jfa_check_offsets(const int64_t *offsets, int64_t B, int64_t max_len, void *
  */
 size_t jfa_workspace_bytes(int64_t B, int64_t max_len, int H, int D, int pass);
 
+/*
+ * Per-kernel timing, a benchmark aid (thread-local; do not use under stream capture).  While enabled,
+ * every call above brackets each kernel it enqueues with a pair of HIP events on the call's stream.
+ * jfa_timing_read waits for those events and reports, per distinct kernel name, the summed duration in
+ * milliseconds and the number of launches since the last read (or enable), then forgets them.
+ * names / total_ms / launches are host arrays of `capacity` entries; the return value is the number
+ * of entries filled, or a negative jfa_status.  The name strings are static.
+ */
+int jfa_timing_enable(int on);
+int jfa_timing_read(int capacity, const char **names, float *total_ms, int *launches);
+
 /* Description of the last failure on this thread (a static, thread-local string; never freed). */
 const char *jfa_last_error(void);
 

@@ -24,7 +24,8 @@ JFA_ERR_HIP = -4
 
 EXPORTS = (
     "jfa_forward", "jfa_forward_f32", "jfa_backward", "jfa_backward_f32", "jfa_build_schedule",
-    "jfa_check_offsets", "jfa_workspace_bytes", "jfa_last_error", "jfa_version",
+    "jfa_check_offsets", "jfa_workspace_bytes", "jfa_last_error", "jfa_version", "jfa_timing_enable",
+    "jfa_timing_read",
 )
 
 
@@ -62,6 +63,11 @@ def load() -> ctypes.CDLL:
     lib.jfa_last_error.argtypes = []
     lib.jfa_version.restype = i32
     lib.jfa_version.argtypes = []
+    lib.jfa_timing_enable.restype = i32
+    lib.jfa_timing_enable.argtypes = [i32]
+    lib.jfa_timing_read.restype = i32
+    lib.jfa_timing_read.argtypes = [i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float),
+                                    ctypes.POINTER(ctypes.c_int)]
     _lib = lib
     return lib
 
@@ -139,6 +145,21 @@ def jfa_check_offsets(offsets: torch.Tensor, max_len: int) -> int:
 
 def jfa_workspace_bytes(B: int, max_len: int, H: int, D: int, backward: bool = False) -> int:
     return int(load().jfa_workspace_bytes(B, max_len, H, D, 1 if backward else 0))
+
+
+def jfa_timing_enable(on: bool) -> None:
+    _check(load().jfa_timing_enable(1 if on else 0))
+
+
+def jfa_timing_read(capacity: int = 16):
+    """{kernel name: (total milliseconds, launches)} since the last read; waits for the recorded events."""
+    names = (ctypes.c_char_p * capacity)()
+    ms = (ctypes.c_float * capacity)()
+    cnt = (ctypes.c_int * capacity)()
+    n = load().jfa_timing_read(capacity, names, ms, cnt)
+    if n < 0:
+        _check(n)
+    return {names[i].decode(): (float(ms[i]), int(cnt[i])) for i in range(n)}
 
 
 def jfa_version() -> int:

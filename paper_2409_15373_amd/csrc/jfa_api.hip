@@ -4,7 +4,9 @@
 #include <mutex>
 #include <stdarg.h>
 #include <stdio.h>
+#include <string.h>
 #include <utility>
+#include <vector>
 
 #include "../../include/jfa.h"
 #include "jfa_common.h"
@@ -98,16 +100,72 @@ int check_common(const char *fn, int64_t B, int64_t max_len, int H, int D, const
     return JFA_OK;
 }
 
-int hip_fail(const char *what, hipError_t e) { return fail(JFA_ERR_HIP, "%s: %s", what, hipGetErrorString(e)); }
+// ---- optional per-kernel timing (see jfa_timing_enable) ----
+struct TimedLaunch {
+    const char *name;
+    hipEvent_t e0, e1;
+};
+thread_local bool g_timing = false;
+thread_local std::vector<TimedLaunch> g_timed;
 
-// Persistent grid: enough workgroups to fill every compute unit at the kernels' occupancy.
-int persistent_grid(int cus, int per_cu) { return cus * per_cu; }
+// Brackets one kernel launch with events when timing is on; a no-op otherwise.
+struct ScopedTimer {
+    TimedLaunch t{nullptr, nullptr, nullptr};
+    hipStream_t stream;
+    ScopedTimer(const char *name, hipStream_t s) : stream(s) {
+        if (!g_timing) return;
+        if (hipEventCreate(&t.e0) != hipSuccess) return;
+        if (hipEventCreate(&t.e1) != hipSuccess) { (void)hipEventDestroy(t.e0); return; }
+        t.name = name;
+        (void)hipEventRecord(t.e0, stream);
+    }
+    ~ScopedTimer() {
+        if (!t.name) return;
+        (void)hipEventRecord(t.e1, stream);
+        g_timed.push_back(t);
+    }
+};
+
+void drop_timed() {
+    for (auto &t : g_timed) { (void)hipEventDestroy(t.e0); (void)hipEventDestroy(t.e1); }
+    g_timed.clear();
+}
+
+int hip_fail(const char *what, hipError_t e) { return fail(JFA_ERR_HIP, "%s: %s", what, hipGetErrorString(e)); }
 
 }  // namespace
 
 extern "C" {
 
 const char *jfa_last_error(void) { return g_err; }
+
+int jfa_timing_enable(int on) {
+    drop_timed();
+    g_timing = on != 0;
+    return JFA_OK;
+}
+
+int jfa_timing_read(int capacity, const char **names, float *total_ms, int *launches) {
+    if (capacity < 0 || (capacity > 0 && (!names || !total_ms || !launches)))
+        return fail(JFA_ERR_INVALID_ARG, "jfa_timing_read: null output array");
+    int n = 0;
+    for (auto &t : g_timed) {
+        hipError_t e = hipEventSynchronize(t.e1);
+        float ms = 0.0f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, t.e0, t.e1);
+        if (e != hipSuccess) { drop_timed(); return hip_fail("timing events", e); }
+        int i = 0;
+        while (i < n && strcmp(names[i], t.name) != 0) ++i;
+        if (i == n) {
+            if (n == capacity) continue;
+            names[n] = t.name; total_ms[n] = 0.0f; launches[n] = 0; ++n;
+        }
+        total_ms[i] += ms;
+        launches[i] += 1;
+    }
+    drop_timed();
+    return n;
+}
 int jfa_version(void) { return 100; }
 
 size_t jfa_workspace_bytes(int64_t B, int64_t max_len, int H, int D, int pass) {
@@ -156,10 +214,11 @@ int jfa_forward_f32(const float *q, const float *k, const float *v, const int64_
     hipStream_t s = (hipStream_t)stream;
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
-    hipError_t e = jfa::launch_schedule(offsets, (int)B, jfa::kF32BlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s);
+    hipError_t e;
+    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, jfa::kF32BlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
-    e = jfa::launch_fwd_f32(q, k, v, offsets, (int)B, H, D, sc, out, lse, persistent_grid(w.cus, 2), s);
+    { ScopedTimer tm("fwd_f32", s); e = jfa::launch_fwd_f32(q, k, v, offsets, (int)B, H, D, sc, out, lse, w.cus, s); }
     if (e != hipSuccess) return hip_fail("fp32 forward kernel", e);
     return JFA_OK;
 }
@@ -173,11 +232,13 @@ int jfa_backward_f32(const float *q, const float *k, const float *v, const float
     hipStream_t s = (hipStream_t)stream;
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
-    hipError_t e = jfa::launch_schedule(offsets, (int)B, jfa::kF32BlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s);
+    hipError_t e;
+    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, jfa::kF32BlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
     jfa::Schedule s_dkv{w.order[0], w.tile_start[0], w.counters + 1};
-    e = jfa::launch_bwd_f32(q, k, v, out, dout, lse, offsets, (int)B, H, D, s_dq, s_dkv, dq, dk, dv, delta, persistent_grid(w.cus, 2), s);
+    ScopedTimer tm_bwd("bwd_f32", s);
+    e = jfa::launch_bwd_f32(q, k, v, out, dout, lse, offsets, (int)B, H, D, s_dq, s_dkv, dq, dk, dv, delta, w.cus, s);
     if (e != hipSuccess) return hip_fail("fp32 backward kernels", e);
     return JFA_OK;
 }
@@ -190,10 +251,11 @@ int jfa_forward(const void *q, const void *k, const void *v, const int64_t *offs
     hipStream_t s = (hipStream_t)stream;
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
-    hipError_t e = jfa::launch_schedule(offsets, (int)B, jfa::kFwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s);
+    hipError_t e;
+    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, jfa::kFwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
-    e = jfa::launch_fwd_bf16(q, k, v, offsets, (int)B, H, D, sc, out, lse, persistent_grid(w.cus, 2), s);
+    { ScopedTimer tm("fwd_bf16", s); e = jfa::launch_fwd_bf16(q, k, v, offsets, (int)B, H, D, sc, out, lse, w.cus, s); }
     if (e != hipSuccess) return hip_fail("bf16 forward kernel", e);
     return JFA_OK;
 }
@@ -207,14 +269,17 @@ int jfa_backward(const void *q, const void *k, const void *v, const void *out, c
     hipStream_t s = (hipStream_t)stream;
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
-    hipError_t e = jfa::launch_schedule(offsets, (int)B, jfa::kBwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s);
+    hipError_t e;
+    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, jfa::kBwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
-    e = jfa::launch_delta(out, dout, offsets, (int)B, H, D, true, delta, persistent_grid(w.cus, 8), s);
+    { ScopedTimer tm("delta", s); e = jfa::launch_delta(out, dout, offsets, (int)B, H, D, true, delta, w.cus, s); }
     if (e != hipSuccess) return hip_fail("delta kernel", e);
     jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
     jfa::Schedule s_dkv{w.order[0], w.tile_start[0], w.counters + 1};
-    e = jfa::launch_bwd_bf16(q, k, v, dout, lse, delta, offsets, (int)B, H, D, s_dq, s_dkv, dq, dk, dv, persistent_grid(w.cus, 2), s);
-    if (e != hipSuccess) return hip_fail("bf16 backward kernels", e);
+    { ScopedTimer tm("dkv_bf16", s); e = jfa::launch_dkv_bf16(q, k, v, dout, lse, delta, offsets, (int)B, H, D, s_dkv, dk, dv, w.cus, s); }
+    if (e != hipSuccess) return hip_fail("bf16 dK/dV kernel", e);
+    { ScopedTimer tm("dq_bf16", s); e = jfa::launch_dq_bf16(q, k, v, dout, lse, delta, offsets, (int)B, H, D, s_dq, dq, w.cus, s); }
+    if (e != hipSuccess) return hip_fail("bf16 dQ kernel", e);
     return JFA_OK;
 }
 

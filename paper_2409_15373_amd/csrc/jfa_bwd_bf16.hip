@@ -28,14 +28,14 @@ template <int D>
 struct Stage {
     static constexpr int kChunksPerRow = D / 8;
     static constexpr int kLoads = kBwdStage * kChunksPerRow / kBwdThreads;
-    uint4 regs[kLoads];
+    u32x4 regs[kLoads];
     __device__ inline void prefetch(const __bf16 *base, int64_t row_stride, int r0, int L) {
 #pragma unroll
         for (int u = 0; u < kLoads; ++u) {
             const int chunk = threadIdx.x + u * kBwdThreads;
             const int r = chunk / kChunksPerRow, cc = chunk % kChunksPerRow;
             const int j = r0 + r < L ? r0 + r : L - 1;  // rows past the end repeat the last row (masked by the caller)
-            regs[u] = *reinterpret_cast<const uint4 *>(base + j * row_stride + cc * 8);
+            regs[u] = *reinterpret_cast<const u32x4 *>(base + j * row_stride + cc * 8);
         }
     }
     __device__ inline void commit(char *lds, int stride) const {
@@ -43,7 +43,7 @@ struct Stage {
         for (int u = 0; u < kLoads; ++u) {
             const int chunk = threadIdx.x + u * kBwdThreads;
             const int r = chunk / kChunksPerRow, cc = chunk % kChunksPerRow;
-            *reinterpret_cast<uint4 *>(lds + r * stride + cc * 16) = regs[u];
+            *reinterpret_cast<u32x4 *>(lds + r * stride + cc * 16) = regs[u];
         }
     }
 };
@@ -300,17 +300,31 @@ __global__ __launch_bounds__(kBwdThreads, 1) void dkv_bf16_kernel(const __bf16 *
     }
 }
 
-hipError_t launch_bwd_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
-                           const float *delta, const int64_t *offsets, int B, int H, int D, Schedule s_dq,
-                           Schedule s_dkv, void *dq, void *dk, void *dv, int grid, hipStream_t stream) {
+hipError_t launch_dkv_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
+                           const float *delta, const int64_t *offsets, int B, int H, int D, Schedule s, void *dk,
+                           void *dv, int cus, hipStream_t stream) {
 #define JFA_CASE(DD)                                                                                             \
     case DD:                                                                                                     \
-        hipLaunchKernelGGL(dkv_bf16_kernel<DD>, dim3(grid), dim3(kBwdThreads), 0, stream, (const __bf16 *)q,     \
+        hipLaunchKernelGGL(dkv_bf16_kernel<DD>, dim3(persistent_grid<dkv_bf16_kernel<DD>>(kBwdThreads, cus)), dim3(kBwdThreads), 0, stream, (const __bf16 *)q,     \
                            (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, lse, delta, offsets, B, H, \
-                           s_dkv, (__bf16 *)dk, (__bf16 *)dv);                                                   \
-        hipLaunchKernelGGL(dq_bf16_kernel<DD>, dim3(grid), dim3(kBwdThreads), 0, stream, (const __bf16 *)q,      \
+                           s, (__bf16 *)dk, (__bf16 *)dv);                                                       \
+        break;
+    switch (D) {
+        JFA_CASE(32) JFA_CASE(64) JFA_CASE(128)
+        default: return hipErrorInvalidValue;
+    }
+#undef JFA_CASE
+    return hipGetLastError();
+}
+
+hipError_t launch_dq_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
+                          const float *delta, const int64_t *offsets, int B, int H, int D, Schedule s, void *dq,
+                          int cus, hipStream_t stream) {
+#define JFA_CASE(DD)                                                                                             \
+    case DD:                                                                                                     \
+        hipLaunchKernelGGL(dq_bf16_kernel<DD>, dim3(persistent_grid<dq_bf16_kernel<DD>>(kBwdThreads, cus)), dim3(kBwdThreads), 0, stream, (const __bf16 *)q,      \
                            (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, lse, delta, offsets, B, H, \
-                           s_dq, (__bf16 *)dq);                                                                  \
+                           s, (__bf16 *)dq);                                                                     \
         break;
     switch (D) {
         JFA_CASE(32) JFA_CASE(64) JFA_CASE(128)

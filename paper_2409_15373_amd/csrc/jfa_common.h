@@ -50,7 +50,20 @@ __device__ inline Work decode_work(const Schedule &s, const int64_t *offsets, in
     return t;
 }
 
-// ---- launchers (each enqueues on `stream` and returns the launch status) ----
+// Persistent-grid size for `kernel`: every compute unit filled to the kernel's occupancy, no more
+// (extra workgroups would only find the work counter exhausted).  Queried once per kernel.
+template <auto Kernel>
+inline int persistent_grid(int threads, int cus) {
+    static int per_cu = 0;  // one instance per kernel function
+    if (per_cu == 0) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, Kernel, threads, 0) != hipSuccess || n < 1) n = 1;
+        per_cu = n;
+    }
+    return cus * per_cu;
+}
+
+// ---- launchers (each enqueues on `stream` and returns the launch status; `cus` = compute units of the device) ----
 
 // Scheduler: fills order / tile_start for the given row-block size and zeroes `n_counters` counters.
 hipError_t launch_schedule(const int64_t *offsets, int B, int block_rows, int32_t *order, int32_t *tile_start,
@@ -59,21 +72,24 @@ hipError_t launch_check_offsets(const int64_t *offsets, int B, int64_t max_len, 
 
 constexpr int kF32BlockRows = 64;
 hipError_t launch_fwd_f32(const float *q, const float *k, const float *v, const int64_t *offsets, int B, int H, int D,
-                          Schedule s, float *out, float *lse, int grid, hipStream_t stream);
+                          Schedule s, float *out, float *lse, int cus, hipStream_t stream);
 hipError_t launch_bwd_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
                           const float *lse, const int64_t *offsets, int B, int H, int D, Schedule s_dq,
-                          Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int grid,
+                          Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int cus,
                           hipStream_t stream);
 // delta[h, row] = sum_d dout * out, for T = float or bf16 (is_bf16)
 hipError_t launch_delta(const void *out, const void *dout, const int64_t *offsets, int B, int H, int D, bool is_bf16,
-                        float *delta, int grid, hipStream_t stream);
+                        float *delta, int cus, hipStream_t stream);
 
 constexpr int kFwdBlockRows = 128;
 constexpr int kBwdBlockRows = 128;
 hipError_t launch_fwd_bf16(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H, int D,
-                           Schedule s, void *out, float *lse, int grid, hipStream_t stream);
-hipError_t launch_bwd_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
-                           const float *delta, const int64_t *offsets, int B, int H, int D, Schedule s_dq,
-                           Schedule s_dkv, void *dq, void *dk, void *dv, int grid, hipStream_t stream);
+                           Schedule s, void *out, float *lse, int cus, hipStream_t stream);
+hipError_t launch_dkv_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
+                           const float *delta, const int64_t *offsets, int B, int H, int D, Schedule s, void *dk,
+                           void *dv, int cus, hipStream_t stream);
+hipError_t launch_dq_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
+                          const float *delta, const int64_t *offsets, int B, int H, int D, Schedule s, void *dq,
+                          int cus, hipStream_t stream);
 
 }  // namespace jfa

@@ -245,7 +245,8 @@ __global__ __launch_bounds__(256) void delta_kernel(const void *__restrict__ out
 }
 
 hipError_t launch_delta(const void *out, const void *dout, const int64_t *offsets, int B, int H, int D, bool is_bf16,
-                        float *delta, int grid, hipStream_t stream) {
+                        float *delta, int cus, hipStream_t stream) {
+    const int grid = cus * 8;
     if (is_bf16)
         hipLaunchKernelGGL(delta_kernel<true>, dim3(grid), dim3(256), 0, stream, out, dout, offsets, B, H, D, delta);
     else
@@ -254,10 +255,10 @@ hipError_t launch_delta(const void *out, const void *dout, const int64_t *offset
 }
 
 hipError_t launch_fwd_f32(const float *q, const float *k, const float *v, const int64_t *offsets, int B, int H, int D,
-                          Schedule s, float *out, float *lse, int grid, hipStream_t stream) {
+                          Schedule s, float *out, float *lse, int cus, hipStream_t stream) {
 #define JFA_CASE(DD)                                                                                              \
     case DD:                                                                                                      \
-        hipLaunchKernelGGL(fwd_f32_kernel<DD>, dim3(grid), dim3(kThreads), 0, stream, q, k, v, offsets, B, H, s, \
+        hipLaunchKernelGGL(fwd_f32_kernel<DD>, dim3(persistent_grid<fwd_f32_kernel<DD>>(kThreads, cus)), dim3(kThreads), 0, stream, q, k, v, offsets, B, H, s, \
                            out, lse);                                                                             \
         break;
     switch (D) {
@@ -270,15 +271,15 @@ hipError_t launch_fwd_f32(const float *q, const float *k, const float *v, const 
 
 hipError_t launch_bwd_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
                           const float *lse, const int64_t *offsets, int B, int H, int D, Schedule s_dq,
-                          Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int grid,
+                          Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int cus,
                           hipStream_t stream) {
-    hipError_t e = launch_delta(out, dout, offsets, B, H, D, false, delta, grid, stream);
+    hipError_t e = launch_delta(out, dout, offsets, B, H, D, false, delta, cus, stream);
     if (e != hipSuccess) return e;
 #define JFA_CASE(DD)                                                                                               \
     case DD:                                                                                                       \
-        hipLaunchKernelGGL(dq_f32_kernel<DD>, dim3(grid), dim3(kThreads), 0, stream, q, k, v, dout, lse, delta,   \
+        hipLaunchKernelGGL(dq_f32_kernel<DD>, dim3(persistent_grid<dq_f32_kernel<DD>>(kThreads, cus)), dim3(kThreads), 0, stream, q, k, v, dout, lse, delta,   \
                            offsets, B, H, s_dq, dq);                                                               \
-        hipLaunchKernelGGL(dkv_f32_kernel<DD>, dim3(grid), dim3(kThreads), 0, stream, q, k, v, dout, lse, delta,  \
+        hipLaunchKernelGGL(dkv_f32_kernel<DD>, dim3(persistent_grid<dkv_f32_kernel<DD>>(kThreads, cus)), dim3(kThreads), 0, stream, q, k, v, dout, lse, delta,  \
                            offsets, B, H, s_dkv, dk, dv);                                                          \
         break;
     switch (D) {

@@ -81,15 +81,15 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
         float lsum = 0.0f;     // this lane's share of the running sum (keys held by this lane only)
 
         // ---- software pipeline: global -> registers for block jb+1 while block jb is computed ----
-        uint4 kpre[kLoads], vpre[kLoads];
+        u32x4 kpre[kLoads], vpre[kLoads];
         auto prefetch = [&](int j0) {
 #pragma unroll
             for (int u = 0; u < kLoads; ++u) {
                 const int chunk = tid + u * kFwdThreads;
                 const int r = chunk / kChunksPerRow, cc = chunk % kChunksPerRow;
                 const int j = j0 + r < L ? j0 + r : L - 1;          // tail rows repeat the last key (masked later)
-                kpre[u] = *reinterpret_cast<const uint4 *>(kbase + j * row_stride + cc * 8);
-                vpre[u] = *reinterpret_cast<const uint4 *>(vbase + j * row_stride + cc * 8);
+                kpre[u] = *reinterpret_cast<const u32x4 *>(kbase + j * row_stride + cc * 8);
+                vpre[u] = *reinterpret_cast<const u32x4 *>(vbase + j * row_stride + cc * 8);
             }
         };
         auto commit = [&]() {
@@ -97,8 +97,8 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
             for (int u = 0; u < kLoads; ++u) {
                 const int chunk = tid + u * kFwdThreads;
                 const int r = chunk / kChunksPerRow, cc = chunk % kChunksPerRow;
-                *reinterpret_cast<uint4 *>(sm.k + r * Smem::kStrideK + cc * 16) = kpre[u];
-                *reinterpret_cast<uint4 *>(sm.v + r * Smem::kStrideV + cc * 16) = vpre[u];
+                *reinterpret_cast<u32x4 *>(sm.k + r * Smem::kStrideK + cc * 16) = kpre[u];
+                *reinterpret_cast<u32x4 *>(sm.v + r * Smem::kStrideV + cc * 16) = vpre[u];
             }
         };
 
@@ -195,10 +195,10 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
 }
 
 hipError_t launch_fwd_bf16(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H, int D,
-                           Schedule s, void *out, float *lse, int grid, hipStream_t stream) {
+                           Schedule s, void *out, float *lse, int cus, hipStream_t stream) {
 #define JFA_CASE(DD)                                                                                         \
     case DD:                                                                                                 \
-        hipLaunchKernelGGL(fwd_bf16_kernel<DD>, dim3(grid), dim3(kFwdThreads), 0, stream, (const __bf16 *)q, \
+        hipLaunchKernelGGL(fwd_bf16_kernel<DD>, dim3(persistent_grid<fwd_bf16_kernel<DD>>(kFwdThreads, cus)), dim3(kFwdThreads), 0, stream, (const __bf16 *)q, \
                            (const __bf16 *)k, (const __bf16 *)v, offsets, B, H, s, (__bf16 *)out, lse);      \
         break;
     switch (D) {
