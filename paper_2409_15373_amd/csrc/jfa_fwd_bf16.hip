@@ -23,10 +23,13 @@ constexpr int kFwdBN = 64;  // keys per LDS stage
 
 template <int D>
 struct alignas(16) FwdSmem {
-    static constexpr int kStrideK = D * 2 + 16;  // bytes per K row: conflict-free 16-byte row reads
-    static constexpr int kStrideV = D * 2 + 32;  // bytes per V row: conflict-free transposing reads
-    char k[kFwdBN * kStrideK];
-    char v[kFwdBN * kStrideV];
+    // 64 banks x 4 bytes: 16 lanes x 16 bytes (one pass of a 16-byte read) are conflict-free when rows are
+    // 16 bytes apart modulo 256; 32 lanes x 8 bytes of the transposing read (4 rows x 64 bytes) are
+    // conflict-free when rows are 64 bytes apart modulo 256.
+    static constexpr int kStrideK = D * 2 + 16;
+    static constexpr int kStrideV = D * 2 + 64;
+    char k[2][kFwdBN * kStrideK];   // double buffered: stage jb lives in buffer jb % 2
+    char v[2][kFwdBN * kStrideV];
     int slot;
 };
 
@@ -47,9 +50,19 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
     const float c = 1.4426950408889634f / sqrtf((float)D);  // log2(e) / sqrt(D): exp(x / sqrt(D)) = exp2(c x)
+    // The running maximum is only raised when a block exceeds it by more than 2^8 in the exp2 domain;
+    // until then probabilities are taken relative to the stale maximum (at most 256, exact in fp32 and
+    // harmless in bf16), which keeps the rescaling of the accumulator off the common path.
+    const float tau = 8.0f / c;
     const int64_t total = (int64_t)s.tile_start[B] * H;
     const int64_t sum_B = offsets[B];
     const int64_t row_stride = (int64_t)H * D;    // elements between consecutive rows of one head
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+
+    // per-lane LDS offsets of the operand reads
+    const int koff = col * Smem::kStrideK + half * 16;                       // K row `col`, slots 8 half .. +7
+    const int voff = (half * 4 + ((lane & 15) >> 2)) * Smem::kStrideV        // V^T: key row inside a 16-key step
+                     + (((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;        //      feature column of this lane
 
     for (;;) {
         __syncthreads();
@@ -65,6 +78,7 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
         // ---- this lane's query row as B operands: Q[i][16 ks + 8 half .. +7] ----
         const int i = t.block * kFwdBlockRows + wave * 32 + col;   // query index inside the sample
         const int iq = i < L ? i : L - 1;                           // rows past the end recompute the last row
+        const bool wave_active = t.block * kFwdBlockRows + wave * 32 < L;
         bf16x8 qreg[kKSteps];
         {
             const __bf16 *qrow = q + (t.row0 + iq) * row_stride + (int64_t)t.head * D + 8 * half;
@@ -77,10 +91,10 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
         for (int db = 0; db < kDBlocks; ++db)
 #pragma unroll
             for (int e = 0; e < 16; ++e) o[db][e] = 0.0f;
-        float m = -INFINITY;   // running maximum of the raw (unscaled) scores of this lane's query
+        float m = -INFINITY;   // reference maximum (raw, unscaled scores) of this lane's query
         float lsum = 0.0f;     // this lane's share of the running sum (keys held by this lane only)
 
-        // ---- software pipeline: global -> registers for block jb+1 while block jb is computed ----
+        // ---- staging: global -> registers (in flight during the compute) -> the other LDS buffer ----
         u32x4 kpre[kLoads], vpre[kLoads];
         auto prefetch = [&](int j0) {
 #pragma unroll
@@ -92,86 +106,113 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
                 vpre[u] = *reinterpret_cast<const u32x4 *>(vbase + j * row_stride + cc * 8);
             }
         };
-        auto commit = [&]() {
+        auto commit = [&](int buf) {
 #pragma unroll
             for (int u = 0; u < kLoads; ++u) {
                 const int chunk = tid + u * kFwdThreads;
                 const int r = chunk / kChunksPerRow, cc = chunk % kChunksPerRow;
-                *reinterpret_cast<u32x4 *>(sm.k + r * Smem::kStrideK + cc * 16) = kpre[u];
-                *reinterpret_cast<u32x4 *>(sm.v + r * Smem::kStrideV + cc * 16) = vpre[u];
+                *reinterpret_cast<u32x4 *>(sm.k[buf] + r * Smem::kStrideK + cc * 16) = kpre[u];
+                *reinterpret_cast<u32x4 *>(sm.v[buf] + r * Smem::kStrideV + cc * 16) = vpre[u];
             }
         };
 
         prefetch(0);
-        for (int j0 = 0; j0 < L; j0 += kFwdBN) {
-            __syncthreads();          // every wave is done reading the previous stage
-            commit();
-            __syncthreads();
-            if (j0 + kFwdBN < L) prefetch(j0 + kFwdBN);
+        commit(0);
+        // Pin the completion of the Q loads here: left pending into the loop, their wait would be merged into
+        // every iteration and stall the first matrix products on the stage prefetch issued just before them.
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qreg[ks]));
+        __syncthreads();
+        int buf = 0;
+        for (int j0 = 0; j0 < L; j0 += kFwdBN, buf ^= 1) {
+            const bool more = j0 + kFwdBN < L;
+            if (more) prefetch(j0 + kFwdBN);
+            if (wave_active) {
+                const char *kt = sm.k[buf] + koff;
+                const char *vt = sm.v[buf] + voff;
 
-            // ---- S^T = K Q^T : two 32-key row blocks ----
-            f32x16 st[2];
+                // ---- S^T = K Q^T : two 32-key row blocks; operands of a block are fetched together ----
+                f32x16 st[2];
+                bf16x8 ka[kKSteps], kb[kKSteps];
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb) {
+                for (int ks = 0; ks < kKSteps; ++ks) ka[ks] = lds_read_b128(kt + ks * 32);
 #pragma unroll
-                for (int e = 0; e < 16; ++e) st[mb][e] = 0.0f;
-                const char *krow = sm.k + (mb * 32 + col) * Smem::kStrideK + half * 16;
+                for (int ks = 0; ks < kKSteps; ++ks) kb[ks] = lds_read_b128(kt + 32 * Smem::kStrideK + ks * 32);
 #pragma unroll
-                for (int ks = 0; ks < kKSteps; ++ks)
-                    st[mb] = mfma_32x32x16(lds_read_b128(krow + ks * 32), qreg[ks], st[mb]);
-            }
+                for (int e = 0; e < 16; ++e) { st[0][e] = 0.0f; st[1][e] = 0.0f; }
+#pragma unroll
+                for (int ks = 0; ks < kKSteps; ++ks) st[0] = mfma_32x32x16(ka[ks], qreg[ks], st[0]);
+#pragma unroll
+                for (int ks = 0; ks < kKSteps; ++ks) st[1] = mfma_32x32x16(kb[ks], qreg[ks], st[1]);
+                // issue order: the first block's operand reads, then one read of the second block behind each
+                // matrix product of the first, so that LDS latency hides under the matrix pipe
+                __builtin_amdgcn_sched_group_barrier(0x100, kKSteps, 0);
+#pragma unroll
+                for (int ks = 0; ks < kKSteps; ++ks) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, kKSteps, 0);
 
-            // ---- mask keys past the end of the sample (last block only) ----
-            if (j0 + kFwdBN > L) {
+                // ---- mask keys past the end of the sample (last block only) ----
+                if (j0 + kFwdBN > L) {
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e)
+                            if (j0 + mb * 32 + acc_row(e, half) >= L) st[mb][e] = -INFINITY;
+                }
+
+                // ---- online softmax for this lane's query ----
+                float mx = st[0][0];
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-                    for (int e = 0; e < 16; ++e)
-                        if (j0 + mb * 32 + acc_row(e, half) >= L) st[mb][e] = -INFINITY;
-            }
-
-            // ---- online softmax for this lane's query ----
-            float mx = st[0][0];
+                    for (int e = 0; e < 16; ++e) mx = fmaxf(mx, st[mb][e]);
+                mx = pair_max(mx);
+                if (__builtin_amdgcn_ballot_w64(mx > m + tau) != 0) {   // wave-uniform, rare after the first block
+                    const float m_new = fmaxf(m, mx);
+                    const float alpha = fast_exp2((m - m_new) * c);     // exp2(-inf) = 0 on the first block
+                    m = m_new;
+                    lsum *= alpha;
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
+                    for (int db = 0; db < kDBlocks; ++db)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) mx = fmaxf(mx, st[mb][e]);
-            mx = pair_max(mx);
-            const float m_new = fmaxf(m, mx);
-            const float alpha = fast_exp2((m - m_new) * c);   // exp2(-inf) = 0 on the first block
-            const float mc = m_new * c;
-            m = m_new;
-            float psum = 0.0f;
-#pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const float p = fast_exp2(fmaf(st[mb][e], c, -mc));
-                    st[mb][e] = p;
-                    psum += p;
+                        for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
                 }
-            lsum = fmaf(lsum, alpha, psum);
+                const float mc = m * c;
+                bf16x8 pb[4];
 #pragma unroll
-            for (int db = 0; db < kDBlocks; ++db)
+                for (int g = 0; g < 4; ++g) {
+                    u32x4 pw;
 #pragma unroll
-                for (int e = 0; e < 16; ++e) o[db][e] *= alpha;
+                    for (int e = 0; e < 4; ++e) {
+                        bf16x2 pr;
+                        pr[0] = (__bf16)fast_exp2(fmaf(st[g >> 1][8 * (g & 1) + 2 * e], c, -mc));
+                        pr[1] = (__bf16)fast_exp2(fmaf(st[g >> 1][8 * (g & 1) + 2 * e + 1], c, -mc));
+                        // row sum of the ROUNDED probabilities, the values the second product uses
+                        lsum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lsum, false);
+                        pw[e] = __builtin_bit_cast(uint32_t, pr);
+                    }
+                    pb[g] = __builtin_bit_cast(bf16x8, pw);
+                }
 
-            // ---- O^T += V^T P^T : contraction over the 64 keys in four steps of 16 ----
+                // ---- O^T += V^T P^T : contraction over the 64 keys in four steps of 16 ----
+                // slot e of step g is key 16 g + 8 (e / 4) + 4 half + e % 4
 #pragma unroll
-            for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-                for (int ts = 0; ts < 2; ++ts) {
-                    const bf16x8 pb = pack_bf16(st[mb], 8 * ts);
-                    // slot e of this lane is key 32 mb + 16 ts + 8 (e / 4) + 4 half + e % 4
-                    const int key0 = mb * 32 + ts * 16 + half * 4 + ((lane & 15) >> 2);
-                    const char *vrow = sm.v + key0 * Smem::kStrideV + (((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
+                for (int g = 0; g < 4; ++g) {
+                    bf16x8 va[kDBlocks];
 #pragma unroll
                     for (int db = 0; db < kDBlocks; ++db) {
-                        const bf16x4 lo = lds_read_tr16(vrow + db * 64);
-                        const bf16x4 hi = lds_read_tr16(vrow + db * 64 + 8 * Smem::kStrideV);
-                        o[db] = mfma_32x32x16(concat(lo, hi), pb, o[db]);
+                        const char *pv = vt + g * 16 * Smem::kStrideV + db * 64;
+                        va[db] = concat(lds_read_tr16(pv), lds_read_tr16(pv + 8 * Smem::kStrideV));
                     }
+#pragma unroll
+                    for (int db = 0; db < kDBlocks; ++db) o[db] = mfma_32x32x16(va[db], pb[g], o[db]);
                 }
+            }
+            if (more) commit(buf ^ 1);
+            __syncthreads();
         }
 
         // ---- epilogue: normalise, store this lane's query row and its log-sum-exp ----
