@@ -96,15 +96,32 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
 
         // ---- staging: global -> registers (in flight during the compute) -> the other LDS buffer ----
         u32x4 kpre[kLoads], vpre[kLoads];
+        // Each thread always fetches the same chunk of rows r0 + u * rows_per_pass of the stage, so its source
+        // pointers just advance by one stage per iteration; only a ragged last stage clamps its row indices.
+        constexpr int kRowsPerPass = kFwdThreads / kChunksPerRow;
+        const int my_r = tid / kChunksPerRow, my_cc = tid % kChunksPerRow;
+        const __bf16 *kptr = kbase + (int64_t)my_r * row_stride + my_cc * 8;
+        const __bf16 *vptr = vbase + (int64_t)my_r * row_stride + my_cc * 8;
+        const int64_t pass_stride = (int64_t)kRowsPerPass * row_stride;
+        const int64_t stage_stride = (int64_t)kFwdBN * row_stride;
         auto prefetch = [&](int j0) {
+            if (j0 + kFwdBN <= L) {
 #pragma unroll
-            for (int u = 0; u < kLoads; ++u) {
-                const int chunk = tid + u * kFwdThreads;
-                const int r = chunk / kChunksPerRow, cc = chunk % kChunksPerRow;
-                const int j = j0 + r < L ? j0 + r : L - 1;          // tail rows repeat the last key (masked later)
-                kpre[u] = *reinterpret_cast<const u32x4 *>(kbase + j * row_stride + cc * 8);
-                vpre[u] = *reinterpret_cast<const u32x4 *>(vbase + j * row_stride + cc * 8);
+                for (int u = 0; u < kLoads; ++u) {
+                    kpre[u] = *reinterpret_cast<const u32x4 *>(kptr + u * pass_stride);
+                    vpre[u] = *reinterpret_cast<const u32x4 *>(vptr + u * pass_stride);
+                }
+            } else {
+#pragma unroll
+                for (int u = 0; u < kLoads; ++u) {
+                    const int r = my_r + u * kRowsPerPass;
+                    const int j = j0 + r < L ? j0 + r : L - 1;      // tail rows repeat the last key (masked later)
+                    kpre[u] = *reinterpret_cast<const u32x4 *>(kbase + j * row_stride + my_cc * 8);
+                    vpre[u] = *reinterpret_cast<const u32x4 *>(vbase + j * row_stride + my_cc * 8);
+                }
             }
+            kptr += stage_stride;
+            vptr += stage_stride;
         };
         auto commit = [&](int buf) {
 #pragma unroll
