@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--workload", default="c4_bimodal_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--forward-only", action="store_true", help="time the forward call alone (diagnostic)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy kernel (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU by design (samples are independent and would shard with no exchange); "
@@ -77,6 +79,14 @@ def main():
         forward()
         if not args.forward_only:
             backward()
+
+    if args.calibrate_copy:
+        # a plain elementwise copy of known size: 2^28 fp32 read + 2^28 fp32 written = 1 GiB each way
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -130,7 +140,8 @@ def main():
         kernels[name] = kk
     dom = max((kname for kname in kernels if "achieved" in kernels[kname]), key=lambda kname: kernels[kname]["avg_us"])
     roofline = {"kernel": dom, "bound": "mfma", "achieved": kernels[dom]["achieved"], "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": kernels[dom]["frac"], "avg_us": kernels[dom]["avg_us"], "traffic": None}
+                "unit": "TFLOP/s", "frac": kernels[dom]["frac"], "avg_us": kernels[dom]["avg_us"],
+                "traffic": recorded_traffic(w.name, dom)}
 
     result = {
         "metric": "jagged attention useful TFLOP/s (forward + backward step, non-padded flops only)",
@@ -157,6 +168,20 @@ def main():
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, args.forward_only)
     print(json.dumps(result), flush=True)
+
+
+def recorded_traffic(workload, kernel):
+    """HBM bytes per launch (FETCH_SIZE + WRITE_SIZE, copy-calibrated) of `kernel`, as recorded from the rocprofv3
+    --pmc passes in profiles/<workload>_traffic.txt; None when no record exists for this kernel."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) >= 3 and f[0] == kernel:
+                return int(float(f[1]) + float(f[2]))
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(w, forward_only):
