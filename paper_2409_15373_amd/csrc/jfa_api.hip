@@ -236,7 +236,7 @@ int jfa_backward_f32(const float *q, const float *k, const float *v, const float
     { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, jfa::kF32BlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
-    jfa::Schedule s_dkv{w.order[0], w.tile_start[0], w.counters + 1};
+    jfa::Schedule s_dkv{w.order[0], w.tile_start[0], w.counters + jfa::kXcds};
     ScopedTimer tm_bwd("bwd_f32", s);
     e = jfa::launch_bwd_f32(q, k, v, out, dout, lse, offsets, (int)B, H, D, s_dq, s_dkv, dq, dk, dv, delta, w.cus, s);
     if (e != hipSuccess) return hip_fail("fp32 backward kernels", e);
@@ -275,7 +275,7 @@ int jfa_backward(const void *q, const void *k, const void *v, const void *out, c
     { ScopedTimer tm("delta", s); e = jfa::launch_delta(out, dout, offsets, (int)B, H, D, true, delta, w.cus, s); }
     if (e != hipSuccess) return hip_fail("delta kernel", e);
     jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
-    jfa::Schedule s_dkv{w.order[0], w.tile_start[0], w.counters + 1};
+    jfa::Schedule s_dkv{w.order[0], w.tile_start[0], w.counters + jfa::kXcds};
     { ScopedTimer tm("dkv_bf16", s); e = jfa::launch_dkv_bf16(q, k, v, dout, lse, delta, offsets, (int)B, H, D, s_dkv, dk, dv, w.cus, s); }
     if (e != hipSuccess) return hip_fail("bf16 dK/dV kernel", e);
     { ScopedTimer tm("dq_bf16", s); e = jfa::launch_dq_bf16(q, k, v, dout, lse, delta, offsets, (int)B, H, D, s_dq, dq, w.cus, s); }

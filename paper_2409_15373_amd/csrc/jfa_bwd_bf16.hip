@@ -55,7 +55,7 @@ struct alignas(16) BwdSmem {
     char b[kBwdStage * kStride];                // dq: V      dkv: dO
     float lse2[kBwdStage];                      // dkv only: lse * log2(e), +inf for rows past the end
     float delta[kBwdStage];                     // dkv only
-    int slot;
+    int64_t slot;
 };
 
 // Store a transposed accumulator (rows = features, column = this lane's row of the output tensor).
@@ -92,12 +92,13 @@ __global__ __launch_bounds__(kBwdThreads, 2) void dq_bf16_kernel(const __bf16 *_
     const int64_t sum_B = offsets[B];
     const int64_t row_stride = (int64_t)H * D;
 
+    WorkCursor cursor;
     for (;;) {
         __syncthreads();
-        if (tid == 0) sm.slot = atomicAdd(s.counter, 1);
+        if (tid == 0) sm.slot = next_work(s.counter, cursor, total);
         __syncthreads();
         const int64_t w = sm.slot;
-        if (w >= total) break;
+        if (w < 0) break;
         const Work t = decode_work(s, offsets, B, H, w);
         const int L = t.len;
         const __bf16 *kbase = k + t.row0 * row_stride + (int64_t)t.head * D;
@@ -197,12 +198,13 @@ __global__ __launch_bounds__(kBwdThreads, 1) void dkv_bf16_kernel(const __bf16 *
     const int64_t sum_B = offsets[B];
     const int64_t row_stride = (int64_t)H * D;
 
+    WorkCursor cursor;
     for (;;) {
         __syncthreads();
-        if (tid == 0) sm.slot = atomicAdd(s.counter, 1);
+        if (tid == 0) sm.slot = next_work(s.counter, cursor, total);
         __syncthreads();
         const int64_t w = sm.slot;
-        if (w >= total) break;
+        if (w < 0) break;
         const Work t = decode_work(s, offsets, B, H, w);
         const int L = t.len;
         const __bf16 *qbase = q + t.row0 * row_stride + (int64_t)t.head * D;

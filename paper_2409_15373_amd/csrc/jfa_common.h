@@ -14,8 +14,68 @@ constexpr int kSchedBins = 1024;
 struct Schedule {
     const int32_t *order;       // [B]
     const int32_t *tile_start;  // [B+1]
-    int32_t *counter;           // one zeroed work counter, bumped by the persistent workgroups
+    int32_t *counter;           // kXcds zeroed work counters (one queue per XCD), bumped by the persistent workgroups
 };
+
+// The chip has 8 accelerator dies (XCDs), each with its own L2, and workgroups are dealt to them round-robin
+// by workgroup id.  Work ids are cut into groups of kWorkGroup consecutive ids -- consecutive ids are row
+// blocks of the same (sample, head), which stream the same K/V -- and group g belongs to the queue of XCD
+// g % 8, so the blocks that share K/V run on the die whose L2 already holds it.  A workgroup drains its own
+// die's queue first and then helps the others, so the assumption about placement only affects locality.
+constexpr int kXcds = 8;
+constexpr int kWorkGroup = 32;
+
+// Work id of local index t of queue y.
+__device__ inline int64_t work_id(int y, int t) {
+    return ((int64_t)(t / kWorkGroup) * kXcds + y) * kWorkGroup + t % kWorkGroup;
+}
+
+// Per-workgroup claim state (kept by the one thread that claims).
+struct WorkCursor {
+    bool first = true;
+    bool home_done = false;
+};
+
+// Next work id for this workgroup, or -1 when nothing is left.  Called by one thread.
+//   * The first item is assigned statically (queue blockIdx % 8, local index blockIdx / 8): no memory traffic,
+//     and on problems smaller than the grid the surplus workgroups leave at once.
+//   * Further items of the home queue are claimed with one atomic add (local indices continue after the
+//     static ones, hence the gridDim / 8 base; the grid is a multiple of 8).
+//   * Once the home queue is empty the workgroup looks at all eight counters with plain loads and only
+//     spends an atomic on a queue that still shows work.
+__device__ inline int64_t next_work(int32_t *counters, WorkCursor &cur, int64_t total) {
+    const int home = blockIdx.x % kXcds;
+    const int base = gridDim.x / kXcds;
+    if (cur.first) {
+        cur.first = false;
+        const int64_t id = work_id(home, blockIdx.x / kXcds);
+        if (id < total) return id;
+        cur.home_done = true;  // ids grow with the local index: nothing later in this queue is valid either
+    }
+    if (!cur.home_done) {
+        const int64_t id = work_id(home, base + atomicAdd(&counters[home], 1));
+        if (id < total) return id;
+        cur.home_done = true;
+    }
+    for (;;) {
+        int seen[kXcds];  // all eight counters in one round of independent loads
+#pragma unroll
+        for (int y = 0; y < kXcds; ++y) seen[y] = __atomic_load_n(&counters[y], __ATOMIC_RELAXED);
+        bool any = false;
+#pragma unroll
+        for (int d = 1; d < kXcds; ++d) {
+            const int y = (home + d) % kXcds;
+            int c = 0;
+#pragma unroll
+            for (int z = 0; z < kXcds; ++z) c = z == y ? seen[z] : c;
+            if (work_id(y, base + c) >= total) continue;
+            any = true;
+            const int64_t id = work_id(y, base + atomicAdd(&counters[y], 1));
+            if (id < total) return id;
+        }
+        if (!any) return -1;  // counters only grow, so this loop ends
+    }
+}
 
 // One decoded work item.
 struct Work {
@@ -60,7 +120,8 @@ inline int persistent_grid(int threads, int cus) {
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, Kernel, threads, 0) != hipSuccess || n < 1) n = 1;
         per_cu = n;
     }
-    return cus * per_cu;
+    const int grid = cus * per_cu;
+    return (grid + kXcds - 1) / kXcds * kXcds;  // next_work() relies on a multiple of 8
 }
 
 // ---- launchers (each enqueues on `stream` and returns the launch status; `cus` = compute units of the device) ----

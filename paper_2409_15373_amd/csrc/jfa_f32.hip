@@ -29,9 +29,9 @@ __device__ inline void stage_rows(float *dst, const float *__restrict__ src, int
     }
 }
 
-__device__ inline int fetch_work(int32_t *counter, int *slot) {
+__device__ inline int64_t fetch_work(int32_t *counters, WorkCursor &probe, int64_t total, int64_t *slot) {
     __syncthreads();
-    if (threadIdx.x == 0) *slot = atomicAdd(counter, 1);
+    if (threadIdx.x == 0) *slot = next_work(counters, probe, total);
     __syncthreads();
     return *slot;
 }
@@ -46,13 +46,14 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(const float *__restri
     constexpr int kCols = cols_for<D>();
     __shared__ float Ks[kCols * D];
     __shared__ float Vs[kCols * D];
-    __shared__ int slot;
+    __shared__ int64_t slot;
+    WorkCursor probe;
     const int r = threadIdx.x >> 2, c = threadIdx.x & 3;
     const float scale = 1.0f / sqrtf((float)D);
     const int64_t total = (int64_t)s.tile_start[B] * H;
     const int64_t sum_B = offsets[B];
 
-    for (int64_t w = fetch_work(s.counter, &slot); w < total; w = fetch_work(s.counter, &slot)) {
+    for (int64_t w = fetch_work(s.counter, probe, total, &slot); w >= 0; w = fetch_work(s.counter, probe, total, &slot)) {
         const Work t = decode_work(s, offsets, B, H, w);
         const int i = t.block * kRows + r;                    // query index inside the sample
         const int iq = i < t.len ? i : t.len - 1;             // rows past the end recompute the last row
@@ -101,13 +102,14 @@ __global__ __launch_bounds__(kThreads) void dq_f32_kernel(const float *__restric
     constexpr int kCols = cols_for<D>();
     __shared__ float Ks[kCols * D];
     __shared__ float Vs[kCols * D];
-    __shared__ int slot;
+    __shared__ int64_t slot;
+    WorkCursor probe;
     const int r = threadIdx.x >> 2, c = threadIdx.x & 3;
     const float scale = 1.0f / sqrtf((float)D);
     const int64_t total = (int64_t)s.tile_start[B] * H;
     const int64_t sum_B = offsets[B];
 
-    for (int64_t w = fetch_work(s.counter, &slot); w < total; w = fetch_work(s.counter, &slot)) {
+    for (int64_t w = fetch_work(s.counter, probe, total, &slot); w >= 0; w = fetch_work(s.counter, probe, total, &slot)) {
         const Work t = decode_work(s, offsets, B, H, w);
         const int i = t.block * kRows + r;
         const int iq = i < t.len ? i : t.len - 1;
@@ -158,13 +160,14 @@ __global__ __launch_bounds__(kThreads) void dkv_f32_kernel(const float *__restri
     __shared__ float Os[kCols * D];
     __shared__ float lse_s[kCols];
     __shared__ float delta_s[kCols];
-    __shared__ int slot;
+    __shared__ int64_t slot;
+    WorkCursor probe;
     const int r = threadIdx.x >> 2, c = threadIdx.x & 3;
     const float scale = 1.0f / sqrtf((float)D);
     const int64_t total = (int64_t)s.tile_start[B] * H;
     const int64_t sum_B = offsets[B];
 
-    for (int64_t w = fetch_work(s.counter, &slot); w < total; w = fetch_work(s.counter, &slot)) {
+    for (int64_t w = fetch_work(s.counter, probe, total, &slot); w >= 0; w = fetch_work(s.counter, probe, total, &slot)) {
         const Work t = decode_work(s, offsets, B, H, w);
         const int j = t.block * kRows + r;
         const int jk = j < t.len ? j : t.len - 1;

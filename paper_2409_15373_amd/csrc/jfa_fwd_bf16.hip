@@ -30,7 +30,7 @@ struct alignas(16) FwdSmem {
     static constexpr int kStrideV = D * 2 + 64;
     char k[2][kFwdBN * kStrideK];   // double buffered: stage jb lives in buffer jb % 2
     char v[2][kFwdBN * kStrideV];
-    int slot;
+    int64_t slot;
 };
 
 template <int D>
@@ -64,12 +64,13 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
     const int voff = (half * 4 + ((lane & 15) >> 2)) * Smem::kStrideV        // V^T: key row inside a 16-key step
                      + (((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;        //      feature column of this lane
 
+    WorkCursor cursor;
     for (;;) {
         __syncthreads();
-        if (tid == 0) sm.slot = atomicAdd(s.counter, 1);
+        if (tid == 0) sm.slot = next_work(s.counter, cursor, total);
         __syncthreads();
         const int64_t w = sm.slot;
-        if (w >= total) break;
+        if (w < 0) break;
         const Work t = decode_work(s, offsets, B, H, w);
         const int L = t.len;
         const __bf16 *kbase = k + t.row0 * row_stride + (int64_t)t.head * D;
