@@ -4,6 +4,7 @@
 #include <mutex>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 #include <utility>
 #include <vector>
@@ -131,6 +132,19 @@ void drop_timed() {
     g_timed.clear();
 }
 
+// Forward variant: the wide kernel (256-query tiles, one wave per SIMD) pays off on long samples.
+// JFA_FWD_VARIANT=wide|narrow overrides the choice (for experiments).
+bool use_wide_forward(int64_t max_len) {
+    static const int forced = [] {
+        const char *v = getenv("JFA_FWD_VARIANT");
+        if (v && !strcmp(v, "wide")) return 1;
+        if (v && !strcmp(v, "narrow")) return 0;
+        return -1;
+    }();
+    if (forced >= 0) return forced == 1;
+    return max_len >= 2048;
+}
+
 int hip_fail(const char *what, hipError_t e) { return fail(JFA_ERR_HIP, "%s: %s", what, hipGetErrorString(e)); }
 
 }  // namespace
@@ -252,10 +266,12 @@ int jfa_forward(const void *q, const void *k, const void *v, const int64_t *offs
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
-    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, jfa::kFwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
+    const bool wide = use_wide_forward(max_len);
+    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, wide ? jfa::kFwdWideBlockRows : jfa::kFwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
-    { ScopedTimer tm("fwd_bf16", s); e = jfa::launch_fwd_bf16(q, k, v, offsets, (int)B, H, D, sc, out, lse, w.cus, s); }
+    if (wide) { ScopedTimer tm("fwd_bf16_wide", s); e = jfa::launch_fwd_bf16_wide(q, k, v, offsets, (int)B, H, D, sc, out, lse, w.cus, s); }
+    else { ScopedTimer tm("fwd_bf16", s); e = jfa::launch_fwd_bf16(q, k, v, offsets, (int)B, H, D, sc, out, lse, w.cus, s); }
     if (e != hipSuccess) return hip_fail("bf16 forward kernel", e);
     return JFA_OK;
 }

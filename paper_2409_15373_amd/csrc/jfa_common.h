@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 namespace jfa {
 
@@ -143,6 +144,9 @@ hipError_t launch_delta(const void *out, const void *dout, const int64_t *offset
                         float *delta, int cus, hipStream_t stream);
 
 constexpr int kFwdBlockRows = 128;
+constexpr int kFwdWideBlockRows = 256;
+hipError_t launch_fwd_bf16_wide(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H,
+                                int D, Schedule s, void *out, float *lse, int cus, hipStream_t stream);
 constexpr int kBwdBlockRows = 128;
 hipError_t launch_fwd_bf16(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H, int D,
                            Schedule s, void *out, float *lse, int cus, hipStream_t stream);
