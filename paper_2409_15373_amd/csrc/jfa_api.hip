@@ -132,8 +132,7 @@ void drop_timed() {
     g_timed.clear();
 }
 
-// Forward variant: the wide kernel (256-query tiles, one wave per SIMD) pays off on long samples.
-// JFA_FWD_VARIANT=wide|narrow overrides the choice (for experiments).
+// Forward variant: JFA_FWD_VARIANT=wide selects the experimental 64-queries-per-wave kernel (D = 128 only).
 bool use_wide_forward(int64_t max_len) {
     static const int forced = [] {
         const char *v = getenv("JFA_FWD_VARIANT");
@@ -142,7 +141,8 @@ bool use_wide_forward(int64_t max_len) {
         return -1;
     }();
     if (forced >= 0) return forced == 1;
-    return max_len >= 2048;
+    (void)max_len;
+    return false;   // measured slower than the 32-query kernel so far (one wave per SIMD exposes every latency)
 }
 
 int hip_fail(const char *what, hipError_t e) { return fail(JFA_ERR_HIP, "%s: %s", what, hipGetErrorString(e)); }
@@ -266,7 +266,7 @@ int jfa_forward(const void *q, const void *k, const void *v, const int64_t *offs
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
-    const bool wide = use_wide_forward(max_len);
+    const bool wide = D == 128 && use_wide_forward(max_len);
     { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, wide ? jfa::kFwdWideBlockRows : jfa::kFwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};

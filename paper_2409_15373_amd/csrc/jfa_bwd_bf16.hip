@@ -97,7 +97,7 @@ __global__ __launch_bounds__(kBwdThreads, 2) void dq_bf16_kernel(const __bf16 *_
         __syncthreads();
         if (tid == 0) sm.slot = next_work(s.counter, cursor, total);
         __syncthreads();
-        const int64_t w = sm.slot;
+        const int64_t w = uniform64(sm.slot);
         if (w < 0) break;
         const Work t = decode_work(s, offsets, B, H, w);
         const int L = t.len;
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(kBwdThreads, 1) void dkv_bf16_kernel(const __bf16 *
         __syncthreads();
         if (tid == 0) sm.slot = next_work(s.counter, cursor, total);
         __syncthreads();
-        const int64_t w = sm.slot;
+        const int64_t w = uniform64(sm.slot);
         if (w < 0) break;
         const Work t = decode_work(s, offsets, B, H, w);
         const int L = t.len;

@@ -78,6 +78,14 @@ __device__ inline int64_t next_work(int32_t *counters, WorkCursor &cur, int64_t 
     }
 }
 
+// The work id is the same for every lane; saying so lets the tile parameters derived from it live in scalar
+// registers and be fetched with scalar loads.
+__device__ inline int64_t uniform64(int64_t x) {
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)x >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
 // One decoded work item.
 struct Work {
     int sample;   // sample id b

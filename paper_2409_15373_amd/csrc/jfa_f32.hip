@@ -33,7 +33,7 @@ __device__ inline int64_t fetch_work(int32_t *counters, WorkCursor &probe, int64
     __syncthreads();
     if (threadIdx.x == 0) *slot = next_work(counters, probe, total);
     __syncthreads();
-    return *slot;
+    return uniform64(*slot);
 }
 
 template <int D>
