@@ -133,16 +133,19 @@ void drop_timed() {
 }
 
 // Forward variant: JFA_FWD_VARIANT=wide selects the experimental 64-queries-per-wave kernel (D = 128 only).
-bool use_wide_forward(int64_t max_len) {
+enum FwdVariant { kNarrow = 0, kWide = 1, kDma = 2 };
+FwdVariant forward_variant(int64_t max_len, int D) {
     static const int forced = [] {
         const char *v = getenv("JFA_FWD_VARIANT");
-        if (v && !strcmp(v, "wide")) return 1;
-        if (v && !strcmp(v, "narrow")) return 0;
+        if (v && !strcmp(v, "wide")) return (int)kWide;
+        if (v && !strcmp(v, "dma")) return (int)kDma;
+        if (v && !strcmp(v, "narrow")) return (int)kNarrow;
         return -1;
     }();
-    if (forced >= 0) return forced == 1;
+    if (D != 128) return kNarrow;
+    if (forced >= 0) return (FwdVariant)forced;
     (void)max_len;
-    return false;   // measured slower than the 32-query kernel so far (one wave per SIMD exposes every latency)
+    return kNarrow;
 }
 
 int hip_fail(const char *what, hipError_t e) { return fail(JFA_ERR_HIP, "%s: %s", what, hipGetErrorString(e)); }
@@ -266,11 +269,12 @@ int jfa_forward(const void *q, const void *k, const void *v, const int64_t *offs
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
-    const bool wide = D == 128 && use_wide_forward(max_len);
-    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, wide ? jfa::kFwdWideBlockRows : jfa::kFwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
+    const FwdVariant variant = forward_variant(max_len, D);
+    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, variant == kNarrow ? jfa::kFwdBlockRows : jfa::kFwdWideBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
-    if (wide) { ScopedTimer tm("fwd_bf16_wide", s); e = jfa::launch_fwd_bf16_wide(q, k, v, offsets, (int)B, H, D, sc, out, lse, w.cus, s); }
+    if (variant == kWide) { ScopedTimer tm("fwd_bf16_wide", s); e = jfa::launch_fwd_bf16_wide(q, k, v, offsets, (int)B, H, D, sc, out, lse, w.cus, s); }
+    else if (variant == kDma) { ScopedTimer tm("fwd_bf16_dma", s); e = jfa::launch_fwd_bf16_dma(q, k, v, offsets, (int)B, H, D, sc, out, lse, w.cus, s); }
     else { ScopedTimer tm("fwd_bf16", s); e = jfa::launch_fwd_bf16(q, k, v, offsets, (int)B, H, D, sc, out, lse, w.cus, s); }
     if (e != hipSuccess) return hip_fail("bf16 forward kernel", e);
     return JFA_OK;

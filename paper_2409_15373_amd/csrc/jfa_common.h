@@ -153,6 +153,8 @@ hipError_t launch_delta(const void *out, const void *dout, const int64_t *offset
 
 constexpr int kFwdBlockRows = 128;
 constexpr int kFwdWideBlockRows = 256;
+hipError_t launch_fwd_bf16_dma(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H,
+                               int D, Schedule s, void *out, float *lse, int cus, hipStream_t stream);
 hipError_t launch_fwd_bf16_wide(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H,
                                 int D, Schedule s, void *out, float *lse, int cus, hipStream_t stream);
 constexpr int kBwdBlockRows = 128;

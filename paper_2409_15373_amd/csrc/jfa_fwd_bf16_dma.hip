@@ -1,0 +1,345 @@
+// Jagged flash attention forward, bf16, D = 128, long-sample variant (paper Section 2.1).
+//
+// Same mathematics and operand layouts as fwd_bf16_kernel (transposed score tile S^T = K Q^T, a lane owns
+// one query, V^T through the transposing LDS read, 32 queries per wave, two waves per SIMD).  What differs:
+//   * a workgroup is eight waves = 256 queries sharing each K / V stage, so the HBM/L2 -> LDS traffic per
+//     flop is half that of the 128-query kernel;
+//   * stages travel HBM/L2 -> LDS directly (global_load_lds_dwordx4): no staging registers, no LDS store
+//     instructions.  The tiles are unpadded and XOR-swizzled on 16-byte (K) / 64-byte (V) granules so that
+//     the 16-byte row reads and the transposing reads are conflict-free on the 64-bank LDS;
+//   * three stage buffers, DMA two stages ahead, and a bare s_barrier with a partial vmcnt wait at the end of a
+//     stage (a __syncthreads() would wait for every load in flight);
+//   * exponentials are taken against a FIXED reference maximum per query (the maximum over the sample's
+//     first 32 keys): no running maximum, no rescaling, no branch in the hot loop.  A reference below the
+//     true maximum only scales numerator and denominator alike -- probabilities keep their relative
+//     precision in fp32 and bf16 -- as long as nothing overflows; a row sum above 2^62 (or not finite) at the
+//     end of the tile shows that it got too stale, and the workgroup then redoes the tile in the conservative
+//     order (maximum first, online rescaling).  On data whose scores are of one scale this never runs.
+#include "jfa_common.h"
+#include "jfa_mfma.h"
+
+namespace jfa {
+
+constexpr int kDmaThreads = 512;
+constexpr int kDmaWaves = kDmaThreads / 64;
+constexpr int kDmaBN = 64;            // keys per LDS stage
+constexpr int kDmaD = 128;
+constexpr int kDmaTile = kDmaBN * kDmaD * 2;   // bytes of one K or V stage in LDS
+constexpr int kDmaOpsPerStage = 2 * (kDmaBN / 4) / kDmaWaves;   // DMA instructions per wave per stage (K and V)
+
+template <int N> using IntC = std::integral_constant<int, N>;
+
+__device__ inline void dma16b(const __bf16 *src, char *lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+
+__global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf16 *__restrict__ q,
+                                                                      const __bf16 *__restrict__ k,
+                                                                      const __bf16 *__restrict__ v,
+                                                                      const int64_t *__restrict__ offsets, int B,
+                                                                      int H, Schedule s, __bf16 *__restrict__ out,
+                                                                      float *__restrict__ lse) {
+    constexpr int D = kDmaD;
+    constexpr int kKSteps = D / 16;    // 8
+    constexpr int kDBlocks = D / 32;   // 4
+    // Separate arrays (not one indexed array) so that the compiler can tell the buffer being filled by the
+    // DMA from the one being read and does not make the reads wait for the loads in flight.
+    __shared__ __attribute__((aligned(1024))) char K0[kDmaTile];
+    __shared__ __attribute__((aligned(1024))) char K1[kDmaTile];
+    __shared__ __attribute__((aligned(1024))) char K2[kDmaTile];
+    __shared__ __attribute__((aligned(1024))) char V0[kDmaTile];
+    __shared__ __attribute__((aligned(1024))) char V1[kDmaTile];
+    __shared__ __attribute__((aligned(1024))) char V2[kDmaTile];
+    __shared__ int64_t slot;
+    __shared__ int restart;   // set by a wave whose reference maximum went stale beyond repair
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = lane & 31, half = lane >> 5;
+    const float c = 1.4426950408889634f / sqrtf((float)D);
+    const int64_t total = (int64_t)s.tile_start[B] * H;
+    const int64_t sum_B = offsets[B];
+    const int64_t row_stride = (int64_t)H * D;
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+
+    // ---- LDS read addresses (bytes inside a tile), fixed for the whole kernel ----
+    // K element (row r, 16-byte chunk ch) sits at r * 256 + ((ch ^ (r & 15)) << 4).
+    int kaddr[kKSteps];
+#pragma unroll
+    for (int ks = 0; ks < kKSteps; ++ks) kaddr[ks] = col * 256 + (((2 * ks + half) ^ (col & 15)) << 4);
+    // V element (row r, 64-byte group g, byte b inside it) sits at r * 256 + ((g ^ (r & 3)) << 6) + b.
+    // The transposing read of this lane: row = 4 half + (lane & 15) / 4 (+8 for the second half of the
+    // operand, +16 per 16-key step), group = feature block db, bytes 32 * ((lane >> 4) & 1) + 8 * (lane & 3).
+    int vaddr[kDBlocks];
+    {
+        const int r = half * 4 + ((lane & 15) >> 2);
+#pragma unroll
+        for (int db = 0; db < kDBlocks; ++db)
+            vaddr[db] = r * 256 + ((db ^ (r & 3)) << 6) + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
+    }
+    // ---- DMA: one instruction moves 64 lanes x 16 bytes = 4 rows; wave w, instruction u fills rows 8 w + 4 u .. +3.
+    // Lane l lands on physical chunk l & 15 of row 8 w + 4 u + (l >> 4) and so fetches the logical chunk that
+    // the swizzle puts there.
+    const int dma_row0 = 8 * wave + (lane >> 4);
+    const int pc = lane & 15;
+
+    WorkCursor cursor;
+    for (;;) {
+        __syncthreads();
+        if (tid == 0) slot = next_work(s.counter, cursor, total);
+        __syncthreads();
+        const int64_t w = uniform64(slot);
+        if (w < 0) break;
+        const Work t = decode_work(s, offsets, B, H, w);
+        const int L = t.len;
+        const int n_stages = (L + kDmaBN - 1) / kDmaBN;
+        const __bf16 *kbase = k + t.row0 * row_stride + (int64_t)t.head * D;
+        const __bf16 *vbase = v + t.row0 * row_stride + (int64_t)t.head * D;
+
+        // element offsets of this lane's DMA chunks inside a full stage (K and V differ in the swizzle)
+        int koffs[2], voffs[2];
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int r = dma_row0 + 4 * u;
+            koffs[u] = r * (int)row_stride + ((pc ^ (r & 15)) << 3);
+            voffs[u] = r * (int)row_stride + ((pc ^ ((r & 3) << 2)) << 3);
+        }
+        auto issue = [&](const __bf16 *base, char *tile, int stage, bool is_k) {
+            const int j0 = stage * kDmaBN;
+            const __bf16 *sbase = base + (int64_t)j0 * row_stride;
+            if (j0 + kDmaBN <= L) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) dma16b(sbase + (is_k ? koffs[u] : voffs[u]), tile + (8 * wave + 4 * u) * 256);
+            } else {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int r = dma_row0 + 4 * u;
+                    const int ch = is_k ? (pc ^ (r & 15)) : (pc ^ ((r & 3) << 2));
+                    const int jr = j0 + r < L ? r : L - 1 - j0;   // rows past the end repeat the last key (masked later)
+                    dma16b(sbase + (int64_t)jr * row_stride + ch * 8, tile + (8 * wave + 4 * u) * 256);
+                }
+            }
+        };
+
+        const int i = t.block * kFwdWideBlockRows + wave * 32 + col;   // this lane's query
+        const int iq = i < L ? i : L - 1;
+        const bool wave_active = t.block * kFwdWideBlockRows + wave * 32 < L;
+        bf16x8 qreg[kKSteps];
+        {
+            const __bf16 *qrow = q + (t.row0 + iq) * row_stride + (int64_t)t.head * D + 8 * half;
+#pragma unroll
+            for (int ks = 0; ks < kKSteps; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * ks);
+        }
+
+        f32x16 o[kDBlocks];
+#pragma unroll
+        for (int db = 0; db < kDBlocks; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[db][e] = 0.0f;
+        float m = -INFINITY, lsum = 0.0f;
+
+        // ---- helpers ----
+        auto scores = [&](const char *tile, int mb, f32x16 &a) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) a[e] = 0.0f;
+            bf16x8 kop[kKSteps];
+#pragma unroll
+            for (int ks = 0; ks < kKSteps; ++ks) kop[ks] = lds_read_b128(tile + mb * 32 * 256 + kaddr[ks]);
+#pragma unroll
+            for (int ks = 0; ks < kKSteps; ++ks) a = mfma_32x32x16(kop[ks], qreg[ks], a);
+        };
+        auto accumulate = [&](const char *tile, int mb, const bf16x8 (&p)[2]) {
+#pragma unroll
+            for (int ts = 0; ts < 2; ++ts) {
+                bf16x8 vop[kDBlocks];
+#pragma unroll
+                for (int db = 0; db < kDBlocks; ++db) {
+                    const char *pvp = tile + (mb * 32 + ts * 16) * 256 + vaddr[db];
+                    vop[db] = concat(lds_read_tr16(pvp), lds_read_tr16(pvp + 8 * 256));
+                }
+#pragma unroll
+                for (int db = 0; db < kDBlocks; ++db) o[db] = mfma_32x32x16(vop[db], p[ts], o[db]);
+            }
+        };
+        // exponentials of one unit (32 keys x 32 queries) against the reference maximum; the rounded
+        // probabilities are what the second product uses, so they are what the row sum adds up
+        auto exps = [&](const f32x16 &st, float mc, bf16x8 (&p)[2]) {
+#pragma unroll
+            for (int ts = 0; ts < 2; ++ts) {
+                u32x4 pw;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    bf16x2 pr;
+                    pr[0] = (__bf16)fast_exp2(fmaf(st[8 * ts + 2 * e], c, -mc));
+                    pr[1] = (__bf16)fast_exp2(fmaf(st[8 * ts + 2 * e + 1], c, -mc));
+                    lsum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lsum, false);
+                    pw[e] = __builtin_bit_cast(uint32_t, pr);
+                }
+                p[ts] = __builtin_bit_cast(bf16x8, pw);
+            }
+        };
+        auto mask = [&](f32x16 &st, int key0) {   // keys past the end of the sample
+#pragma unroll
+            for (int e = 0; e < 16; ++e)
+                if (key0 + acc_row(e, half) >= L) st[e] = -INFINITY;
+        };
+        auto unit_max = [&](const f32x16 &a, float mx) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) mx = fmaxf(mx, a[e]);
+            return mx;
+        };
+        auto kbuf = [&](int bsel) { return bsel == 0 ? K0 : (bsel == 1 ? K1 : K2); };
+        auto vbuf = [&](int bsel) { return bsel == 0 ? V0 : (bsel == 1 ? V1 : V2); };
+
+        // pipelined(): fast order against the fixed reference maximum m
+        auto pipelined = [&](auto BUF, auto RAGGED, int j) {
+            constexpr int P = decltype(BUF)::value;   // buffer of this stage: j % 3
+            constexpr bool kRagged = decltype(RAGGED)::value != 0;
+            const char *const Kc = P == 0 ? K0 : (P == 1 ? K1 : K2);
+            const char *const Vc = P == 0 ? V0 : (P == 1 ? V1 : V2);
+            const float mc = m * c;
+            f32x16 s0, s1;
+            bf16x8 p0[2], p1[2];
+            scores(Kc, 0, s0);
+            scores(Kc, 1, s1);                         // matrix pipe: scores of key block 1 ...
+            if (kRagged) mask(s0, j * kDmaBN);
+            exps(s0, mc, p0);                          // ... VALU: exponentials of key block 0
+            accumulate(Vc, 0, p0);                     // matrix pipe: O^T += V^T P^T of key block 0 ...
+            if (kRagged) mask(s1, j * kDmaBN + 32);
+            exps(s1, mc, p1);                          // ... VALU: exponentials of key block 1
+            accumulate(Vc, 1, p1);
+        };
+        // conservative(): maximum first, rescale, then exponentials; used when a tile had to be restarted
+        auto conservative = [&](int bsel, int j) {
+            const char *const Kc = kbuf(bsel);
+            const char *const Vc = vbuf(bsel);
+            f32x16 s0, s1;
+            bf16x8 p0[2], p1[2];
+            scores(Kc, 0, s0);
+            scores(Kc, 1, s1);
+            if ((j + 1) * kDmaBN > L) { mask(s0, j * kDmaBN); mask(s1, j * kDmaBN + 32); }
+            const float x = pair_max(unit_max(s1, unit_max(s0, -INFINITY)));
+            const float n = fmaxf(m, x);
+            const float a = fast_exp2((m - n) * c);   // 0 on the first stage
+            m = n;
+            lsum *= a;
+#pragma unroll
+            for (int db = 0; db < kDBlocks; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[db][e] *= a;
+            exps(s0, n * c, p0);
+            accumulate(Vc, 0, p0);
+            exps(s1, n * c, p1);
+            accumulate(Vc, 1, p1);
+        };
+
+        // ---- pass 1: pipelined, three stage buffers, DMA two stages ahead ----
+        // Stage j lives in buffer j % 3.  At the top of stage j the DMA of stage j + 2 is issued into the buffer
+        // that stage j - 1 has just released; at the end of stage j each wave waits until only those newest
+        // DMA operations are outstanding (so stage j + 1 has landed) and meets the others at a bare s_barrier.
+        auto issue_stage = [&](auto BUF, int j) {
+            constexpr int Bf = decltype(BUF)::value;
+            issue(kbase, Bf == 0 ? K0 : (Bf == 1 ? K1 : K2), j, true);
+            issue(vbase, Bf == 0 ? V0 : (Bf == 1 ? V1 : V2), j, false);
+        };
+        auto run_stage = [&](auto BUF, auto RAGGED, int j) {
+            constexpr int Bf = decltype(BUF)::value;
+            const bool ahead = j + 2 < n_stages;
+            if (ahead) issue_stage(IntC<(Bf + 2) % 3>{}, j + 2);
+            if (wave_active) pipelined(BUF, RAGGED, j);
+            asm volatile("" ::: "memory");
+            if (ahead) __builtin_amdgcn_s_waitcnt(0x0070 | kDmaOpsPerStage);   // vmcnt(ops of one stage) lgkmcnt(0)
+            else __builtin_amdgcn_s_waitcnt(0x0070);                           // vmcnt(0) lgkmcnt(0)
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        };
+
+        if (tid == 0) restart = 0;
+        issue_stage(IntC<0>{}, 0);
+        if (n_stages > 1) issue_stage(IntC<1>{}, 1);
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qreg[ks]));   // Q loads complete here
+        if (n_stages > 1) __builtin_amdgcn_s_waitcnt(0x0070 | kDmaOpsPerStage); else __builtin_amdgcn_s_waitcnt(0x0070);
+        __syncthreads();
+        if (wave_active) {   // reference maximum: the first 32 keys
+            f32x16 s0;
+            scores(K0, 0, s0);
+            if (L < 32) mask(s0, 0);
+            m = pair_max(unit_max(s0, -INFINITY));
+        }
+        {
+            const int n_full = L / kDmaBN;   // stages with all 64 keys valid; a ragged one may follow
+            int j = 0;
+            for (; j + 3 <= n_full; j += 3) {
+                run_stage(IntC<0>{}, IntC<0>{}, j);
+                run_stage(IntC<1>{}, IntC<0>{}, j + 1);
+                run_stage(IntC<2>{}, IntC<0>{}, j + 2);
+            }
+            if (j < n_full) { run_stage(IntC<0>{}, IntC<0>{}, j); ++j; }
+            if (j < n_full) { run_stage(IntC<1>{}, IntC<0>{}, j); ++j; }
+            if (j < n_stages) {               // the ragged last stage, in buffer n_full % 3
+                const int r = n_full % 3;
+                if (r == 0) run_stage(IntC<0>{}, IntC<1>{}, j);
+                else if (r == 1) run_stage(IntC<1>{}, IntC<1>{}, j);
+                else run_stage(IntC<2>{}, IntC<1>{}, j);
+            }
+        }
+        // a row sum this large (or not finite) means the fixed reference was too far below the true maximum
+        if (wave_active && __builtin_amdgcn_ballot_w64(!(lsum < 0x1p62f)) != 0 && lane == 0) restart = 1;
+        __syncthreads();
+        const bool again = restart != 0;
+
+        // ---- pass 2 (never on data of one scale): the whole tile again, maximum first, two buffers ----
+        if (again) {
+            __syncthreads();   // every wave has seen `restart` before the next tile clears it
+            issue(kbase, K0, 0, true);
+            issue(vbase, V0, 0, false);
+            __builtin_amdgcn_s_waitcnt(0x0070);
+            __syncthreads();
+            m = -INFINITY;
+            lsum = 0.0f;
+#pragma unroll
+            for (int db = 0; db < kDBlocks; ++db)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[db][e] = 0.0f;
+            for (int j = 0; j < n_stages; ++j) {
+                if (j + 1 < n_stages) {
+                    issue(kbase, kbuf((j + 1) & 1), j + 1, true);
+                    issue(vbase, vbuf((j + 1) & 1), j + 1, false);
+                }
+                if (wave_active) conservative(j & 1, j);
+                __builtin_amdgcn_s_waitcnt(0x0070);
+                __syncthreads();
+            }
+        }
+
+        // ---- epilogue: normalise, store this lane's query row and its log-sum-exp ----
+        const float l_total = pair_sum(lsum);
+        if (i < L) {
+            const float inv = 1.0f / l_total;
+            __bf16 *orow = out + (t.row0 + i) * row_stride + (int64_t)t.head * D;
+#pragma unroll
+            for (int db = 0; db < kDBlocks; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x4 x;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) x[e] = (__bf16)(o[db][4 * g + e] * inv);
+                    *reinterpret_cast<bf16x4 *>(orow + db * 32 + g * 8 + half * 4) = x;
+                }
+            if (half == 0)
+                lse[(int64_t)t.head * sum_B + t.row0 + i] = (m * c + fast_log2(l_total)) * 0.6931471805599453f;
+        }
+    }
+}
+
+hipError_t launch_fwd_bf16_dma(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H,
+                               int D, Schedule s, void *out, float *lse, int cus, hipStream_t stream) {
+    if (D != kDmaD) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(fwd_bf16_dma_kernel, dim3(persistent_grid<fwd_bf16_dma_kernel>(kDmaThreads, cus)),
+                       dim3(kDmaThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, offsets,
+                       B, H, s, (__bf16 *)out, lse);
+    return hipGetLastError();
+}
+
+}  // namespace jfa
