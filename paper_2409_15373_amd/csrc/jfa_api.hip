@@ -144,8 +144,7 @@ FwdVariant forward_variant(int64_t max_len, int D) {
     }();
     if (D != 128) return kNarrow;
     if (forced >= 0) return (FwdVariant)forced;
-    (void)max_len;
-    return kNarrow;
+    return max_len > 256 ? kDma : kNarrow;   // 256-query tiles only pay off when samples can be long
 }
 
 int hip_fail(const char *what, hipError_t e) { return fail(JFA_ERR_HIP, "%s: %s", what, hipGetErrorString(e)); }

@@ -50,7 +50,9 @@ struct Stage {
 
 template <int D>
 struct alignas(16) BwdSmem {
-    static constexpr int kStride = D * 2 + 16;  // bytes per staged row
+    // bytes per staged row: +80 keeps both the 16-byte row reads and the transposing reads (nearly) conflict-free
+    // on the 64-bank LDS (16 lanes x 16 bytes need rows 16 bytes apart modulo 256, 4 rows x 64 bytes need them 64 apart)
+    static constexpr int kStride = D * 2 + 80;
     char a[kBwdStage * kStride];                // dq: K      dkv: Q
     char b[kBwdStage * kStride];                // dq: V      dkv: dO
     float lse2[kBwdStage];                      // dkv only: lse * log2(e), +inf for rows past the end

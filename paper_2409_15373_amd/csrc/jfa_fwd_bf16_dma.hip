@@ -170,9 +170,15 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     bf16x2 pr;
+#ifdef JFA_EXP_NOSOFTMAX
+                    pr[0] = (__bf16)(st[8 * ts + 2 * e]);
+                    pr[1] = (__bf16)(st[8 * ts + 2 * e + 1]);
+                    lsum = mc;
+#else
                     pr[0] = (__bf16)fast_exp2(fmaf(st[8 * ts + 2 * e], c, -mc));
                     pr[1] = (__bf16)fast_exp2(fmaf(st[8 * ts + 2 * e + 1], c, -mc));
                     lsum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lsum, false);
+#endif
                     pw[e] = __builtin_bit_cast(uint32_t, pr);
                 }
                 p[ts] = __builtin_bit_cast(bf16x8, pw);
@@ -200,8 +206,28 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             const float mc = m * c;
             f32x16 s0, s1;
             bf16x8 p0[2], p1[2];
-            scores(Kc, 0, s0);
-            scores(Kc, 1, s1);                         // matrix pipe: scores of key block 1 ...
+            {
+                bf16x8 ka[kKSteps], kb[kKSteps];
+#pragma unroll
+                for (int ks = 0; ks < kKSteps; ++ks) ka[ks] = lds_read_b128(Kc + kaddr[ks]);
+#pragma unroll
+                for (int ks = 0; ks < kKSteps; ++ks) kb[ks] = lds_read_b128(Kc + 32 * 256 + kaddr[ks]);
+#pragma unroll
+                for (int e = 0; e < 16; ++e) { s0[e] = 0.0f; s1[e] = 0.0f; }
+#pragma unroll
+                for (int ks = 0; ks < kKSteps; ++ks) s0 = mfma_32x32x16(ka[ks], qreg[ks], s0);
+#pragma unroll
+                for (int ks = 0; ks < kKSteps; ++ks) s1 = mfma_32x32x16(kb[ks], qreg[ks], s1);   // scores of key block 1 ...
+                // issue order: the first block's operand reads, then one read of the second block behind each
+                // matrix product of the first, so that LDS latency hides under the matrix pipe
+                __builtin_amdgcn_sched_group_barrier(0x100, kKSteps, 0);
+#pragma unroll
+                for (int ks = 0; ks < kKSteps; ++ks) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, kKSteps, 0);
+            }
             if (kRagged) mask(s0, j * kDmaBN);
             exps(s0, mc, p0);                          // ... VALU: exponentials of key block 0
             accumulate(Vc, 0, p0);                     // matrix pipe: O^T += V^T P^T of key block 0 ...
@@ -244,6 +270,22 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         };
         auto run_stage = [&](auto BUF, auto RAGGED, int j) {
             constexpr int Bf = decltype(BUF)::value;
+#if defined(JFA_EXP_NOSTAGE)
+            if (wave_active) pipelined(BUF, RAGGED, j);
+#elif defined(JFA_EXP_NODMA)
+            if (wave_active) pipelined(BUF, RAGGED, j);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+#elif defined(JFA_EXP_NOWAIT)
+            const bool ahead = j + 2 < n_stages;
+            if (ahead) issue_stage(IntC<(Bf + 2) % 3>{}, j + 2);
+            if (wave_active) pipelined(BUF, RAGGED, j);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(0x0070 | 63 & 15 | 0xC000);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+#else
             const bool ahead = j + 2 < n_stages;
             if (ahead) issue_stage(IntC<(Bf + 2) % 3>{}, j + 2);
             if (wave_active) pipelined(BUF, RAGGED, j);
@@ -252,6 +294,7 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             else __builtin_amdgcn_s_waitcnt(0x0070);                           // vmcnt(0) lgkmcnt(0)
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
+#endif
         };
 
         if (tid == 0) restart = 0;
