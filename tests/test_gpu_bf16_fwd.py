@@ -72,6 +72,43 @@ def test_bf16_forward_large_scores_stay_finite(oracle):
     gate_bf16("lse", f64(lse), ref_lse, abs_tol=2e-2 * max(1.0, np.abs(ref_lse).max() / 4))
 
 
+def test_both_forward_kernels_on_the_same_data(oracle):
+    """D = 128: max_len <= 256 selects the 128-query kernel, max_len > 256 the 256-query direct-to-LDS kernel."""
+    from paper_2409_15373_amd import binding
+    w = make_custom("both", [256, 130, 1, 77, 0, 200, 33], 2, 128, dtype="bf16", seed=11, dout=False)
+    ref_out, ref_lse = oracle.forward(w.q, w.k, w.v, w.offsets)
+    d = to_device(w, names=("q", "k", "v"))
+    outs = []
+    for max_len in (256, 257):
+        out, lse = binding.jfa_forward(d["q"], d["k"], d["v"], d["offsets"], max_len)
+        torch.cuda.synchronize()
+        gate_bf16(f"out(max_len={max_len})", f64(out), ref_out)
+        gate_bf16(f"lse(max_len={max_len})", f64(lse), ref_lse)
+        outs.append(out)
+    assert (outs[0].float() - outs[1].float()).abs().max().item() <= 2e-2
+
+
+def test_stale_reference_maximum_falls_back_to_the_conservative_pass(oracle):
+    """The direct-to-LDS kernel exponentiates against the maximum over the first 32 keys.  Here the first 40
+    keys score 0 and the rest score ~724 (e^724 overflows fp32 by far), so the row sums blow up and the
+    workgroup must redo the tile with the maximum-first order -- and still match the oracle."""
+    from paper_2409_15373_amd.synthetic import round_to_bf16_bits
+    lengths = [300, 500, 40]
+    w = make_custom("stale", lengths, 1, 128, dtype="bf16", seed=12, dout=False, max_len=512)
+    q = np.full_like(w.q, 8.0)
+    k = np.zeros_like(w.k)
+    for b, L in enumerate(lengths):
+        s0 = int(w.offsets[b])
+        k[s0 + 40: s0 + L] = 8.0            # keys 40.. score 8 * 8 * 128 / sqrt(128) = 724; a 40-long sample has none
+    w.q, w.k = q, k
+    w.bits["q"], w.bits["k"] = round_to_bf16_bits(q), round_to_bf16_bits(k)
+    out, lse = gpu_forward(w)
+    ref_out, ref_lse = oracle.forward(w.q, w.k, w.v, w.offsets)
+    assert np.isfinite(f64(out)).all() and np.isfinite(f64(lse)).all()
+    gate_bf16("out", f64(out), ref_out)
+    gate_bf16("lse", f64(lse), ref_lse, abs_tol=2e-2 * max(1.0, np.abs(ref_lse).max() / 4))
+
+
 def test_config2_full(oracle):
     w = make_workload("c2_geom_bf16")
     out, lse = gpu_forward(w)
