@@ -289,10 +289,21 @@ int jfa_backward(const void *q, const void *k, const void *v, const void *out, c
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
-    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, jfa::kBwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
+    const bool dma = D == 128 && forward_variant(max_len, D) != kNarrow;   // long samples: direct-to-LDS kernels
+    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, dma ? jfa::kFwdWideBlockRows : jfa::kBwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     { ScopedTimer tm("delta", s); e = jfa::launch_delta(out, dout, offsets, (int)B, H, D, true, delta, w.cus, s); }
     if (e != hipSuccess) return hip_fail("delta kernel", e);
+    if (dma) {
+        static const char *const names[3] = {"dq_bf16_dma", "dk_bf16_dma", "dv_bf16_dma"};
+        void *const grads[3] = {dq, dk, dv};
+        for (int mode = 0; mode < 3; ++mode) {
+            jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters + mode * jfa::kXcds};
+            { ScopedTimer tm(names[mode], s); e = jfa::launch_bwd_bf16_dma(mode, q, k, v, dout, lse, delta, offsets, (int)B, H, D, sc, grads[mode], w.cus, s); }
+            if (e != hipSuccess) return hip_fail(names[mode], e);
+        }
+        return JFA_OK;
+    }
     jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
     jfa::Schedule s_dkv{w.order[0], w.tile_start[0], w.counters + jfa::kXcds};
     { ScopedTimer tm("dkv_bf16", s); e = jfa::launch_dkv_bf16(q, k, v, dout, lse, delta, offsets, (int)B, H, D, s_dkv, dk, dv, w.cus, s); }

@@ -1,0 +1,319 @@
+// Jagged flash attention backward, bf16, D = 128, long-sample variant (paper Section 2.2).
+//
+//   P = exp(S / sqrt(D) - lse),  dP = dO V^T,  dS = P o (dP - delta),  dV = P^T dO,  dQ = dS K / sqrt(D),  dK = dS^T Q / sqrt(D)
+//
+// Three kernels of one template, all shaped like the direct-to-LDS forward kernel: a workgroup is eight
+// waves (two per SIMD), a wave owns 32 "stationary" rows whose operands stay in registers and whose gradient
+// it accumulates, and the sample's other rows stream through three XOR-swizzled LDS stage buffers filled by
+// global_load_lds two stages ahead (bare s_barrier + partial vmcnt wait per stage):
+//   dQ  stationary = queries (Q, dO rows, lse, delta per lane); streams K and V;      dQ^T += K^T dS^T
+//   dK  stationary = keys (K, V rows); streams Q, dO and lse, delta per streamed row;  dK^T += Q^T dS
+//   dV  stationary = keys (K rows);    streams Q, dO and lse;                          dV^T += dO^T P
+// In every case the score tile has the streamed rows on the MFMA row axis and the stationary rows on the
+// column (= lane) axis, so P / dS leave the accumulator already in operand position for the last product,
+// whose other operand is the transposing LDS read of a streamed tile.  Keeping dK and dV in separate kernels
+// costs one more recomputation of S but lets each of them run two waves per SIMD (their accumulators together
+// need the whole register file), and nothing is accumulated with atomics: results are deterministic.
+#include "jfa_common.h"
+#include "jfa_mfma.h"
+
+namespace jfa {
+
+constexpr int kBdThreads = 512;
+constexpr int kBdWaves = kBdThreads / 64;
+constexpr int kBdBN = 64;             // streamed rows per LDS stage
+constexpr int kBdD = 128;
+constexpr int kBdTile = kBdBN * kBdD * 2;
+
+enum BwdMode { kModeDQ = 0, kModeDK = 1, kModeDV = 2 };
+
+template <int N> using IntB = std::integral_constant<int, N>;
+
+// Row r, 16-byte chunk ch of a streamed tile sits at r * 256 + ((ch ^ swz(r)) << 4): conflict-free for the
+// 16-byte row reads (16 consecutive rows hit 16 different chunk columns) and for the transposing reads
+// (4 consecutive rows hit 4 different 64-byte groups) on the 64-bank LDS.
+__device__ inline int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
+
+__device__ inline void bd_dma16(const __bf16 *src, char *lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
+}
+__device__ inline void bd_dma4(const float *src, char *lds_wave_base) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                     (__attribute__((address_space(3))) void *)lds_wave_base, 4, 0, 0);
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf16 *__restrict__ q,
+                                                                     const __bf16 *__restrict__ k,
+                                                                     const __bf16 *__restrict__ v,
+                                                                     const __bf16 *__restrict__ dout,
+                                                                     const float *__restrict__ lse,
+                                                                     const float *__restrict__ delta,
+                                                                     const int64_t *__restrict__ offsets, int B, int H,
+                                                                     Schedule s, __bf16 *__restrict__ grad) {
+    constexpr int D = kBdD;
+    constexpr int kKSteps = D / 16;
+    constexpr int kDBlocks = D / 32;
+    constexpr bool kRowStats = MODE != kModeDQ;   // lse / delta belong to the streamed rows
+    constexpr bool kSecond = MODE != kModeDV;     // dP / dS are needed
+    // streamed tile A: dQ: K, dK: Q, dV: Q      (16-byte row reads; transposing reads too unless dV)
+    // streamed tile B: dQ: V, dK: dO, dV: dO    (16-byte row reads; dV: transposing reads only)
+    __shared__ __attribute__((aligned(1024))) char A0[kBdTile];
+    __shared__ __attribute__((aligned(1024))) char A1[kBdTile];
+    __shared__ __attribute__((aligned(1024))) char A2[kBdTile];
+    __shared__ __attribute__((aligned(1024))) char B0[kBdTile];
+    __shared__ __attribute__((aligned(1024))) char B1[kBdTile];
+    __shared__ __attribute__((aligned(1024))) char B2[kBdTile];
+    __shared__ __attribute__((aligned(256))) char S0[512];   // per stage: lse[64], delta[64] of the streamed rows
+    __shared__ __attribute__((aligned(256))) char S1[512];
+    __shared__ __attribute__((aligned(256))) char S2[512];
+    __shared__ int64_t slot;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = lane & 31, half = lane >> 5;
+    const float scale = 1.0f / sqrtf((float)D);
+    const float c = 1.4426950408889634f * scale;
+    const int64_t total = (int64_t)s.tile_start[B] * H;
+    const int64_t sum_B = offsets[B];
+    const int64_t row_stride = (int64_t)H * D;
+
+    // LDS read addresses inside a tile
+    int raddr[kKSteps];   // 16-byte row reads: row = col (+32 per block), chunk 2 ks + half
+#pragma unroll
+    for (int ks = 0; ks < kKSteps; ++ks) raddr[ks] = col * 256 + (((2 * ks + half) ^ swz(col)) << 4);
+    int taddr[2][kDBlocks];   // transposing reads: row = 4 half + (lane & 15) / 4 (+8 for the operand's second half)
+    {
+        const int r = half * 4 + ((lane & 15) >> 2);
+        const int chunk_in_group = ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1), byte_in_chunk = (lane & 1) * 8;
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2)
+#pragma unroll
+            for (int db = 0; db < kDBlocks; ++db)
+                taddr[h2][db] = (r + 8 * h2) * 256 + (((db * 4 + chunk_in_group) ^ swz(r + 8 * h2)) << 4) + byte_in_chunk;
+    }
+    const int dma_row0 = 8 * wave + (lane >> 4);
+    const int pc = lane & 15;
+
+    WorkCursor cursor;
+    for (;;) {
+        __syncthreads();
+        if (tid == 0) slot = next_work(s.counter, cursor, total);
+        __syncthreads();
+        const int64_t w = uniform64(slot);
+        if (w < 0) break;
+        const Work t = decode_work(s, offsets, B, H, w);
+        const int L = t.len;
+        const int n_stages = (L + kBdBN - 1) / kBdBN;
+        const int64_t head_off = t.row0 * row_stride + (int64_t)t.head * D;
+        const __bf16 *abase = (MODE == kModeDQ ? k : q) + head_off;
+        const __bf16 *bbase = (MODE == kModeDQ ? v : dout) + head_off;
+        const float *lse_rows = lse + (int64_t)t.head * sum_B + t.row0;
+        const float *delta_rows = delta + (int64_t)t.head * sum_B + t.row0;
+
+        int offs[2];   // element offsets of this lane's two DMA chunks inside a full stage
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int r = dma_row0 + 4 * u;
+            offs[u] = r * (int)row_stride + ((pc ^ swz(r)) << 3);
+        }
+        auto issue = [&](const __bf16 *base, char *tile, int stage) {
+            const int j0 = stage * kBdBN;
+            const __bf16 *sbase = base + (int64_t)j0 * row_stride;
+            if (j0 + kBdBN <= L) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) bd_dma16(sbase + offs[u], tile + (8 * wave + 4 * u) * 256);
+            } else {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int r = dma_row0 + 4 * u;
+                    const int jr = j0 + r < L ? r : L - 1 - j0;   // rows past the end repeat the last row (masked later)
+                    bd_dma16(sbase + (int64_t)jr * row_stride + ((pc ^ swz(r)) << 3), tile + (8 * wave + 4 * u) * 256);
+                }
+            }
+        };
+        auto issue_stats = [&](char *stats, int stage) {   // wave 0 only: lse and delta of the 64 streamed rows
+            const int j0 = stage * kBdBN;
+            const int j = j0 + lane < L ? j0 + lane : L - 1;
+            bd_dma4(lse_rows + j, stats);
+            if (kSecond) bd_dma4(delta_rows + j, stats + 256);
+        };
+
+        // ---- stationary rows: this lane's row as B operands ----
+        const int i = t.block * kFwdWideBlockRows + wave * 32 + col;
+        const int ic = i < L ? i : L - 1;
+        const bool wave_active = t.block * kFwdWideBlockRows + wave * 32 < L;
+        bf16x8 xreg[kKSteps], yreg[kKSteps];   // dQ: Q, dO rows   dK: K, V rows   dV: K rows
+        {
+            const int64_t off = (t.row0 + ic) * row_stride + (int64_t)t.head * D + 8 * half;
+            const __bf16 *xsrc = MODE == kModeDQ ? q : k;
+            const __bf16 *ysrc = MODE == kModeDQ ? dout : v;
+#pragma unroll
+            for (int ks = 0; ks < kKSteps; ++ks) {
+                xreg[ks] = *reinterpret_cast<const bf16x8 *>(xsrc + off + 16 * ks);
+                if (kSecond) yreg[ks] = *reinterpret_cast<const bf16x8 *>(ysrc + off + 16 * ks);
+            }
+        }
+        float lse2_lane = 0.0f, delta_lane = 0.0f;
+        if (!kRowStats) {
+            lse2_lane = lse_rows[ic] * 1.4426950408889634f;
+            delta_lane = delta_rows[ic];
+        }
+        f32x16 acc[kDBlocks];
+#pragma unroll
+        for (int db = 0; db < kDBlocks; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[db][e] = 0.0f;
+
+        // ---- one stage: 64 streamed rows in two blocks of 32 ----
+        auto run_block = [&](const char *At, const char *Bt, const char *St, int mb, int j0, bool ragged) {
+            f32x16 sc, dp;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) { sc[e] = 0.0f; dp[e] = 0.0f; }
+            // operands are fetched four at a time to keep the register footprint at two waves per SIMD
+#pragma unroll
+            for (int k4 = 0; k4 < kKSteps; k4 += 4) {
+                bf16x8 aop[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) aop[u] = lds_read_b128(At + mb * 32 * 256 + raddr[k4 + u]);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) sc = mfma_32x32x16(aop[u], xreg[k4 + u], sc);
+            }
+            if (kSecond) {
+#pragma unroll
+                for (int k4 = 0; k4 < kKSteps; k4 += 4) {
+                    bf16x8 bop[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) bop[u] = lds_read_b128(Bt + mb * 32 * 256 + raddr[k4 + u]);
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) dp = mfma_32x32x16(bop[u], yreg[k4 + u], dp);
+                }
+            }
+            // P (and dS) for this lane's stationary row and its 16 streamed rows of the block
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                float lv[4], dl[4];
+                if (kRowStats) {
+                    const float4 l4 = *reinterpret_cast<const float4 *>(St + (mb * 32 + g * 8 + half * 4) * 4);
+                    lv[0] = l4.x * 1.4426950408889634f; lv[1] = l4.y * 1.4426950408889634f;
+                    lv[2] = l4.z * 1.4426950408889634f; lv[3] = l4.w * 1.4426950408889634f;
+                    if (kSecond) {
+                        const float4 d4 = *reinterpret_cast<const float4 *>(St + 256 + (mb * 32 + g * 8 + half * 4) * 4);
+                        dl[0] = d4.x; dl[1] = d4.y; dl[2] = d4.z; dl[3] = d4.w;
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float p = fast_exp2(fmaf(sc[4 * g + e], c, -(kRowStats ? lv[e] : lse2_lane)));
+                    if (ragged && j0 + mb * 32 + g * 8 + half * 4 + e >= L) p = 0.0f;   // streamed rows past the end
+                    sc[4 * g + e] = p;
+                    if (kSecond) dp[4 * g + e] = p * (dp[4 * g + e] - (kRowStats ? dl[e] : delta_lane));
+                }
+            }
+            // gradient accumulation: contraction over the 32 streamed rows in two steps of 16
+            const char *Tt = MODE == kModeDV ? Bt : At;
+#pragma unroll
+            for (int ts = 0; ts < 2; ++ts) {
+                const bf16x8 pb = pack_bf16(kSecond ? dp : sc, 8 * ts);
+                bf16x8 top[kDBlocks];
+#pragma unroll
+                for (int db = 0; db < kDBlocks; ++db) {
+                    const char *base = Tt + (mb * 32 + ts * 16) * 256;
+                    top[db] = concat(lds_read_tr16(base + taddr[0][db]), lds_read_tr16(base + taddr[1][db]));
+                }
+#pragma unroll
+                for (int db = 0; db < kDBlocks; ++db) acc[db] = mfma_32x32x16(top[db], pb, acc[db]);
+            }
+        };
+        auto issue_stage = [&](auto BUF, int j) {
+            constexpr int Bf = decltype(BUF)::value;
+            issue(abase, Bf == 0 ? A0 : (Bf == 1 ? A1 : A2), j);
+            issue(bbase, Bf == 0 ? B0 : (Bf == 1 ? B1 : B2), j);
+            if (kRowStats && wave == 0) issue_stats(Bf == 0 ? S0 : (Bf == 1 ? S1 : S2), j);
+        };
+        // DMA operations per wave per stage: 4 tile chunks, plus the row statistics on wave 0
+        auto wait_one_stage_outstanding = [&]() {
+            if (kRowStats && wave == 0) {
+                if (kSecond) __builtin_amdgcn_s_waitcnt(0x0070 | 6); else __builtin_amdgcn_s_waitcnt(0x0070 | 5);
+            } else {
+                __builtin_amdgcn_s_waitcnt(0x0070 | 4);
+            }
+        };
+        auto run_stage = [&](auto BUF, int j) {
+            constexpr int Bf = decltype(BUF)::value;
+            const bool ahead = j + 2 < n_stages;
+            if (ahead) issue_stage(IntB<(Bf + 2) % 3>{}, j + 2);
+            if (wave_active) {
+                const char *At = Bf == 0 ? A0 : (Bf == 1 ? A1 : A2);
+                const char *Bt = Bf == 0 ? B0 : (Bf == 1 ? B1 : B2);
+                const char *St = Bf == 0 ? S0 : (Bf == 1 ? S1 : S2);
+                const int j0 = j * kBdBN;
+                const bool ragged = j0 + kBdBN > L;
+                run_block(At, Bt, St, 0, j0, ragged);
+                if (j0 + 32 < L) run_block(At, Bt, St, 1, j0, ragged);
+            }
+            asm volatile("" ::: "memory");
+            if (ahead) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        };
+
+        issue_stage(IntB<0>{}, 0);
+        if (n_stages > 1) issue_stage(IntB<1>{}, 1);
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks) {
+            asm volatile("" : "+v"(xreg[ks]));   // stationary-row loads complete here
+            if (kSecond) asm volatile("" : "+v"(yreg[ks]));
+        }
+        if (n_stages > 1) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);
+        __syncthreads();
+        {
+            int j = 0;
+            for (; j + 3 <= n_stages; j += 3) {
+                run_stage(IntB<0>{}, j);
+                run_stage(IntB<1>{}, j + 1);
+                run_stage(IntB<2>{}, j + 2);
+            }
+            if (j < n_stages) { run_stage(IntB<0>{}, j); ++j; }
+            if (j < n_stages) { run_stage(IntB<1>{}, j); ++j; }
+        }
+
+        if (i < L) {
+            __bf16 *grow = grad + (t.row0 + i) * row_stride + (int64_t)t.head * D;
+            const float out_scale = MODE == kModeDV ? 1.0f : scale;
+#pragma unroll
+            for (int db = 0; db < kDBlocks; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x4 x;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) x[e] = (__bf16)(acc[db][4 * g + e] * out_scale);
+                    *reinterpret_cast<bf16x4 *>(grow + db * 32 + g * 8 + half * 4) = x;
+                }
+        }
+    }
+}
+
+template <int MODE>
+static hipError_t launch_mode(const void *q, const void *k, const void *v, const void *dout, const float *lse,
+                              const float *delta, const int64_t *offsets, int B, int H, Schedule s, void *grad, int cus,
+                              hipStream_t stream) {
+    hipLaunchKernelGGL(bwd_bf16_dma_kernel<MODE>, dim3(persistent_grid<bwd_bf16_dma_kernel<MODE>>(kBdThreads, cus)),
+                       dim3(kBdThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,
+                       (const __bf16 *)dout, lse, delta, offsets, B, H, s, (__bf16 *)grad);
+    return hipGetLastError();
+}
+
+hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const void *v, const void *dout,
+                               const float *lse, const float *delta, const int64_t *offsets, int B, int H, int D,
+                               Schedule s, void *grad, int cus, hipStream_t stream) {
+    if (D != kBdD) return hipErrorInvalidValue;
+    switch (mode) {
+        case kModeDQ: return launch_mode<kModeDQ>(q, k, v, dout, lse, delta, offsets, B, H, s, grad, cus, stream);
+        case kModeDK: return launch_mode<kModeDK>(q, k, v, dout, lse, delta, offsets, B, H, s, grad, cus, stream);
+        case kModeDV: return launch_mode<kModeDV>(q, k, v, dout, lse, delta, offsets, B, H, s, grad, cus, stream);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace jfa

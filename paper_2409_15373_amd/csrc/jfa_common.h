@@ -151,6 +151,11 @@ hipError_t launch_bwd_f32(const float *q, const float *k, const float *v, const 
 hipError_t launch_delta(const void *out, const void *dout, const int64_t *offsets, int B, int H, int D, bool is_bf16,
                         float *delta, int cus, hipStream_t stream);
 
+// mode: 0 = dQ, 1 = dK, 2 = dV (D = 128 only; work items are blocks of kFwdWideBlockRows stationary rows)
+hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const void *v, const void *dout,
+                               const float *lse, const float *delta, const int64_t *offsets, int B, int H, int D,
+                               Schedule s, void *grad, int cus, hipStream_t stream);
+
 constexpr int kFwdBlockRows = 128;
 constexpr int kFwdWideBlockRows = 256;
 hipError_t launch_fwd_bf16_dma(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H,

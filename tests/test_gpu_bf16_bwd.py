@@ -42,6 +42,21 @@ def test_bf16_backward_small_ragged(oracle, D, H):
     gate_bf16("dv", f64(dv), rdv)
 
 
+def test_both_backward_paths_on_the_same_data(oracle):
+    """D = 128: max_len <= 256 runs the dQ + fused dK/dV kernels, max_len > 256 the three direct-to-LDS kernels."""
+    from paper_2409_15373_amd import binding
+    w = make_custom("both", [256, 130, 1, 77, 0, 200, 33], 2, 128, dtype="bf16", seed=21)
+    rdq, rdk, rdv, rdelta = oracle.backward(w.q, w.k, w.v, w.dout, w.offsets)
+    d = to_device(w)
+    for max_len in (256, 257):
+        out, lse = binding.jfa_forward(d["q"], d["k"], d["v"], d["offsets"], max_len)
+        dq, dk, dv, delta = binding.jfa_backward(d["q"], d["k"], d["v"], out, d["dout"], lse, d["offsets"], max_len)
+        torch.cuda.synchronize()
+        gate_bf16(f"dq(max_len={max_len})", f64(dq), rdq)
+        gate_bf16(f"dk(max_len={max_len})", f64(dk), rdk)
+        gate_bf16(f"dv(max_len={max_len})", f64(dv), rdv)
+
+
 def test_bf16_backward_length_one(oracle):
     w = make_custom("ones", [1] * 21, 2, 64, dtype="bf16", seed=7)
     dq, dk, dv, _ = gpu_forward_backward(w)
