@@ -134,7 +134,7 @@ void drop_timed() {
 
 // Forward variant: JFA_FWD_VARIANT=wide selects the experimental 64-queries-per-wave kernel (D = 128 only).
 enum FwdVariant { kNarrow = 0, kWide = 1, kDma = 2 };
-FwdVariant forward_variant(int64_t max_len, int D) {
+FwdVariant forward_variant(int64_t max_len, int D, int H) {
     static const int forced = [] {
         const char *v = getenv("JFA_FWD_VARIANT");
         if (v && !strcmp(v, "wide")) return (int)kWide;
@@ -142,7 +142,7 @@ FwdVariant forward_variant(int64_t max_len, int D) {
         if (v && !strcmp(v, "narrow")) return (int)kNarrow;
         return -1;
     }();
-    if (D != 128) return kNarrow;
+    if (D != 128 || (int64_t)H * D > (1 << 20)) return kNarrow;   // the direct-to-LDS kernels keep 32-bit row offsets
     if (forced >= 0) return (FwdVariant)forced;
     return max_len > 256 ? kDma : kNarrow;   // 256-query tiles only pay off when samples can be long
 }
@@ -268,7 +268,7 @@ int jfa_forward(const void *q, const void *k, const void *v, const int64_t *offs
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
-    const FwdVariant variant = forward_variant(max_len, D);
+    const FwdVariant variant = forward_variant(max_len, D, H);
     { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, variant == kNarrow ? jfa::kFwdBlockRows : jfa::kFwdWideBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
@@ -289,7 +289,7 @@ int jfa_backward(const void *q, const void *k, const void *v, const void *out, c
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
-    const bool dma = D == 128 && forward_variant(max_len, D) != kNarrow;   // long samples: direct-to-LDS kernels
+    const bool dma = D == 128 && forward_variant(max_len, D, H) != kNarrow;   // long samples: direct-to-LDS kernels
     { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, dma ? jfa::kFwdWideBlockRows : jfa::kBwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     { ScopedTimer tm("delta", s); e = jfa::launch_delta(out, dout, offsets, (int)B, H, D, true, delta, w.cus, s); }

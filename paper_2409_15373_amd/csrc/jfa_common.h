@@ -35,6 +35,7 @@ __device__ inline int64_t work_id(int y, int t) {
 struct WorkCursor {
     bool first = true;
     bool home_done = false;
+    int64_t next = -1;   // small problems: next statically assigned id
 };
 
 // Next work id for this workgroup, or -1 when nothing is left.  Called by one thread.
@@ -44,7 +45,14 @@ struct WorkCursor {
 //     static ones, hence the gridDim / 8 base; the grid is a multiple of 8).
 //   * Once the home queue is empty the workgroup looks at all eight counters with plain loads and only
 //     spends an atomic on a queue that still shows work.
+//   * Problems of at most four items per workgroup skip all of this (see below).
 __device__ inline int64_t next_work(int32_t *counters, WorkCursor &cur, int64_t total) {
+    // Small problems (at most four items per workgroup) are dealt round-robin with no atomics at all: the
+    // items are sorted longest-first, so the deal is even, and the claim traffic would dominate the run time.
+    if (total <= 4 * (int64_t)gridDim.x) {
+        cur.next = cur.next < 0 ? blockIdx.x : cur.next + gridDim.x;
+        return cur.next < total ? cur.next : -1;
+    }
     const int home = blockIdx.x % kXcds;
     const int base = gridDim.x / kXcds;
     if (cur.first) {

@@ -143,11 +143,7 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
         __syncthreads();
         int buf = 0;
         for (int j0 = 0; j0 < L; j0 += kFwdBN, buf ^= 1) {
-#ifdef JFA_EXP_NOSTAGE
-            const bool more = false;
-#else
             const bool more = j0 + kFwdBN < L;
-#endif
             if (more) prefetch(j0 + kFwdBN);
             if (wave_active) {
                 const char *kt = sm.k[buf] + koff;
@@ -186,11 +182,6 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
                 }
 
                 // ---- online softmax for this lane's query ----
-#ifdef JFA_EXP_NOSOFTMAX
-                float mx = m;
-                if (j0 == 0) m = 0.0f;
-                if (false) {
-#else
                 float mx = st[0][0];
 #pragma unroll
                 for (int mb = 0; mb < 2; ++mb)
@@ -198,7 +189,6 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
                     for (int e = 0; e < 16; ++e) mx = fmaxf(mx, st[mb][e]);
                 mx = pair_max(mx);
                 if (__builtin_amdgcn_ballot_w64(mx > m + tau) != 0) {
-#endif   // wave-uniform, rare after the first block
                     const float m_new = fmaxf(m, mx);
                     const float alpha = fast_exp2((m - m_new) * c);     // exp2(-inf) = 0 on the first block
                     m = m_new;
@@ -216,16 +206,10 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
                         bf16x2 pr;
-#ifdef JFA_EXP_NOSOFTMAX
-                        pr[0] = (__bf16)(st[g >> 1][8 * (g & 1) + 2 * e]);
-                        pr[1] = (__bf16)(st[g >> 1][8 * (g & 1) + 2 * e + 1]);
-                        lsum = mc;
-#else
                         pr[0] = (__bf16)fast_exp2(fmaf(st[g >> 1][8 * (g & 1) + 2 * e], c, -mc));
                         pr[1] = (__bf16)fast_exp2(fmaf(st[g >> 1][8 * (g & 1) + 2 * e + 1], c, -mc));
                         // row sum of the ROUNDED probabilities, the values the second product uses
                         lsum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lsum, false);
-#endif
                         pw[e] = __builtin_bit_cast(uint32_t, pr);
                     }
                     pb[g] = __builtin_bit_cast(bf16x8, pw);

@@ -170,15 +170,9 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     bf16x2 pr;
-#ifdef JFA_EXP_NOSOFTMAX
-                    pr[0] = (__bf16)(st[8 * ts + 2 * e]);
-                    pr[1] = (__bf16)(st[8 * ts + 2 * e + 1]);
-                    lsum = mc;
-#else
                     pr[0] = (__bf16)fast_exp2(fmaf(st[8 * ts + 2 * e], c, -mc));
                     pr[1] = (__bf16)fast_exp2(fmaf(st[8 * ts + 2 * e + 1], c, -mc));
                     lsum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lsum, false);
-#endif
                     pw[e] = __builtin_bit_cast(uint32_t, pr);
                 }
                 p[ts] = __builtin_bit_cast(bf16x8, pw);
@@ -270,22 +264,6 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         };
         auto run_stage = [&](auto BUF, auto RAGGED, int j) {
             constexpr int Bf = decltype(BUF)::value;
-#if defined(JFA_EXP_NOSTAGE)
-            if (wave_active) pipelined(BUF, RAGGED, j);
-#elif defined(JFA_EXP_NODMA)
-            if (wave_active) pipelined(BUF, RAGGED, j);
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-#elif defined(JFA_EXP_NOWAIT)
-            const bool ahead = j + 2 < n_stages;
-            if (ahead) issue_stage(IntC<(Bf + 2) % 3>{}, j + 2);
-            if (wave_active) pipelined(BUF, RAGGED, j);
-            asm volatile("" ::: "memory");
-            __builtin_amdgcn_s_waitcnt(0x0070 | 63 & 15 | 0xC000);
-            __builtin_amdgcn_s_barrier();
-            asm volatile("" ::: "memory");
-#else
             const bool ahead = j + 2 < n_stages;
             if (ahead) issue_stage(IntC<(Bf + 2) % 3>{}, j + 2);
             if (wave_active) pipelined(BUF, RAGGED, j);
@@ -294,7 +272,6 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             else __builtin_amdgcn_s_waitcnt(0x0070);                           // vmcnt(0) lgkmcnt(0)
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-#endif
         };
 
         if (tid == 0) restart = 0;

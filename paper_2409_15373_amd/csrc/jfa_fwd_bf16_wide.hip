@@ -186,15 +186,9 @@ __global__ __launch_bounds__(kWideThreads, 1) void fwd_bf16_wide_kernel(const __
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     bf16x2 pr;
-#ifdef JFA_EXP_NOSOFTMAX
-                    pr[0] = (__bf16)(st[8 * ts + 2 * e]);
-                    pr[1] = (__bf16)(st[8 * ts + 2 * e + 1]);
-                    sum = mc;
-#else
                     pr[0] = (__bf16)fast_exp2(fmaf(st[8 * ts + 2 * e], c, -mc));
                     pr[1] = (__bf16)fast_exp2(fmaf(st[8 * ts + 2 * e + 1], c, -mc));
                     sum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum, false);
-#endif
                     pw[e] = __builtin_bit_cast(uint32_t, pr);
                 }
                 pb[ts] = __builtin_bit_cast(bf16x8, pw);
@@ -349,9 +343,6 @@ __global__ __launch_bounds__(kWideThreads, 1) void fwd_bf16_wide_kernel(const __
         };
         auto run_stage = [&](auto BUF, auto RAGGED, int j) {
             constexpr int Bf = decltype(BUF)::value;
-#ifdef JFA_EXP_NOSTAGE
-            if (wave_active) pipelined(BUF, RAGGED, j);
-#else
             const bool ahead = j + 2 < n_stages;
             if (ahead) issue_stage(Int<(Bf + 2) % 3>{}, j + 2);
             if (wave_active) pipelined(BUF, RAGGED, j);
@@ -360,7 +351,6 @@ __global__ __launch_bounds__(kWideThreads, 1) void fwd_bf16_wide_kernel(const __
             else __builtin_amdgcn_s_waitcnt(0x0070);         // vmcnt(0) lgkmcnt(0)
             __builtin_amdgcn_s_barrier();
             asm volatile("" ::: "memory");
-#endif
         };
 
         if (tid == 0) restart = 0;
