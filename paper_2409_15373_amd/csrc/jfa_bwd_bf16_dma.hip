@@ -20,7 +20,6 @@
 namespace jfa {
 
 constexpr int kBdThreads = 512;
-constexpr int kBdWaves = kBdThreads / 64;
 constexpr int kBdBN = 64;             // streamed rows per LDS stage
 constexpr int kBdD = 128;
 constexpr int kBdTile = kBdBN * kBdD * 2;
@@ -68,7 +67,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
     __shared__ __attribute__((aligned(256))) char S0[512];   // per stage: lse[64], delta[64] of the streamed rows
     __shared__ __attribute__((aligned(256))) char S1[512];
     __shared__ __attribute__((aligned(256))) char S2[512];
-    __shared__ int64_t slot;
+    __shared__ WorkSlot slot;   // the NEXT work item, claimed and decoded while the current one starts up
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, half = lane >> 5;
@@ -96,13 +95,12 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
     const int pc = lane & 15;
 
     WorkCursor cursor;
+    if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor);
     for (;;) {
-        __syncthreads();
-        if (tid == 0) slot = next_work(s.counter, cursor, total);
-        __syncthreads();
-        const int64_t w = uniform64(slot);
-        if (w < 0) break;
-        const Work t = decode_work(s, offsets, B, H, w);
+        __syncthreads();   // the slot is written; the previous tile is finished
+        Work t;
+        if (!load_work(&slot, t)) break;
+        __syncthreads();   // every wave has read the slot before wave 0 refills it
         const int L = t.len;
         const int n_stages = (L + kBdBN - 1) / kBdBN;
         const int64_t head_off = t.row0 * row_stride + (int64_t)t.head * D;
@@ -260,6 +258,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
 
         issue_stage(IntB<0>{}, 0);
         if (n_stages > 1) issue_stage(IntB<1>{}, 1);
+        if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor);   // overlaps with the loads in flight
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) {
             asm volatile("" : "+v"(xreg[ks]));   // stationary-row loads complete here

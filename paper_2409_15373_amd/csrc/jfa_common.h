@@ -141,6 +141,72 @@ inline int persistent_grid(int threads, int cus) {
     return (grid + kXcds - 1) / kXcds * kXcds;  // next_work() relies on a multiple of 8
 }
 
+// A decoded work item parked in LDS for the whole workgroup.
+struct WorkSlot {
+    int valid;   // 0: nothing left
+    int sample, head, block, len;
+    int row0_lo, row0_hi;
+};
+
+// Largest p in [0, B) with tile_start[p] * H <= w, found by one wave: 64 probes per round instead of one.
+__device__ inline int find_position_wave(const int32_t *tile_start, int B, int H, int64_t w) {
+    const int lane = threadIdx.x & 63;
+    int lo = 0, hi = B;  // invariant: tile_start[lo]*H <= w < tile_start[hi]*H
+    while (hi - lo > 1) {
+        const int step = (hi - lo + 63) / 64;
+        const int idx = lo + (lane + 1) * step;
+        const bool ok = idx < hi && (int64_t)tile_start[idx] * H <= w;   // true for a prefix of the lanes
+        const int cnt = __popcll(__builtin_amdgcn_ballot_w64(ok));
+        lo += cnt * step;
+        hi = hi < lo + step ? hi : lo + step;
+    }
+    return lo;
+}
+
+// Claim the next work item and decode it into `slot`.  Called by every lane of ONE wave (the claim itself is
+// made by its lane 0, whose registers hold `cur`); meant to be issued right after a tile's first loads so
+// that its latency chain (atomic, search, offsets) overlaps with theirs.
+__device__ inline void claim_and_decode(WorkSlot *slot, const Schedule &s, const int64_t *offsets, int B, int H,
+                                        int64_t total, WorkCursor &cur) {
+    const int lane = threadIdx.x & 63;
+    int64_t w = -1;
+    if (lane == 0) w = next_work(s.counter, cur, total);
+    w = uniform64(w);
+    if (w < 0) {
+        if (lane == 0) slot->valid = 0;
+        return;
+    }
+    const int p = find_position_wave(s.tile_start, B, H, w);
+    const int t0 = s.tile_start[p];
+    const int n = s.tile_start[p + 1] - t0;
+    const int r = (int)(w - (int64_t)t0 * H);
+    const int sample = s.order[p];
+    const int64_t row0 = offsets[sample];
+    const int len = (int)(offsets[sample + 1] - row0);
+    if (lane == 0) {
+        slot->valid = 1;
+        slot->sample = sample;
+        slot->head = r / n;
+        slot->block = r - (r / n) * n;
+        slot->len = len;
+        slot->row0_lo = (int)(uint32_t)row0;
+        slot->row0_hi = (int)(uint32_t)((uint64_t)row0 >> 32);
+    }
+}
+
+// Read the parked work item into scalar registers; returns false when nothing is left.
+__device__ inline bool load_work(const WorkSlot *slot, Work &t) {
+    if (__builtin_amdgcn_readfirstlane(slot->valid) == 0) return false;
+    t.sample = __builtin_amdgcn_readfirstlane(slot->sample);
+    t.head = __builtin_amdgcn_readfirstlane(slot->head);
+    t.block = __builtin_amdgcn_readfirstlane(slot->block);
+    t.len = __builtin_amdgcn_readfirstlane(slot->len);
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane(slot->row0_lo);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane(slot->row0_hi);
+    t.row0 = (int64_t)(((uint64_t)hi << 32) | lo);
+    return true;
+}
+
 // ---- launchers (each enqueues on `stream` and returns the launch status; `cus` = compute units of the device) ----
 
 // Scheduler: fills order / tile_start for the given row-block size and zeroes `n_counters` counters.

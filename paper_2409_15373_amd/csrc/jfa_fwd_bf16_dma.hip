@@ -51,7 +51,7 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
     __shared__ __attribute__((aligned(1024))) char V0[kDmaTile];
     __shared__ __attribute__((aligned(1024))) char V1[kDmaTile];
     __shared__ __attribute__((aligned(1024))) char V2[kDmaTile];
-    __shared__ int64_t slot;
+    __shared__ WorkSlot slot;   // the NEXT work item, claimed and decoded while the current one starts up
     __shared__ int restart;   // set by a wave whose reference maximum went stale beyond repair
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -84,13 +84,12 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
     const int pc = lane & 15;
 
     WorkCursor cursor;
+    if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor);
     for (;;) {
-        __syncthreads();
-        if (tid == 0) slot = next_work(s.counter, cursor, total);
-        __syncthreads();
-        const int64_t w = uniform64(slot);
-        if (w < 0) break;
-        const Work t = decode_work(s, offsets, B, H, w);
+        __syncthreads();   // the slot is written; the previous tile is finished
+        Work t;
+        if (!load_work(&slot, t)) break;
+        __syncthreads();   // every wave has read the slot before wave 0 refills it
         const int L = t.len;
         const int n_stages = (L + kDmaBN - 1) / kDmaBN;
         const __bf16 *kbase = k + t.row0 * row_stride + (int64_t)t.head * D;
@@ -277,6 +276,7 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         if (tid == 0) restart = 0;
         issue_stage(IntC<0>{}, 0);
         if (n_stages > 1) issue_stage(IntC<1>{}, 1);
+        if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor);   // overlaps with the loads in flight
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qreg[ks]));   // Q loads complete here
         if (n_stages > 1) __builtin_amdgcn_s_waitcnt(0x0070 | kDmaOpsPerStage); else __builtin_amdgcn_s_waitcnt(0x0070);
