@@ -164,7 +164,8 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             for (int e = 0; e < 16; ++e) acc[db][e] = 0.0f;
 
         // ---- one stage: 64 streamed rows in two blocks of 32 ----
-        auto run_block = [&](const char *At, const char *Bt, const char *St, int mb, int j0, bool ragged) {
+        auto run_block = [&](auto RAGGED, const char *At, const char *Bt, const char *St, int mb, int j0) {
+            constexpr bool ragged = decltype(RAGGED)::value != 0;
             f32x16 sc, dp;
 #pragma unroll
             for (int e = 0; e < 16; ++e) { sc[e] = 0.0f; dp[e] = 0.0f; }
@@ -237,8 +238,9 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                 __builtin_amdgcn_s_waitcnt(0x0070 | 4);
             }
         };
-        auto run_stage = [&](auto BUF, int j) {
+        auto run_stage = [&](auto BUF, auto RAGGED, int j) {
             constexpr int Bf = decltype(BUF)::value;
+            constexpr bool ragged = decltype(RAGGED)::value != 0;   // only the sample's last stage can be
             const bool ahead = j + 2 < n_stages;
             if (ahead) issue_stage(IntB<(Bf + 2) % 3>{}, j + 2);
             if (wave_active) {
@@ -246,9 +248,8 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                 const char *Bt = Bf == 0 ? B0 : (Bf == 1 ? B1 : B2);
                 const char *St = Bf == 0 ? S0 : (Bf == 1 ? S1 : S2);
                 const int j0 = j * kBdBN;
-                const bool ragged = j0 + kBdBN > L;
-                run_block(At, Bt, St, 0, j0, ragged);
-                if (j0 + 32 < L) run_block(At, Bt, St, 1, j0, ragged);
+                run_block(RAGGED, At, Bt, St, 0, j0);
+                if (!ragged || j0 + 32 < L) run_block(RAGGED, At, Bt, St, 1, j0);
             }
             asm volatile("" ::: "memory");
             if (ahead) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);
@@ -267,14 +268,21 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         if (n_stages > 1) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);
         __syncthreads();
         {
+            const int n_full = L / kBdBN;   // stages with all 64 streamed rows valid; a ragged one may follow
             int j = 0;
-            for (; j + 3 <= n_stages; j += 3) {
-                run_stage(IntB<0>{}, j);
-                run_stage(IntB<1>{}, j + 1);
-                run_stage(IntB<2>{}, j + 2);
+            for (; j + 3 <= n_full; j += 3) {
+                run_stage(IntB<0>{}, IntB<0>{}, j);
+                run_stage(IntB<1>{}, IntB<0>{}, j + 1);
+                run_stage(IntB<2>{}, IntB<0>{}, j + 2);
             }
-            if (j < n_stages) { run_stage(IntB<0>{}, j); ++j; }
-            if (j < n_stages) { run_stage(IntB<1>{}, j); ++j; }
+            if (j < n_full) { run_stage(IntB<0>{}, IntB<0>{}, j); ++j; }
+            if (j < n_full) { run_stage(IntB<1>{}, IntB<0>{}, j); ++j; }
+            if (j < n_stages) {             // the ragged last stage, in buffer n_full % 3
+                const int r = n_full % 3;
+                if (r == 0) run_stage(IntB<0>{}, IntB<1>{}, j);
+                else if (r == 1) run_stage(IntB<1>{}, IntB<1>{}, j);
+                else run_stage(IntB<2>{}, IntB<1>{}, j);
+            }
         }
 
         if (i < L) {
