@@ -68,7 +68,7 @@ def main():
     out = torch.empty_like(q)
     lse = torch.empty((H, n), dtype=torch.float32, device="cuda")
     dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
-    delta = torch.empty((H, n), dtype=torch.float32, device="cuda")
+    delta = torch.empty((2, H, n), dtype=torch.float32, device="cuda")   # delta and the base-2 lse plane
 
     def forward():
         binding.jfa_forward(q, k, v, offsets, w.max_len, out=out, lse=lse)

@@ -70,15 +70,16 @@ int jfa_forward_f32(const float *q, const float *k, const float *v, const int64_
 /*
  * Backward, bf16 (Section 2.2 states that every jagged operator has a backward).
  * Inputs: q, k, v as in the forward; out and lse as produced by jfa_forward; dout bf16 [sum_B, H, D].
- * Outputs: dq, dk, dv bf16 [sum_B, H, D]; delta fp32 [H, sum_B] = rowsum(dout * out), a
- * caller-provided buffer that the call fills and then reads (it is an output, and the only
- * sum_B-sized scratch of the backward).
+ * Outputs: dq, dk, dv bf16 [sum_B, H, D]; delta fp32 [2, H, sum_B], a caller-provided buffer that the call
+ * fills and then reads: plane 0 is rowsum(dout * out) (an output), plane 1 is lse * log2(e), the log-sum-exp
+ * in the base-2 scale in which the kernels take exponentials (scratch).  These two planes are the only
+ * sum_B-sized scratch of the backward.
  */
 int jfa_backward(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
                  const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, void *dq, void *dk, void *dv,
                  float *delta, void *stream);
 
-/* Backward, fp32 end to end. */
+/* Backward, fp32 end to end.  Here delta is fp32 [H, sum_B] (one plane: rowsum(dout * out)). */
 int jfa_backward_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
                      const float *lse, const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, float *dq,
                      float *dk, float *dv, float *delta, void *stream);

@@ -115,17 +115,23 @@ def jfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, offsets: torc
 
 
 def jfa_backward(q, k, v, out, dout, lse, offsets, max_len: int, dq=None, dk=None, dv=None, delta=None):
-    """dq, dk, dv [sum_B, H, D] (dtype of q) and delta fp32 [H, sum_B]."""
+    """dq, dk, dv [sum_B, H, D] (dtype of q) and delta fp32 [H, sum_B].
+
+    The statistics buffer handed to the library is fp32 [H, sum_B] for fp32 inputs and fp32 [2, H, sum_B] for
+    bf16 inputs (plane 0: delta, plane 1: the library's base-2 copy of lse).  A caller-provided `delta` must
+    have that size and is returned as it is; otherwise one is allocated here and plane 0 is returned.
+    """
     sum_B, H, D = q.shape
     B = offsets.numel() - 1
     dq = torch.empty_like(q) if dq is None else dq
     dk = torch.empty_like(q) if dk is None else dk
     dv = torch.empty_like(q) if dv is None else dv
-    delta = torch.empty((H, sum_B), dtype=torch.float32, device=q.device) if delta is None else delta
+    planes = 2 if q.dtype == torch.bfloat16 else 1
+    stats = torch.empty((planes, H, sum_B), dtype=torch.float32, device=q.device) if delta is None else delta
     fn = _pick(q.dtype, "jfa_backward")
     _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(dout), _ptr(lse), _ptr(offsets), B, max_len, H, D,
-              _ptr(dq), _ptr(dk), _ptr(dv), _ptr(delta), _stream()))
-    return dq, dk, dv, delta
+              _ptr(dq), _ptr(dk), _ptr(dv), _ptr(stats), _stream()))
+    return dq, dk, dv, (stats[0] if delta is None else delta)
 
 
 def jfa_build_schedule(offsets: torch.Tensor, block_rows: int):

@@ -292,7 +292,7 @@ int jfa_backward(const void *q, const void *k, const void *v, const void *out, c
     const bool dma = D == 128 && forward_variant(max_len, D, H) != kNarrow;   // long samples: direct-to-LDS kernels
     { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, dma ? jfa::kFwdWideBlockRows : jfa::kBwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
-    { ScopedTimer tm("delta", s); e = jfa::launch_delta(out, dout, offsets, (int)B, H, D, true, delta, w.cus, s); }
+    { ScopedTimer tm("delta", s); e = jfa::launch_delta(out, dout, lse, offsets, (int)B, H, D, true, delta, w.cus, s); }
     if (e != hipSuccess) return hip_fail("delta kernel", e);
     if (dma) {
         static const char *const names[3] = {"dq_bf16_dma", "dk_bf16_dma", "dv_bf16_dma"};

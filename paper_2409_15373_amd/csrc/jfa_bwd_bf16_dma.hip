@@ -106,8 +106,9 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         const int64_t head_off = t.row0 * row_stride + (int64_t)t.head * D;
         const __bf16 *abase = (MODE == kModeDQ ? k : q) + head_off;
         const __bf16 *bbase = (MODE == kModeDQ ? v : dout) + head_off;
-        const float *lse_rows = lse + (int64_t)t.head * sum_B + t.row0;
+        // plane 0 of the statistics buffer: delta; plane 1: lse * log2(e), written by the delta kernel
         const float *delta_rows = delta + (int64_t)t.head * sum_B + t.row0;
+        const float *lse2_rows = delta + (int64_t)(H + t.head) * sum_B + t.row0;
 
         int offs[2];   // element offsets of this lane's two DMA chunks inside a full stage
 #pragma unroll
@@ -133,7 +134,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         auto issue_stats = [&](char *stats, int stage) {   // wave 0 only: lse and delta of the 64 streamed rows
             const int j0 = stage * kBdBN;
             const int j = j0 + lane < L ? j0 + lane : L - 1;
-            bd_dma4(lse_rows + j, stats);
+            bd_dma4(lse2_rows + j, stats);
             if (kSecond) bd_dma4(delta_rows + j, stats + 256);
         };
 
@@ -152,9 +153,18 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                 if (kSecond) yreg[ks] = *reinterpret_cast<const bf16x8 *>(ysrc + off + 16 * ks);
             }
         }
+        if (MODE == kModeDK) {   // V enters negated: the dP accumulator starts at delta and ends as delta - dP
+#pragma unroll
+            for (int ks = 0; ks < kKSteps; ++ks) {
+                u32x4 w = __builtin_bit_cast(u32x4, yreg[ks]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] ^= 0x80008000u;
+                yreg[ks] = __builtin_bit_cast(bf16x8, w);
+            }
+        }
         float lse2_lane = 0.0f, delta_lane = 0.0f;
         if (!kRowStats) {
-            lse2_lane = lse_rows[ic] * 1.4426950408889634f;
+            lse2_lane = lse2_rows[ic];
             delta_lane = delta_rows[ic];
         }
         f32x16 acc[kDBlocks];
@@ -169,6 +179,13 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             f32x16 sc, dp;
 #pragma unroll
             for (int e = 0; e < 16; ++e) { sc[e] = 0.0f; dp[e] = 0.0f; }
+            if (MODE == kModeDK) {   // dP accumulator starts at the streamed rows' delta
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float4 d4 = *reinterpret_cast<const float4 *>(St + 256 + (mb * 32 + g * 8 + half * 4) * 4);
+                    dp[4 * g] = d4.x; dp[4 * g + 1] = d4.y; dp[4 * g + 2] = d4.z; dp[4 * g + 3] = d4.w;
+                }
+            }
             // operands are fetched four at a time to keep the register footprint at two waves per SIMD
 #pragma unroll
             for (int k4 = 0; k4 < kKSteps; k4 += 4) {
@@ -188,25 +205,21 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                     for (int u = 0; u < 4; ++u) dp = mfma_32x32x16(bop[u], yreg[k4 + u], dp);
                 }
             }
-            // P (and dS) for this lane's stationary row and its 16 streamed rows of the block
+            // P (and dS, up to the sign in the dK kernel) for this lane's stationary row and its 16 streamed rows
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                float lv[4], dl[4];
+                float lv[4];
                 if (kRowStats) {
                     const float4 l4 = *reinterpret_cast<const float4 *>(St + (mb * 32 + g * 8 + half * 4) * 4);
-                    lv[0] = l4.x * 1.4426950408889634f; lv[1] = l4.y * 1.4426950408889634f;
-                    lv[2] = l4.z * 1.4426950408889634f; lv[3] = l4.w * 1.4426950408889634f;
-                    if (kSecond) {
-                        const float4 d4 = *reinterpret_cast<const float4 *>(St + 256 + (mb * 32 + g * 8 + half * 4) * 4);
-                        dl[0] = d4.x; dl[1] = d4.y; dl[2] = d4.z; dl[3] = d4.w;
-                    }
+                    lv[0] = l4.x; lv[1] = l4.y; lv[2] = l4.z; lv[3] = l4.w;
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     float p = fast_exp2(fmaf(sc[4 * g + e], c, -(kRowStats ? lv[e] : lse2_lane)));
                     if (ragged && j0 + mb * 32 + g * 8 + half * 4 + e >= L) p = 0.0f;   // streamed rows past the end
                     sc[4 * g + e] = p;
-                    if (kSecond) dp[4 * g + e] = p * (dp[4 * g + e] - (kRowStats ? dl[e] : delta_lane));
+                    if (MODE == kModeDK) dp[4 * g + e] = p * dp[4 * g + e];                  // = -dS
+                    if (MODE == kModeDQ) dp[4 * g + e] = p * (dp[4 * g + e] - delta_lane);
                 }
             }
             // gradient accumulation: contraction over the 32 streamed rows in two steps of 16
@@ -287,7 +300,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
 
         if (i < L) {
             __bf16 *grow = grad + (t.row0 + i) * row_stride + (int64_t)t.head * D;
-            const float out_scale = MODE == kModeDV ? 1.0f : scale;
+            const float out_scale = MODE == kModeDV ? 1.0f : (MODE == kModeDK ? -scale : scale);
 #pragma unroll
             for (int db = 0; db < kDBlocks; ++db)
 #pragma unroll

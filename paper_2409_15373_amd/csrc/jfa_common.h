@@ -222,8 +222,8 @@ hipError_t launch_bwd_f32(const float *q, const float *k, const float *v, const 
                           Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int cus,
                           hipStream_t stream);
 // delta[h, row] = sum_d dout * out, for T = float or bf16 (is_bf16)
-hipError_t launch_delta(const void *out, const void *dout, const int64_t *offsets, int B, int H, int D, bool is_bf16,
-                        float *delta, int cus, hipStream_t stream);
+hipError_t launch_delta(const void *out, const void *dout, const float *lse, const int64_t *offsets, int B, int H,
+                        int D, bool is_bf16, float *delta, int cus, hipStream_t stream);
 
 // mode: 0 = dQ, 1 = dK, 2 = dV (D = 128 only; work items are blocks of kFwdWideBlockRows stationary rows)
 hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const void *v, const void *dout,

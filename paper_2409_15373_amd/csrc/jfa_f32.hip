@@ -213,8 +213,11 @@ __global__ __launch_bounds__(kThreads) void dkv_f32_kernel(const float *__restri
 }
 
 // delta[h, row] = sum_d dout[row, h, d] * out[row, h, d]; one group of D*sizeof(T)/16 lanes per (row, head).
+// With lse != nullptr the second plane of the buffer, delta[H + h, row], receives lse[h, row] * log2(e): the
+// log-sum-exp in the base-2 scale in which the bf16 backward kernels take their exponentials.
 template <bool kBf16>
 __global__ __launch_bounds__(256) void delta_kernel(const void *__restrict__ out, const void *__restrict__ dout,
+                                                    const float *__restrict__ lse,
                                                     const int64_t *__restrict__ offsets, int B, int H, int D,
                                                     float *__restrict__ delta) {
     const int64_t sum_B = offsets[B];
@@ -243,17 +246,19 @@ __global__ __launch_bounds__(256) void delta_kernel(const void *__restrict__ out
             const int64_t row = pair / H;
             const int h = (int)(pair - row * H);
             delta[(int64_t)h * sum_B + row] = acc;
+            if (lse != nullptr)
+                delta[(int64_t)(H + h) * sum_B + row] = lse[(int64_t)h * sum_B + row] * 1.4426950408889634f;
         }
     }
 }
 
-hipError_t launch_delta(const void *out, const void *dout, const int64_t *offsets, int B, int H, int D, bool is_bf16,
-                        float *delta, int cus, hipStream_t stream) {
+hipError_t launch_delta(const void *out, const void *dout, const float *lse, const int64_t *offsets, int B, int H,
+                        int D, bool is_bf16, float *delta, int cus, hipStream_t stream) {
     const int grid = cus * 8;
     if (is_bf16)
-        hipLaunchKernelGGL(delta_kernel<true>, dim3(grid), dim3(256), 0, stream, out, dout, offsets, B, H, D, delta);
+        hipLaunchKernelGGL(delta_kernel<true>, dim3(grid), dim3(256), 0, stream, out, dout, lse, offsets, B, H, D, delta);
     else
-        hipLaunchKernelGGL(delta_kernel<false>, dim3(grid), dim3(256), 0, stream, out, dout, offsets, B, H, D, delta);
+        hipLaunchKernelGGL(delta_kernel<false>, dim3(grid), dim3(256), 0, stream, out, dout, lse, offsets, B, H, D, delta);
     return hipGetLastError();
 }
 
@@ -276,7 +281,7 @@ hipError_t launch_bwd_f32(const float *q, const float *k, const float *v, const 
                           const float *lse, const int64_t *offsets, int B, int H, int D, Schedule s_dq,
                           Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int cus,
                           hipStream_t stream) {
-    hipError_t e = launch_delta(out, dout, offsets, B, H, D, false, delta, cus, stream);
+    hipError_t e = launch_delta(out, dout, nullptr, offsets, B, H, D, false, delta, cus, stream);
     if (e != hipSuccess) return e;
 #define JFA_CASE(DD)                                                                                               \
     case DD:                                                                                                       \

@@ -21,13 +21,13 @@ def gpu_forward_backward(w, pad_rows=2):
     lse = torch.full((w.H, n), 777.0, dtype=torch.float32, device="cuda")
     binding.jfa_forward(d["q"], d["k"], d["v"], d["offsets"], w.max_len, out=out, lse=lse)
     g = {x: torch.full_like(d["q"], 777.0) for x in ("dq", "dk", "dv")}
-    delta = torch.full((w.H, n), 777.0, dtype=torch.float32, device="cuda")
+    delta = torch.full((2, w.H, n), 777.0, dtype=torch.float32, device="cuda")   # plane 1: the library's base-2 lse
     binding.jfa_backward(d["q"], d["k"], d["v"], out, d["dout"], lse, d["offsets"], w.max_len,
                          dq=g["dq"], dk=g["dk"], dv=g["dv"], delta=delta)
     torch.cuda.synchronize()
     for name, t in g.items():
         assert (t[n:] == 777.0).all(), f"guard rows of {name} were written"
-    return g["dq"][:n], g["dk"][:n], g["dv"][:n], delta
+    return g["dq"][:n], g["dk"][:n], g["dv"][:n], delta[0]
 
 
 @pytest.mark.parametrize("D", [32, 64, 128])
