@@ -33,11 +33,16 @@ template <int N> using IntB = std::integral_constant<int, N>;
 // (4 consecutive rows hit 4 different 64-byte groups) on the 64-bank LDS.
 __device__ inline int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
 
-__device__ inline void bd_dma16(const __bf16 *src, char *lds_wave_base) {
+// Global -> LDS copies of 16 (or 4) bytes per lane: source = `base` (wave-uniform, scalar registers) +
+// `byte_offset` (per lane, unsigned 32 bits), destination = lds_wave_base + 16 (or 4) * lane.  The scalar-base
+// form needs no 64-bit vector address arithmetic and no vector registers for addresses.
+__device__ inline void bd_dma16(const void *base, uint32_t byte_offset, char *lds_wave_base) {
+    const char *src = reinterpret_cast<const char *>(base) + byte_offset;
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                      (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
 }
-__device__ inline void bd_dma4(const float *src, char *lds_wave_base) {
+__device__ inline void bd_dma4(const void *base, uint32_t byte_offset, char *lds_wave_base) {
+    const char *src = reinterpret_cast<const char *>(base) + byte_offset;
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                      (__attribute__((address_space(3))) void *)lds_wave_base, 4, 0, 0);
 }
@@ -56,6 +61,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
     constexpr int kDBlocks = D / 32;
     constexpr bool kRowStats = MODE != kModeDQ;   // lse / delta belong to the streamed rows
     constexpr bool kSecond = MODE != kModeDV;     // dP / dS are needed
+    constexpr bool kLeanAddresses = MODE != kModeDV;
     // streamed tile A: dQ: K, dK: Q, dV: Q      (16-byte row reads; transposing reads too unless dV)
     // streamed tile B: dQ: V, dK: dO, dV: dO    (16-byte row reads; dV: transposing reads only)
     __shared__ __attribute__((aligned(1024))) char A0[kBdTile];
@@ -91,9 +97,6 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             for (int db = 0; db < kDBlocks; ++db)
                 taddr[h2][db] = (r + 8 * h2) * 256 + (((db * 4 + chunk_in_group) ^ swz(r + 8 * h2)) << 4) + byte_in_chunk;
     }
-    const int dma_row0 = 8 * wave + (lane >> 4);
-    const int pc = lane & 15;
-
     WorkCursor cursor;
     if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor);
     for (;;) {
@@ -110,32 +113,37 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         const float *delta_rows = delta + (int64_t)t.head * sum_B + t.row0;
         const float *lse2_rows = delta + (int64_t)(H + t.head) * sum_B + t.row0;
 
-        int offs[2];   // element offsets of this lane's two DMA chunks inside a full stage
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int r = dma_row0 + 4 * u;
-            offs[u] = r * (int)row_stride + ((pc ^ swz(r)) << 3);
-        }
+        // The per-lane byte offsets of the two DMA chunks of a stage are rebuilt from the thread id at every
+        // issue (a handful of VALU operations per stage) instead of living in registers across the stage: values
+        // used once per stage are the first the register allocator spills, and a reload from scratch memory
+        // would wait on the vector-memory counter, i.e. on the very loads that are meant to stay in flight.
         auto issue = [&](const __bf16 *base, char *tile, int stage) {
             const int j0 = stage * kBdBN;
             const __bf16 *sbase = base + (int64_t)j0 * row_stride;
+            int t_opaque = tid;
+            asm volatile("" : "+v"(t_opaque));
+            const int dma_row0 = 8 * wave + ((t_opaque >> 4) & 3);
+            const int pc = t_opaque & 15;
             if (j0 + kBdBN <= L) {
 #pragma unroll
-                for (int u = 0; u < 2; ++u) bd_dma16(sbase + offs[u], tile + (8 * wave + 4 * u) * 256);
+                for (int u = 0; u < 2; ++u) {
+                    const int r = dma_row0 + 4 * u;
+                    bd_dma16(sbase, 2u * (uint32_t)(r * (int)row_stride + ((pc ^ swz(r)) << 3)), tile + (8 * wave + 4 * u) * 256);
+                }
             } else {
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     const int r = dma_row0 + 4 * u;
                     const int jr = j0 + r < L ? r : L - 1 - j0;   // rows past the end repeat the last row (masked later)
-                    bd_dma16(sbase + (int64_t)jr * row_stride + ((pc ^ swz(r)) << 3), tile + (8 * wave + 4 * u) * 256);
+                    bd_dma16(sbase, 2u * (uint32_t)(jr * (int)row_stride + ((pc ^ swz(r)) << 3)), tile + (8 * wave + 4 * u) * 256);
                 }
             }
         };
         auto issue_stats = [&](char *stats, int stage) {   // wave 0 only: lse and delta of the 64 streamed rows
             const int j0 = stage * kBdBN;
-            const int j = j0 + lane < L ? j0 + lane : L - 1;
-            bd_dma4(lse2_rows + j, stats);
-            if (kSecond) bd_dma4(delta_rows + j, stats + 256);
+            const uint32_t j = 4u * (uint32_t)(j0 + lane < L ? j0 + lane : L - 1);
+            bd_dma4(lse2_rows, j, stats);
+            if (kSecond) bd_dma4(delta_rows, j, stats + 256);
         };
 
         // ---- stationary rows: this lane's row as B operands ----
@@ -176,6 +184,27 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         // ---- one stage: 64 streamed rows in two blocks of 32 ----
         auto run_block = [&](auto RAGGED, const char *At, const char *Bt, const char *St, int mb, int j0) {
             constexpr bool ragged = decltype(RAGGED)::value != 0;
+            // LDS read addresses of this block.  The dQ and dK kernels have no registers to spare for sixteen
+            // loop-invariant addresses: they keep one of each kind and rebuild the others per block with one
+            // XOR each (the swizzle makes them differ by a constant bit pattern); the empty asm keeps the
+            // compiler from hoisting the rebuilt values back out of the loop.
+            int ra[kKSteps], ta[2][kDBlocks];
+            if (kLeanAddresses) {
+                int rb = raddr[0], tb = taddr[0][0];
+                asm volatile("" : "+v"(rb), "+v"(tb));
+#pragma unroll
+                for (int ks = 0; ks < kKSteps; ++ks) ra[ks] = rb ^ (ks << 5);
+#pragma unroll
+                for (int db = 0; db < kDBlocks; ++db) {
+                    ta[0][db] = tb ^ (db << 6);
+                    ta[1][db] = (tb ^ (db << 6) ^ 32) + 2048;
+                }
+            } else {
+#pragma unroll
+                for (int ks = 0; ks < kKSteps; ++ks) ra[ks] = raddr[ks];
+#pragma unroll
+                for (int db = 0; db < kDBlocks; ++db) { ta[0][db] = taddr[0][db]; ta[1][db] = taddr[1][db]; }
+            }
             f32x16 sc, dp;
 #pragma unroll
             for (int e = 0; e < 16; ++e) { sc[e] = 0.0f; dp[e] = 0.0f; }
@@ -191,7 +220,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             for (int k4 = 0; k4 < kKSteps; k4 += 4) {
                 bf16x8 aop[4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) aop[u] = lds_read_b128(At + mb * 32 * 256 + raddr[k4 + u]);
+                for (int u = 0; u < 4; ++u) aop[u] = lds_read_b128(At + mb * 32 * 256 + ra[k4 + u]);
 #pragma unroll
                 for (int u = 0; u < 4; ++u) sc = mfma_32x32x16(aop[u], xreg[k4 + u], sc);
             }
@@ -200,7 +229,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                 for (int k4 = 0; k4 < kKSteps; k4 += 4) {
                     bf16x8 bop[4];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) bop[u] = lds_read_b128(Bt + mb * 32 * 256 + raddr[k4 + u]);
+                    for (int u = 0; u < 4; ++u) bop[u] = lds_read_b128(Bt + mb * 32 * 256 + ra[k4 + u]);
 #pragma unroll
                     for (int u = 0; u < 4; ++u) dp = mfma_32x32x16(bop[u], yreg[k4 + u], dp);
                 }
@@ -231,7 +260,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
 #pragma unroll
                 for (int db = 0; db < kDBlocks; ++db) {
                     const char *base = Tt + (mb * 32 + ts * 16) * 256;
-                    top[db] = concat(lds_read_tr16(base + taddr[0][db]), lds_read_tr16(base + taddr[1][db]));
+                    top[db] = concat(lds_read_tr16(base + ta[0][db]), lds_read_tr16(base + ta[1][db]));
                 }
 #pragma unroll
                 for (int db = 0; db < kDBlocks; ++db) acc[db] = mfma_32x32x16(top[db], pb, acc[db]);
