@@ -64,19 +64,27 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
 
     // ---- LDS read addresses (bytes inside a tile), fixed for the whole kernel ----
     // K element (row r, 16-byte chunk ch) sits at r * 256 + ((ch ^ (r & 15)) << 4).
-    int kaddr[kKSteps];
-#pragma unroll
-    for (int ks = 0; ks < kKSteps; ++ks) kaddr[ks] = col * 256 + (((2 * ks + half) ^ (col & 15)) << 4);
+    // Only k-step 0's address is kept; step ks is at kaddr0 ^ (ks << 5) (the XOR swizzle makes the eight differ by
+    // a constant bit pattern).  Each stage rebuilds them: twelve loop-invariant addresses held in registers
+    // across the stage would be the first values the register allocator spills.
+    const int kaddr0 = col * 256 + ((half ^ (col & 15)) << 4);
     // V element (row r, 64-byte group g, byte b inside it) sits at r * 256 + ((g ^ (r & 3)) << 6) + b.
     // The transposing read of this lane: row = 4 half + (lane & 15) / 4 (+8 for the second half of the
     // operand, +16 per 16-key step), group = feature block db, bytes 32 * ((lane >> 4) & 1) + 8 * (lane & 3).
-    int vaddr[kDBlocks];
+    // Feature block db is at vaddr0 ^ (db << 6).
+    int vaddr0;
     {
         const int r = half * 4 + ((lane & 15) >> 2);
-#pragma unroll
-        for (int db = 0; db < kDBlocks; ++db)
-            vaddr[db] = r * 256 + ((db ^ (r & 3)) << 6) + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
+        vaddr0 = r * 256 + ((r & 3) << 6) + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
     }
+    auto lds_addresses = [&](int (&kaddr)[kKSteps], int (&vaddr)[kDBlocks]) {
+        int kb = kaddr0, vb = vaddr0;
+        asm volatile("" : "+v"(kb), "+v"(vb));   // keeps the rebuilt addresses from being hoisted out of the loop
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks) kaddr[ks] = kb ^ (ks << 5);
+#pragma unroll
+        for (int db = 0; db < kDBlocks; ++db) vaddr[db] = vb ^ (db << 6);
+    };
     // ---- DMA: one instruction moves 64 lanes x 16 bytes = 4 rows; wave w, instruction u fills rows 8 w + 4 u .. +3.
     // Lane l lands on physical chunk l & 15 of row 8 w + 4 u + (l >> 4) and so fetches the logical chunk that
     // the swizzle puts there.
@@ -139,6 +147,8 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
 
         // ---- helpers ----
         auto scores = [&](const char *tile, int mb, f32x16 &a) {
+            int kaddr[kKSteps], vaddr[kDBlocks];
+            lds_addresses(kaddr, vaddr);
 #pragma unroll
             for (int e = 0; e < 16; ++e) a[e] = 0.0f;
             bf16x8 kop[kKSteps];
@@ -147,7 +157,7 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
 #pragma unroll
             for (int ks = 0; ks < kKSteps; ++ks) a = mfma_32x32x16(kop[ks], qreg[ks], a);
         };
-        auto accumulate = [&](const char *tile, int mb, const bf16x8 (&p)[2]) {
+        auto accumulate = [&](const char *tile, int mb, const bf16x8 (&p)[2], const int (&vaddr)[kDBlocks]) {
 #pragma unroll
             for (int ts = 0; ts < 2; ++ts) {
                 bf16x8 vop[kDBlocks];
@@ -197,6 +207,8 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             const char *const Kc = P == 0 ? K0 : (P == 1 ? K1 : K2);
             const char *const Vc = P == 0 ? V0 : (P == 1 ? V1 : V2);
             const float mc = m * c;
+            int kaddr[kKSteps], vaddr[kDBlocks];
+            lds_addresses(kaddr, vaddr);
             f32x16 s0, s1;
             bf16x8 p0[2], p1[2];
             {
@@ -223,15 +235,17 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             }
             if (kRagged) mask(s0, j * kDmaBN);
             exps(s0, mc, p0);                          // ... VALU: exponentials of key block 0
-            accumulate(Vc, 0, p0);                     // matrix pipe: O^T += V^T P^T of key block 0 ...
+            accumulate(Vc, 0, p0, vaddr);              // matrix pipe: O^T += V^T P^T of key block 0 ...
             if (kRagged) mask(s1, j * kDmaBN + 32);
             exps(s1, mc, p1);                          // ... VALU: exponentials of key block 1
-            accumulate(Vc, 1, p1);
+            accumulate(Vc, 1, p1, vaddr);
         };
         // conservative(): maximum first, rescale, then exponentials; used when a tile had to be restarted
         auto conservative = [&](int bsel, int j) {
             const char *const Kc = kbuf(bsel);
             const char *const Vc = vbuf(bsel);
+            int kaddr[kKSteps], vaddr[kDBlocks];
+            lds_addresses(kaddr, vaddr);
             f32x16 s0, s1;
             bf16x8 p0[2], p1[2];
             scores(Kc, 0, s0);
@@ -247,9 +261,9 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
 #pragma unroll
                 for (int e = 0; e < 16; ++e) o[db][e] *= a;
             exps(s0, n * c, p0);
-            accumulate(Vc, 0, p0);
+            accumulate(Vc, 0, p0, vaddr);
             exps(s1, n * c, p1);
-            accumulate(Vc, 1, p1);
+            accumulate(Vc, 1, p1, vaddr);
         };
 
         // ---- pass 1: pipelined, three stage buffers, DMA two stages ahead ----
@@ -333,11 +347,19 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             }
         }
 
-        // ---- epilogue: normalise, store this lane's query row and its log-sum-exp ----
+        // ---- epilogue: normalise; transpose the wave's 32 x 128 output block through LDS so that it leaves as
+        // whole 256-byte rows (16 bytes per lane, four rows per store instruction) instead of 8-byte pieces of 32
+        // different rows per instruction; store the log-sum-exp ----
+        // The stage buffers are idle here (every wave is past the last stage's barrier and no DMA is in flight);
+        // wave w uses 8 KB of them: row r of its block at r * 256, 16-byte chunk ch at (ch ^ (r & 15)) << 4.
         const float l_total = pair_sum(lsum);
-        if (i < L) {
+        {
+            char *const region = (wave < 2 ? K0 : (wave < 4 ? K1 : (wave < 6 ? K2 : V0))) + (wave & 1) * 8192;
             const float inv = 1.0f / l_total;
-            __bf16 *orow = out + (t.row0 + i) * row_stride + (int64_t)t.head * D;
+            int lane_e = lane;   // every address below derives from this copy, which the compiler cannot see
+            asm volatile("" : "+v"(lane_e));   // through: otherwise they are computed at tile start and spilled
+            const int col_e = lane_e & 31, half_e = lane_e >> 5;
+            const int wbase = col_e * 256 + ((half_e * 8) ^ ((col_e & 15) << 4));
 #pragma unroll
             for (int db = 0; db < kDBlocks; ++db)
 #pragma unroll
@@ -345,11 +367,21 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
                     bf16x4 x;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) x[e] = (__bf16)(o[db][4 * g + e] * inv);
-                    *reinterpret_cast<bf16x4 *>(orow + db * 32 + g * 8 + half * 4) = x;
+                    *reinterpret_cast<bf16x4 *>(region + (wbase ^ (db * 64 + g * 16))) = x;
                 }
-            if (half == 0)
-                lse[(int64_t)t.head * sum_B + t.row0 + i] = (m * c + fast_log2(l_total)) * 0.6931471805599453f;
+            const int q0 = t.block * kFwdWideBlockRows + wave * 32;   // first query of this wave
+            __bf16 *const obase = out + (t.row0 + q0) * row_stride + (int64_t)t.head * D;
+            const uint32_t lane_off = 2u * (uint32_t)((lane_e >> 4) * (int)row_stride + (lane_e & 15) * 8);
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int r = it * 4 + (lane_e >> 4);
+                const u32x4 rowpiece = *reinterpret_cast<const u32x4 *>(region + r * 256 + (((lane_e & 15) ^ (r & 15)) << 4));
+                char *dst = reinterpret_cast<char *>(obase + (int64_t)it * 4 * row_stride) + lane_off;   // scalar base + 32-bit lane offset
+                if (q0 + r < L) *reinterpret_cast<u32x4 *>(dst) = rowpiece;
+            }
         }
+        if (i < L && half == 0)
+            lse[(int64_t)t.head * sum_B + t.row0 + i] = (m * c + fast_log2(l_total)) * 0.6931471805599453f;
     }
 }
 
