@@ -327,9 +327,16 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             }
         }
 
-        if (i < L) {
-            __bf16 *grow = grad + (t.row0 + i) * row_stride + (int64_t)t.head * D;
+        // ---- epilogue: scale, transpose the wave's 32 x 128 gradient block through LDS (the stage buffers are
+        // idle: every wave is past the last stage's barrier, no DMA in flight) and store whole 256-byte rows,
+        // four per store instruction.  Row r of the block sits at r * 256, 16-byte chunk ch at (ch ^ (r & 15)) << 4.
+        {
+            char *const region = (wave < 2 ? A0 : (wave < 4 ? A1 : (wave < 6 ? A2 : B0))) + (wave & 1) * 8192;
             const float out_scale = MODE == kModeDV ? 1.0f : (MODE == kModeDK ? -scale : scale);
+            int lane_e = lane;   // every address below derives from this copy, which the compiler cannot see
+            asm volatile("" : "+v"(lane_e));   // through: otherwise they are computed at tile start and spilled
+            const int col_e = lane_e & 31, half_e = lane_e >> 5;
+            const int wbase = col_e * 256 + ((half_e * 8) ^ ((col_e & 15) << 4));
 #pragma unroll
             for (int db = 0; db < kDBlocks; ++db)
 #pragma unroll
@@ -337,8 +344,18 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                     bf16x4 x;
 #pragma unroll
                     for (int e = 0; e < 4; ++e) x[e] = (__bf16)(acc[db][4 * g + e] * out_scale);
-                    *reinterpret_cast<bf16x4 *>(grow + db * 32 + g * 8 + half * 4) = x;
+                    *reinterpret_cast<bf16x4 *>(region + (wbase ^ (db * 64 + g * 16))) = x;
                 }
+            const int r0 = t.block * kFwdWideBlockRows + wave * 32;   // first stationary row of this wave
+            __bf16 *const gbase = grad + (t.row0 + r0) * row_stride + (int64_t)t.head * D;
+            const uint32_t lane_off = 2u * (uint32_t)((lane_e >> 4) * (int)row_stride + (lane_e & 15) * 8);
+#pragma unroll
+            for (int it = 0; it < 8; ++it) {
+                const int r = it * 4 + (lane_e >> 4);
+                const u32x4 rowpiece = *reinterpret_cast<const u32x4 *>(region + r * 256 + (((lane_e & 15) ^ (r & 15)) << 4));
+                char *dst = reinterpret_cast<char *>(gbase + (int64_t)it * 4 * row_stride) + lane_off;
+                if (r0 + r < L) *reinterpret_cast<u32x4 *>(dst) = rowpiece;
+            }
         }
     }
 }
