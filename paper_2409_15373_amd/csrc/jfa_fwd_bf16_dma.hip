@@ -29,7 +29,10 @@ constexpr int kDmaOpsPerStage = 2 * (kDmaBN / 4) / kDmaWaves;   // DMA instructi
 
 template <int N> using IntC = std::integral_constant<int, N>;
 
-__device__ inline void dma16b(const __bf16 *src, char *lds_wave_base) {
+// 16 bytes per lane from `base` (wave-uniform, kept in scalar registers) + `byte_offset` (per lane, unsigned
+// 32 bits) into LDS at lds_wave_base + 16 * lane: the scalar-base form needs no 64-bit vector arithmetic.
+__device__ inline void dma16b(const __bf16 *base, uint32_t byte_offset, char *lds_wave_base) {
+    const char *src = reinterpret_cast<const char *>(base) + byte_offset;
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                      (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
 }
@@ -103,27 +106,27 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         const __bf16 *kbase = k + t.row0 * row_stride + (int64_t)t.head * D;
         const __bf16 *vbase = v + t.row0 * row_stride + (int64_t)t.head * D;
 
-        // element offsets of this lane's DMA chunks inside a full stage (K and V differ in the swizzle)
-        int koffs[2], voffs[2];
+        // byte offsets of this lane's DMA chunks inside a full stage (K and V differ in the swizzle)
+        uint32_t koffs[2], voffs[2];
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int r = dma_row0 + 4 * u;
-            koffs[u] = r * (int)row_stride + ((pc ^ (r & 15)) << 3);
-            voffs[u] = r * (int)row_stride + ((pc ^ ((r & 3) << 2)) << 3);
+            koffs[u] = 2u * (uint32_t)(r * (int)row_stride + ((pc ^ (r & 15)) << 3));
+            voffs[u] = 2u * (uint32_t)(r * (int)row_stride + ((pc ^ ((r & 3) << 2)) << 3));
         }
         auto issue = [&](const __bf16 *base, char *tile, int stage, bool is_k) {
             const int j0 = stage * kDmaBN;
             const __bf16 *sbase = base + (int64_t)j0 * row_stride;
             if (j0 + kDmaBN <= L) {
 #pragma unroll
-                for (int u = 0; u < 2; ++u) dma16b(sbase + (is_k ? koffs[u] : voffs[u]), tile + (8 * wave + 4 * u) * 256);
+                for (int u = 0; u < 2; ++u) dma16b(sbase, is_k ? koffs[u] : voffs[u], tile + (8 * wave + 4 * u) * 256);
             } else {
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     const int r = dma_row0 + 4 * u;
                     const int ch = is_k ? (pc ^ (r & 15)) : (pc ^ ((r & 3) << 2));
                     const int jr = j0 + r < L ? r : L - 1 - j0;   // rows past the end repeat the last key (masked later)
-                    dma16b(sbase + (int64_t)jr * row_stride + ch * 8, tile + (8 * wave + 4 * u) * 256);
+                    dma16b(sbase, 2u * (uint32_t)(jr * (int)row_stride + ch * 8), tile + (8 * wave + 4 * u) * 256);
                 }
             }
         };
