@@ -147,6 +147,7 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
 #pragma unroll
             for (int e = 0; e < 16; ++e) o[db][e] = 0.0f;
         float m = -INFINITY, lsum = 0.0f;
+        f32x16 negm;   // minus the reference maximum, sixteen times: the addend the score products start from
 
         // ---- helpers ----
         auto scores = [&](const char *tile, int mb, f32x16 &a) {
@@ -175,15 +176,15 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         };
         // exponentials of one unit (32 keys x 32 queries) against the reference maximum; the rounded
         // probabilities are what the second product uses, so they are what the row sum adds up
-        auto exps = [&](const f32x16 &st, float mc, bf16x8 (&p)[2]) {
+        auto exps = [&](const f32x16 &st, float sub, bf16x8 (&p)[2]) {   // sub = 0 in the fast order (folded away)
 #pragma unroll
             for (int ts = 0; ts < 2; ++ts) {
                 u32x4 pw;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     bf16x2 pr;
-                    pr[0] = (__bf16)fast_exp2(fmaf(st[8 * ts + 2 * e], c, -mc));
-                    pr[1] = (__bf16)fast_exp2(fmaf(st[8 * ts + 2 * e + 1], c, -mc));
+                    pr[0] = (__bf16)fast_exp2(st[8 * ts + 2 * e] - sub);
+                    pr[1] = (__bf16)fast_exp2(st[8 * ts + 2 * e + 1] - sub);
                     lsum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lsum, false);
                     pw[e] = __builtin_bit_cast(uint32_t, pr);
                 }
@@ -191,9 +192,12 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             }
         };
         auto mask = [&](f32x16 &st, int key0) {   // keys past the end of the sample
+            int h = half;
+            asm volatile("" : "+v"(h));   // keeps the sixteen thresholds from being computed at tile start and spilled
+            const int lim = L - key0 - 4 * h;   // accumulator register e holds key key0 + (e / 4) * 8 + 4 * half + e % 4
 #pragma unroll
             for (int e = 0; e < 16; ++e)
-                if (key0 + acc_row(e, half) >= L) st[e] = -INFINITY;
+                if ((e >> 2) * 8 + (e & 3) >= lim) st[e] = -INFINITY;
         };
         auto unit_max = [&](const f32x16 &a, float mx) {
 #pragma unroll
@@ -209,10 +213,9 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             constexpr bool kRagged = decltype(RAGGED)::value != 0;
             const char *const Kc = P == 0 ? K0 : (P == 1 ? K1 : K2);
             const char *const Vc = P == 0 ? V0 : (P == 1 ? V1 : V2);
-            const float mc = m * c;
             int kaddr[kKSteps], vaddr[kDBlocks];
             lds_addresses(kaddr, vaddr);
-            f32x16 s0, s1;
+            f32x16 s0 = negm, s1 = negm;   // the score accumulators start at minus the reference: no subtraction later
             bf16x8 p0[2], p1[2];
             {
                 bf16x8 ka[kKSteps], kb[kKSteps];
@@ -220,8 +223,6 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
                 for (int ks = 0; ks < kKSteps; ++ks) ka[ks] = lds_read_b128(Kc + kaddr[ks]);
 #pragma unroll
                 for (int ks = 0; ks < kKSteps; ++ks) kb[ks] = lds_read_b128(Kc + 32 * 256 + kaddr[ks]);
-#pragma unroll
-                for (int e = 0; e < 16; ++e) { s0[e] = 0.0f; s1[e] = 0.0f; }
 #pragma unroll
                 for (int ks = 0; ks < kKSteps; ++ks) s0 = mfma_32x32x16(ka[ks], qreg[ks], s0);
 #pragma unroll
@@ -237,10 +238,10 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
                 __builtin_amdgcn_sched_group_barrier(0x008, kKSteps, 0);
             }
             if (kRagged) mask(s0, j * kDmaBN);
-            exps(s0, mc, p0);                          // ... VALU: exponentials of key block 0
+            exps(s0, 0.0f, p0);                        // ... VALU: exponentials of key block 0
             accumulate(Vc, 0, p0, vaddr);              // matrix pipe: O^T += V^T P^T of key block 0 ...
             if (kRagged) mask(s1, j * kDmaBN + 32);
-            exps(s1, mc, p1);                          // ... VALU: exponentials of key block 1
+            exps(s1, 0.0f, p1);                        // ... VALU: exponentials of key block 1
             accumulate(Vc, 1, p1, vaddr);
         };
         // conservative(): maximum first, rescale, then exponentials; used when a tile had to be restarted
@@ -256,16 +257,16 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             if ((j + 1) * kDmaBN > L) { mask(s0, j * kDmaBN); mask(s1, j * kDmaBN + 32); }
             const float x = pair_max(unit_max(s1, unit_max(s0, -INFINITY)));
             const float n = fmaxf(m, x);
-            const float a = fast_exp2((m - n) * c);   // 0 on the first stage
+            const float a = fast_exp2(m - n);   // 0 on the first stage
             m = n;
             lsum *= a;
 #pragma unroll
             for (int db = 0; db < kDBlocks; ++db)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) o[db][e] *= a;
-            exps(s0, n * c, p0);
+            exps(s0, n, p0);
             accumulate(Vc, 0, p0, vaddr);
-            exps(s1, n * c, p1);
+            exps(s1, n, p1);
             accumulate(Vc, 1, p1, vaddr);
         };
 
@@ -296,6 +297,12 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor);   // overlaps with the loads in flight
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qreg[ks]));   // Q loads complete here
+        // The softmax scale and the change to base-2 exponentials go into Q once per tile (q * log2(e) / sqrt(D),
+        // rounded to bf16 again): the matrix product then delivers scores that only need v_exp_f32.
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qreg[ks][e] = (__bf16)((float)qreg[ks][e] * c);
         if (n_stages > 1) __builtin_amdgcn_s_waitcnt(0x0070 | kDmaOpsPerStage); else __builtin_amdgcn_s_waitcnt(0x0070);
         __syncthreads();
         if (wave_active) {   // reference maximum: the first 32 keys
@@ -304,6 +311,9 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             if (L < 32) mask(s0, 0);
             m = pair_max(unit_max(s0, -INFINITY));
         }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) negm[e] = -m;
+        asm volatile("" : "+v"(negm));   // sixteen real registers: the matrix product reads its addend from them
         {
             const int n_full = L / kDmaBN;   // stages with all 64 keys valid; a ragged one may follow
             int j = 0;
@@ -384,7 +394,7 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             }
         }
         if (i < L && half == 0)
-            lse[(int64_t)t.head * sum_B + t.row0 + i] = (m * c + fast_log2(l_total)) * 0.6931471805599453f;
+            lse[(int64_t)t.head * sum_B + t.row0 + i] = (m + fast_log2(l_total)) * 0.6931471805599453f;
     }
 }
 
