@@ -109,7 +109,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         const int64_t head_off = t.row0 * row_stride + (int64_t)t.head * D;
         const __bf16 *abase = (MODE == kModeDQ ? k : q) + head_off;
         const __bf16 *bbase = (MODE == kModeDQ ? v : dout) + head_off;
-        // plane 0 of the statistics buffer: delta; plane 1: lse * log2(e), written by the delta kernel
+        // plane 0 of the statistics buffer: delta; plane 1: -lse * log2(e), written by the delta kernel
         const float *delta_rows = delta + (int64_t)t.head * sum_B + t.row0;
         const float *lse2_rows = delta + (int64_t)(H + t.head) * sum_B + t.row0;
 
@@ -170,9 +170,9 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                 yreg[ks] = __builtin_bit_cast(bf16x8, w);
             }
         }
-        float lse2_lane = 0.0f, delta_lane = 0.0f;
+        float neg_lse2_lane = 0.0f, delta_lane = 0.0f;
         if (!kRowStats) {
-            lse2_lane = lse2_rows[ic];
+            neg_lse2_lane = lse2_rows[ic];
             delta_lane = delta_rows[ic];
         }
         f32x16 acc[kDBlocks];
@@ -208,6 +208,13 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             f32x16 sc, dp;
 #pragma unroll
             for (int e = 0; e < 16; ++e) { sc[e] = 0.0f; dp[e] = 0.0f; }
+            if (kRowStats) {   // score accumulator starts at minus the streamed rows' base-2 lse: P = exp2(acc), no FMA
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float4 l4 = *reinterpret_cast<const float4 *>(St + (mb * 32 + g * 8 + half * 4) * 4);
+                    sc[4 * g] = l4.x; sc[4 * g + 1] = l4.y; sc[4 * g + 2] = l4.z; sc[4 * g + 3] = l4.w;
+                }
+            }
             if (MODE == kModeDK) {   // dP accumulator starts at the streamed rows' delta
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
@@ -237,14 +244,9 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             // P (and dS, up to the sign in the dK kernel) for this lane's stationary row and its 16 streamed rows
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                float lv[4];
-                if (kRowStats) {
-                    const float4 l4 = *reinterpret_cast<const float4 *>(St + (mb * 32 + g * 8 + half * 4) * 4);
-                    lv[0] = l4.x; lv[1] = l4.y; lv[2] = l4.z; lv[3] = l4.w;
-                }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    float p = fast_exp2(fmaf(sc[4 * g + e], c, -(kRowStats ? lv[e] : lse2_lane)));
+                    float p = fast_exp2(kRowStats ? sc[4 * g + e] : sc[4 * g + e] + neg_lse2_lane);
                     if (ragged && j0 + mb * 32 + g * 8 + half * 4 + e >= L) p = 0.0f;   // streamed rows past the end
                     sc[4 * g + e] = p;
                     if (MODE == kModeDK) dp[4 * g + e] = p * dp[4 * g + e];                  // = -dS
@@ -307,6 +309,12 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             asm volatile("" : "+v"(xreg[ks]));   // stationary-row loads complete here
             if (kSecond) asm volatile("" : "+v"(yreg[ks]));
         }
+        // The softmax scale and the change to base-2 exponentials go into the stationary operand of the score
+        // product once per tile (x * log2(e) / sqrt(D), rounded to bf16 again): scores then only need v_exp_f32.
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) xreg[ks][e] = (__bf16)((float)xreg[ks][e] * c);
         if (n_stages > 1) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);
         __syncthreads();
         {
