@@ -73,6 +73,10 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
     __shared__ __attribute__((aligned(256))) char S0[512];   // per stage: lse[64], delta[64] of the streamed rows
     __shared__ __attribute__((aligned(256))) char S1[512];
     __shared__ __attribute__((aligned(256))) char S2[512];
+    // dQ only: per lane, four copies each of minus the base-2 lse and minus delta of the lane's query.  The score
+    // and dP accumulators of every block start from these (four 16-byte LDS reads each, no VALU work, no registers
+    // held across the stage): P = exp2(acc) and dS = P * acc then cost one exponential and one multiply.
+    __shared__ float4 lane_init[MODE == kModeDQ ? kBdThreads * 2 : 1];
     __shared__ WorkSlot slot;   // the NEXT work item, claimed and decoded while the current one starts up
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -170,10 +174,11 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                 yreg[ks] = __builtin_bit_cast(bf16x8, w);
             }
         }
-        float neg_lse2_lane = 0.0f, delta_lane = 0.0f;
-        if (!kRowStats) {
-            neg_lse2_lane = lse2_rows[ic];
-            delta_lane = delta_rows[ic];
+        if (!kRowStats) {   // written and read by the same lane: no barrier needed
+            const float nl = lse2_rows[ic], nd = -delta_rows[ic];
+            float4 *mine = lane_init + wave * 128 + lane;                               // consecutive lanes, consecutive
+            mine[0] = make_float4(nl, nl, nl, nl);                                      // 16-byte slots: no bank conflicts
+            mine[64] = make_float4(nd, nd, nd, nd);
         }
         f32x16 acc[kDBlocks];
 #pragma unroll
@@ -215,6 +220,18 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                     sc[4 * g] = l4.x; sc[4 * g + 1] = l4.y; sc[4 * g + 2] = l4.z; sc[4 * g + 3] = l4.w;
                 }
             }
+            if (MODE == kModeDQ) {   // both accumulators start at this lane's query's statistics
+                int t_opaque = tid;
+                asm volatile("" : "+v"(t_opaque));   // the address is rebuilt here, not carried through the stage
+                int mine = (t_opaque >> 6) * 128 + (t_opaque & 63);   // index of this lane's first 16-byte slot
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    asm volatile("" : "+v"(mine));   // four separate loads: one load and twelve register copies would be VALU work
+                    const float4 l4 = lane_init[mine], d4 = lane_init[mine + 64];
+                    sc[4 * g] = l4.x; sc[4 * g + 1] = l4.y; sc[4 * g + 2] = l4.z; sc[4 * g + 3] = l4.w;
+                    dp[4 * g] = d4.x; dp[4 * g + 1] = d4.y; dp[4 * g + 2] = d4.z; dp[4 * g + 3] = d4.w;
+                }
+            }
             if (MODE == kModeDK) {   // dP accumulator starts at the streamed rows' delta
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
@@ -246,11 +263,11 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             for (int g = 0; g < 4; ++g) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    float p = fast_exp2(kRowStats ? sc[4 * g + e] : sc[4 * g + e] + neg_lse2_lane);
+                    float p = fast_exp2(sc[4 * g + e]);
                     if (ragged && j0 + mb * 32 + g * 8 + half * 4 + e >= L) p = 0.0f;   // streamed rows past the end
                     sc[4 * g + e] = p;
                     if (MODE == kModeDK) dp[4 * g + e] = p * dp[4 * g + e];                  // = -dS
-                    if (MODE == kModeDQ) dp[4 * g + e] = p * (dp[4 * g + e] - delta_lane);
+                    if (MODE == kModeDQ) dp[4 * g + e] = p * dp[4 * g + e];
                 }
             }
             // gradient accumulation: contraction over the 32 streamed rows in two steps of 16
