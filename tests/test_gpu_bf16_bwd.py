@@ -21,7 +21,7 @@ def gpu_forward_backward(w, pad_rows=2):
     lse = torch.full((w.H, n), 777.0, dtype=torch.float32, device="cuda")
     binding.jfa_forward(d["q"], d["k"], d["v"], d["offsets"], w.max_len, out=out, lse=lse)
     g = {x: torch.full_like(d["q"], 777.0) for x in ("dq", "dk", "dv")}
-    delta = torch.full((2, w.H, n), 777.0, dtype=torch.float32, device="cuda")   # plane 1: the library's base-2 lse
+    delta = torch.full((2, w.H, n), 777.0, dtype=torch.float32, device="cuda")   # plane 1: library scratch
     binding.jfa_backward(d["q"], d["k"], d["v"], out, d["dout"], lse, d["offsets"], w.max_len,
                          dq=g["dq"], dk=g["dk"], dv=g["dv"], delta=delta)
     torch.cuda.synchronize()
