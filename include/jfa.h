@@ -85,6 +85,30 @@ int jfa_backward_f32(const float *q, const float *k, const float *v, const float
                      float *dk, float *dv, float *delta, void *stream);
 
 /*
+ * Unfused jagged attention: the three separate jagged operators of the paper's Table 1 (a jagged x jagged product
+ * with a jagged square output, a softmax over that output, and its product with a jagged tensor), which write the
+ * score array to memory.  They are the baseline that Section 3 compares the fused kernel with, provided here
+ * so that the comparison can be run on the same GPU; jfa_forward is the operator to use.
+ *
+ *   sq_offsets  int64 [B+1] on the device: offsets of the jagged square array, sq[b] = sum of L_c^2 over c < b;
+ *               jfa_square_offsets fills it from offsets (one small kernel).
+ *   scores      fp32 [H, sq[B]] on the device, caller-provided (the caller sizes it from its lengths): element
+ *               (h, b, i, j) at h * sq[B] + sq[b] + i * L_b + j.
+ *   jfa_unfused_scores   scores = q k^T / sqrt(D) per sample and head (q, k bf16 [sum_B, H, D]).
+ *   jfa_unfused_softmax  row softmax of every L_b x L_b block, in place.
+ *   jfa_unfused_apply    out = P v per sample and head (v, out bf16 [sum_B, H, D]); P is rounded to bf16 for
+ *                        the matrix product, as in the fused kernel.
+ * Errors, streams and ownership as for the calls above.
+ */
+int jfa_square_offsets(const int64_t *offsets, int64_t B, int64_t *sq_offsets, void *stream);
+int jfa_unfused_scores(const void *q, const void *k, const int64_t *offsets, const int64_t *sq_offsets, int64_t B,
+                       int64_t max_len, int H, int D, float *scores, void *stream);
+int jfa_unfused_softmax(const int64_t *offsets, const int64_t *sq_offsets, int64_t B, int64_t max_len, int H,
+                        float *scores, void *stream);
+int jfa_unfused_apply(const float *probs, const void *v, const int64_t *offsets, const int64_t *sq_offsets, int64_t B,
+                      int64_t max_len, int H, int D, void *out, void *stream);
+
+/*
  * The offsets-driven work schedule on its own (the first kernel of every call above), for
  * inspection and tests.  For row blocks of block_rows rows it writes, on the device,
  *   order      int32 [B]    sample ids, samples with more row blocks first

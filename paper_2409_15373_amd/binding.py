@@ -25,7 +25,7 @@ JFA_ERR_HIP = -4
 EXPORTS = (
     "jfa_forward", "jfa_forward_f32", "jfa_backward", "jfa_backward_f32", "jfa_build_schedule",
     "jfa_check_offsets", "jfa_workspace_bytes", "jfa_last_error", "jfa_version", "jfa_timing_enable",
-    "jfa_timing_read",
+    "jfa_timing_read", "jfa_square_offsets", "jfa_unfused_scores", "jfa_unfused_softmax", "jfa_unfused_apply",
 )
 
 
@@ -68,6 +68,14 @@ def load() -> ctypes.CDLL:
     lib.jfa_timing_read.restype = i32
     lib.jfa_timing_read.argtypes = [i32, ctypes.POINTER(ctypes.c_char_p), ctypes.POINTER(ctypes.c_float),
                                     ctypes.POINTER(ctypes.c_int)]
+    lib.jfa_square_offsets.restype = i32
+    lib.jfa_square_offsets.argtypes = [vp, i64, vp, vp]
+    lib.jfa_unfused_scores.restype = i32
+    lib.jfa_unfused_scores.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, vp]
+    lib.jfa_unfused_softmax.restype = i32
+    lib.jfa_unfused_softmax.argtypes = [vp, vp, i64, i64, i32, vp, vp]
+    lib.jfa_unfused_apply.restype = i32
+    lib.jfa_unfused_apply.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, vp]
     _lib = lib
     return lib
 
@@ -141,6 +149,38 @@ def jfa_build_schedule(offsets: torch.Tensor, block_rows: int):
     tile_start = torch.empty((B + 1,), dtype=torch.int32, device=offsets.device)
     _check(load().jfa_build_schedule(_ptr(offsets), B, block_rows, _ptr(order), _ptr(tile_start), _stream()))
     return order[:B], tile_start
+
+
+def jfa_square_offsets(offsets: torch.Tensor) -> torch.Tensor:
+    """int64 [B+1] on the device: offsets of the jagged square array, sq[b] = sum of L_c^2 over c < b."""
+    B = offsets.numel() - 1
+    sq = torch.empty((B + 1,), dtype=torch.int64, device=offsets.device)
+    _check(load().jfa_square_offsets(_ptr(offsets), B, _ptr(sq), _stream()))
+    return sq
+
+
+def jfa_unfused_scores(q, k, offsets, sq_offsets, max_len: int, scores: torch.Tensor):
+    """scores fp32 [H, sq[B]] = q k^T / sqrt(D) per sample and head (the caller sizes `scores` from its lengths)."""
+    _, H, D = q.shape
+    _check(load().jfa_unfused_scores(_ptr(q), _ptr(k), _ptr(offsets), _ptr(sq_offsets), offsets.numel() - 1, max_len,
+                                     H, D, _ptr(scores), _stream()))
+    return scores
+
+
+def jfa_unfused_softmax(offsets, sq_offsets, max_len: int, H: int, scores: torch.Tensor):
+    """Row softmax of every L_b x L_b block of `scores`, in place."""
+    _check(load().jfa_unfused_softmax(_ptr(offsets), _ptr(sq_offsets), offsets.numel() - 1, max_len, H,
+                                      _ptr(scores), _stream()))
+    return scores
+
+
+def jfa_unfused_apply(probs, v, offsets, sq_offsets, max_len: int, out: Optional[torch.Tensor] = None):
+    """out [sum_B, H, D] (bf16) = P v per sample and head."""
+    _, H, D = v.shape
+    out = torch.empty_like(v) if out is None else out
+    _check(load().jfa_unfused_apply(_ptr(probs), _ptr(v), _ptr(offsets), _ptr(sq_offsets), offsets.numel() - 1,
+                                    max_len, H, D, _ptr(out), _stream()))
+    return out
 
 
 def jfa_check_offsets(offsets: torch.Tensor, max_len: int) -> int:

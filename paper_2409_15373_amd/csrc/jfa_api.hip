@@ -313,4 +313,71 @@ int jfa_backward(const void *q, const void *k, const void *v, const void *out, c
     return JFA_OK;
 }
 
+// ---- unfused jagged attention (paper Table 1): the baseline of Section 3 ----
+
+int jfa_square_offsets(const int64_t *offsets, int64_t B, int64_t *sq_offsets, void *stream) {
+    if (B < 0 || B >= (int64_t)1 << 30) return fail(JFA_ERR_INVALID_ARG, "jfa_square_offsets: bad B");
+    if (!offsets || !sq_offsets) return fail(JFA_ERR_INVALID_ARG, "jfa_square_offsets: null pointer");
+    hipError_t e = jfa::launch_square_offsets(offsets, (int)B, sq_offsets, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail("square offsets kernel", e);
+    return JFA_OK;
+}
+
+namespace {
+// Common front end of the three operators: validation, work table, schedule (row blocks of 128 queries).
+int unfused_begin(const char *who, int64_t B, int64_t max_len, int H, int D, const void *const *ptrs, int n_ptrs,
+                  const int64_t *offsets, hipStream_t s, Views *w, jfa::Schedule *sc) {
+    int st = check_common(who, B, max_len, H, D, ptrs, n_ptrs);
+    if (st != JFA_OK || B == 0) return st;
+    if ((st = get_table(B, s, w)) != JFA_OK) return st;
+    hipError_t e;
+    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, 128, w->order[0], w->tile_start[0], w->counters, jfa::kNumCounters, s); }
+    if (e != hipSuccess) return hip_fail("schedule kernel", e);
+    *sc = jfa::Schedule{w->order[0], w->tile_start[0], w->counters};
+    return JFA_OK;
+}
+}  // namespace
+
+int jfa_unfused_scores(const void *q, const void *k, const int64_t *offsets, const int64_t *sq_offsets, int64_t B,
+                       int64_t max_len, int H, int D, float *scores, void *stream) {
+    const void *ptrs[] = {q, k, offsets, sq_offsets, scores};
+    hipStream_t s = (hipStream_t)stream;
+    Views w;
+    jfa::Schedule sc;
+    int st = unfused_begin("jfa_unfused_scores", B, max_len, H, D, ptrs, 5, offsets, s, &w, &sc);
+    if (st != JFA_OK || B == 0) return st;
+    hipError_t e;
+    { ScopedTimer tm("unfused_scores", s); e = jfa::launch_unfused_scores(q, k, offsets, sq_offsets, (int)B, H, D, sc, scores, w.cus, s); }
+    if (e != hipSuccess) return hip_fail("unfused scores kernel", e);
+    return JFA_OK;
+}
+
+int jfa_unfused_softmax(const int64_t *offsets, const int64_t *sq_offsets, int64_t B, int64_t max_len, int H,
+                        float *scores, void *stream) {
+    const void *ptrs[] = {offsets, sq_offsets, scores};
+    hipStream_t s = (hipStream_t)stream;
+    Views w;
+    jfa::Schedule sc;
+    int st = unfused_begin("jfa_unfused_softmax", B, max_len, H, 128, ptrs, 3, offsets, s, &w, &sc);
+    if (st != JFA_OK || B == 0) return st;
+    hipError_t e;
+    { ScopedTimer tm("unfused_softmax", s); e = jfa::launch_unfused_softmax(offsets, sq_offsets, (int)B, H, sc, scores, w.cus, s); }
+    if (e != hipSuccess) return hip_fail("unfused softmax kernel", e);
+    return JFA_OK;
+}
+
+int jfa_unfused_apply(const float *probs, const void *v, const int64_t *offsets, const int64_t *sq_offsets, int64_t B,
+                      int64_t max_len, int H, int D, void *out, void *stream) {
+    const void *ptrs[] = {probs, v, offsets, sq_offsets, out};
+    hipStream_t s = (hipStream_t)stream;
+    Views w;
+    jfa::Schedule sc;
+    int st = unfused_begin("jfa_unfused_apply", B, max_len, H, D, ptrs, 5, offsets, s, &w, &sc);
+    if (st != JFA_OK || B == 0) return st;
+    hipError_t e;
+    { ScopedTimer tm("unfused_apply", s); e = jfa::launch_unfused_apply(probs, v, offsets, sq_offsets, (int)B, H, D, sc, out, w.cus, s); }
+    if (e != hipSuccess) return hip_fail("unfused apply kernel", e);
+    return JFA_OK;
+}
+
 }  // extern "C"

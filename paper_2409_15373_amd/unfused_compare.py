@@ -1,0 +1,105 @@
+#!/usr/bin/env python3
+"""Fused jagged flash attention versus the unfused jagged attention, forward, on the same GPU.
+
+    python -m paper_2409_15373_amd.unfused_compare [--workloads c2_geom_bf16,c3_zipf_bf16,...] [--reps N]
+
+The paper's Section 3 compares the fused kernel with "jagged attention": the three jagged operators of its
+Table 1 run one after another, with the L_b x L_b score blocks of every sample and head written to memory
+between them.  Both sides here are this library's own kernels (jfa_forward against jfa_unfused_scores ->
+jfa_unfused_softmax -> jfa_unfused_apply).  For each workload it reports microseconds per call of either side,
+the three operators' own durations (HIP events inside the library) with the rate at which each moves the
+score array (4 bytes per score: written once by scores, read and written by softmax, read by apply), and the
+extra device memory either side needs beyond q, k, v and out (Section 3's memory claim): the fp32 score array
+for the unfused path, the fp32 log-sum-exp rows for the fused one.
+Inputs are random normals of the workload's scale drawn on the device.  Prints one JSON line.
+"""
+import argparse
+import json
+import sys
+
+import numpy as np
+
+
+def _time(fn, reps):
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workloads", default="c2_geom_bf16,c3_zipf_bf16,c4_bimodal_bf16,c5_uniform_bf16")
+    ap.add_argument("--reps", type=int, default=5)
+    args = ap.parse_args()
+    import torch
+    from . import binding
+    from .synthetic import CONFIGS, lengths_for, offsets_from_lengths
+    binding.load()
+    assert torch.cuda.is_available(), "needs the GPU"
+    result = {"comparison": "fused jagged flash attention vs unfused jagged attention (scores, softmax, apply), forward",
+              "dtype": "bf16", "data": "synthetic", "workloads": {}}
+    for name in args.workloads.split(","):
+        c = CONFIGS[name]
+        H, D, max_len = c["H"], c["D"], c["max_len"]
+        L = lengths_for(c["lengths"], c["B"], max_len, np.random.Generator(np.random.PCG64(c["seed"])))
+        n = int(L.sum())
+        pairs = int((L.astype(np.int64) ** 2).sum())
+        off = torch.from_numpy(offsets_from_lengths(L)).cuda()
+        gen = torch.Generator(device="cuda").manual_seed(0)
+        mk = lambda s: (torch.randn(n, H, D, device="cuda", generator=gen) * s).bfloat16()
+        q, k, v = mk(c["sigma"]), mk(c["sigma"]), mk(1.0)
+        out, lse = torch.empty_like(q), torch.empty(H, n, device="cuda")
+        out_u = torch.empty_like(q)
+        sq = binding.jfa_square_offsets(off)
+        assert int(sq[-1].item()) == pairs
+        scores = torch.empty(H * pairs, dtype=torch.float32, device="cuda")
+
+        def fused():
+            binding.jfa_forward(q, k, v, off, max_len, out=out, lse=lse)
+
+        def unfused():
+            binding.jfa_unfused_scores(q, k, off, sq, max_len, scores)
+            binding.jfa_unfused_softmax(off, sq, max_len, H, scores)
+            binding.jfa_unfused_apply(scores, v, off, sq, max_len, out=out_u)
+
+        t_f = _time(fused, args.reps)
+        t_u = _time(unfused, args.reps)
+        binding.jfa_timing_enable(True)
+        binding.jfa_timing_read()
+        for _ in range(args.reps):
+            unfused()
+        torch.cuda.synchronize()
+        timers = binding.jfa_timing_read()
+        binding.jfa_timing_enable(False)
+        diff = (out.float() - out_u.float()).abs().max().item()
+        score_bytes = 4 * H * pairs
+        ops = {}
+        for op, passes in (("unfused_scores", 1), ("unfused_softmax", 2), ("unfused_apply", 1)):
+            ms, cnt = timers[op]
+            us = ms * 1e3 / cnt
+            ops[op] = {"us": round(us, 1), "score_array_GB_per_s": round(passes * score_bytes / (us * 1e-6) / 1e9, 1)}
+        result["workloads"][name] = {
+            "B": c["B"], "H": H, "D": D, "max_len": max_len, "rows": n, "score_pairs_per_head": pairs,
+            "fused_us": round(t_f, 1), "unfused_us": round(t_u, 1), "speedup": round(t_u / t_f, 2),
+            "operators": ops,
+            "fused_extra_bytes": 4 * H * n, "unfused_extra_bytes": score_bytes,
+            "qkvo_bytes": 4 * n * H * D * 2,
+            "memory_saving": round(1.0 - (4 * n * H * D * 2 + 4 * H * n) / (4 * n * H * D * 2 + score_bytes), 3),
+            "max_abs_difference_of_outputs": round(diff, 5),
+        }
+        print(f"[unfused_compare] {name}: fused {t_f:.1f} us, unfused {t_u:.1f} us ({t_u / t_f:.2f}x), "
+              f"score array {score_bytes / 1e9:.2f} GB", file=sys.stderr, flush=True)
+        del scores, q, k, v, out, out_u, lse
+        torch.cuda.empty_cache()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()
