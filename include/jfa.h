@@ -109,6 +109,23 @@ int jfa_unfused_apply(const float *probs, const void *v, const int64_t *offsets,
                       int64_t max_len, int H, int D, void *out, void *stream);
 
 /*
+ * Jagged <-> padded-dense conversion (paper Section 2.2: jagged tensors are padded where a dense operator
+ * needs them and the padding is stripped afterwards).  Rows are opaque: row_bytes is the size of one row of the
+ * jagged tensor (everything after its first dimension, e.g. H * D * 2 for bf16 [sum_B, H, D]), a multiple of 16.
+ *
+ *   jfa_jagged_to_dense  dense[b, i] = values[offsets[b] + i] for i < L_b, and for L_b <= i < max_len the row is
+ *                        filled with the 32-bit pad_pattern (a bf16 pad value twice, or an fp32 value's bits).
+ *                        values [sum_B, row_bytes] in, dense [B, max_len, row_bytes] out, both on the device.
+ *   jfa_dense_to_jagged  values[offsets[b] + i] = dense[b, i] for i < L_b; other bytes of `values` stay untouched.
+ * Precondition L_b <= max_len (jfa_check_offsets tells); longer samples are cut at max_len rows, never read or
+ * written out of bounds.  Pointers must be 16-byte aligned.  Errors, streams and ownership as for the calls above.
+ */
+int jfa_jagged_to_dense(const void *values, const int64_t *offsets, int64_t B, int64_t max_len, int64_t row_bytes,
+                        uint32_t pad_pattern, void *dense, void *stream);
+int jfa_dense_to_jagged(const void *dense, const int64_t *offsets, int64_t B, int64_t max_len, int64_t row_bytes,
+                        void *values, void *stream);
+
+/*
  * The offsets-driven work schedule on its own (the first kernel of every call above), for
  * inspection and tests.  For row blocks of block_rows rows it writes, on the device,
  *   order      int32 [B]    sample ids, samples with more row blocks first

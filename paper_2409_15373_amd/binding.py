@@ -26,6 +26,7 @@ EXPORTS = (
     "jfa_forward", "jfa_forward_f32", "jfa_backward", "jfa_backward_f32", "jfa_build_schedule",
     "jfa_check_offsets", "jfa_workspace_bytes", "jfa_last_error", "jfa_version", "jfa_timing_enable",
     "jfa_timing_read", "jfa_square_offsets", "jfa_unfused_scores", "jfa_unfused_softmax", "jfa_unfused_apply",
+    "jfa_jagged_to_dense", "jfa_dense_to_jagged",
 )
 
 
@@ -76,6 +77,10 @@ def load() -> ctypes.CDLL:
     lib.jfa_unfused_softmax.argtypes = [vp, vp, i64, i64, i32, vp, vp]
     lib.jfa_unfused_apply.restype = i32
     lib.jfa_unfused_apply.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, vp]
+    lib.jfa_jagged_to_dense.restype = i32
+    lib.jfa_jagged_to_dense.argtypes = [vp, vp, i64, i64, i64, ctypes.c_uint32, vp, vp]
+    lib.jfa_dense_to_jagged.restype = i32
+    lib.jfa_dense_to_jagged.argtypes = [vp, vp, i64, i64, i64, vp, vp]
     _lib = lib
     return lib
 
@@ -181,6 +186,44 @@ def jfa_unfused_apply(probs, v, offsets, sq_offsets, max_len: int, out: Optional
     _check(load().jfa_unfused_apply(_ptr(probs), _ptr(v), _ptr(offsets), _ptr(sq_offsets), offsets.numel() - 1,
                                     max_len, H, D, _ptr(out), _stream()))
     return out
+
+
+def _row_bytes(t: torch.Tensor, lead: int) -> int:
+    assert t.is_contiguous()
+    n = t.element_size()
+    for d in t.shape[lead:]:
+        n *= d
+    return n
+
+
+def _pad_pattern(dtype: torch.dtype, pad: float) -> int:
+    """The 32-bit pattern that fills padded rows: the pad value's bits, twice for 16-bit types."""
+    one = torch.tensor([pad], dtype=dtype)
+    if one.element_size() == 4:
+        return int(one.view(torch.int32).item()) & 0xFFFFFFFF
+    if one.element_size() == 2:
+        bits = int(one.view(torch.int16).item()) & 0xFFFF
+        return bits | (bits << 16)
+    raise ValueError(f"pad value for {dtype}: only 2- and 4-byte element types")
+
+
+def jfa_jagged_to_dense(values: torch.Tensor, offsets: torch.Tensor, max_len: int, pad: float = 0.0,
+                        dense: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """dense [B, max_len, ...] from values [sum_B, ...]: rows i >= L_b of each sample hold `pad`."""
+    B = offsets.numel() - 1
+    if dense is None:
+        dense = torch.empty((B, max_len) + tuple(values.shape[1:]), dtype=values.dtype, device=values.device)
+    _check(load().jfa_jagged_to_dense(_ptr(values), _ptr(offsets), B, max_len, _row_bytes(values, 1),
+                                      _pad_pattern(values.dtype, pad), _ptr(dense), _stream()))
+    return dense
+
+
+def jfa_dense_to_jagged(dense: torch.Tensor, offsets: torch.Tensor, values: torch.Tensor) -> torch.Tensor:
+    """values[offsets[b] + i] = dense[b, i] for i < L_b; `values` [sum_B, ...] is caller-provided (the host does not know sum_B)."""
+    B, max_len = dense.shape[0], dense.shape[1]
+    assert offsets.numel() - 1 == B and _row_bytes(dense, 2) == _row_bytes(values, 1)
+    _check(load().jfa_dense_to_jagged(_ptr(dense), _ptr(offsets), B, max_len, _row_bytes(dense, 2), _ptr(values), _stream()))
+    return values
 
 
 def jfa_check_offsets(offsets: torch.Tensor, max_len: int) -> int:

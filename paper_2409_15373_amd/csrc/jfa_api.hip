@@ -380,4 +380,36 @@ int jfa_unfused_apply(const float *probs, const void *v, const int64_t *offsets,
     return JFA_OK;
 }
 
+// ---- jagged <-> padded-dense conversion (paper Section 2.2) ----
+
+namespace {
+int convert(const char *who, bool to_dense, const void *src, void *dst, const int64_t *offsets, int64_t B,
+            int64_t max_len, int64_t row_bytes, uint32_t pad, hipStream_t s) {
+    if (B < 0 || B >= (int64_t)1 << 30) return fail(JFA_ERR_INVALID_ARG, "%s: bad B = %lld", who, (long long)B);
+    if (max_len < 0 || max_len >= (int64_t)1 << 30) return fail(JFA_ERR_INVALID_ARG, "%s: bad max_len = %lld", who, (long long)max_len);
+    if (row_bytes <= 0 || row_bytes % 16 != 0 || row_bytes > (int64_t)1 << 24)
+        return fail(JFA_ERR_UNSUPPORTED, "%s: row_bytes = %lld must be a positive multiple of 16, at most 2^24", who, (long long)row_bytes);
+    if (B == 0 || max_len == 0) return JFA_OK;
+    if (!src || !dst || !offsets) return fail(JFA_ERR_INVALID_ARG, "%s: null pointer", who);
+    if (misaligned(src) || misaligned(dst)) return fail(JFA_ERR_INVALID_ARG, "%s: tensors must be 16-byte aligned", who);
+    Views w;   // only the compute-unit count is used
+    int st = get_table(B, s, &w);
+    if (st != JFA_OK) return st;
+    hipError_t e;
+    { ScopedTimer tm(to_dense ? "jagged_to_dense" : "dense_to_jagged", s); e = jfa::launch_convert(to_dense, src, dst, offsets, (int)B, max_len, row_bytes / 16, pad, w.cus, s); }
+    if (e != hipSuccess) return hip_fail("conversion kernel", e);
+    return JFA_OK;
+}
+}  // namespace
+
+int jfa_jagged_to_dense(const void *values, const int64_t *offsets, int64_t B, int64_t max_len, int64_t row_bytes,
+                        uint32_t pad_pattern, void *dense, void *stream) {
+    return convert("jfa_jagged_to_dense", true, values, dense, offsets, B, max_len, row_bytes, pad_pattern, (hipStream_t)stream);
+}
+
+int jfa_dense_to_jagged(const void *dense, const int64_t *offsets, int64_t B, int64_t max_len, int64_t row_bytes,
+                        void *values, void *stream) {
+    return convert("jfa_dense_to_jagged", false, dense, values, offsets, B, max_len, row_bytes, 0, (hipStream_t)stream);
+}
+
 }  // extern "C"

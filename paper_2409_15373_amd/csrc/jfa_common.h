@@ -233,6 +233,8 @@ hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const voi
 constexpr int kFwdBlockRows = 128;
 constexpr int kFwdWideBlockRows = 256;
 // Unfused jagged attention (Table 1): offsets of the jagged square array, then the three operators.
+hipError_t launch_convert(bool to_dense, const void *src, void *dst, const int64_t *offsets, int B, int64_t max_len,
+                          int64_t row_chunks, uint32_t pad, int cus, hipStream_t stream);
 hipError_t launch_square_offsets(const int64_t *offsets, int B, int64_t *sq, hipStream_t stream);
 hipError_t launch_unfused_scores(const void *q, const void *k, const int64_t *offsets, const int64_t *sq, int B, int H,
                                  int D, Schedule s, float *scores, int cus, hipStream_t stream);
