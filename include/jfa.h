@@ -126,6 +126,29 @@ int jfa_dense_to_jagged(const void *dense, const int64_t *offsets, int64_t B, in
                         void *values, void *stream);
 
 /*
+ * The jagged feature operators of the paper's Table 1, on bf16 tensors with fp32 accumulation.  x is a jagged
+ * tensor [sum_B, D] with the same offsets array as above (s_b = offsets[b], L_b rows per sample); D and T are each
+ * one of 32, 64, 128; all tensors on the device, row-major contiguous, 16-byte aligned.
+ *
+ *   jfa_jagged_dense_bmm   x [sum_B, D] times w [B, D, T] -> out [sum_B, T]:  out[s_b + i, :] = x[s_b + i, :] w[b]
+ *   jfa_jagged_jagged_bmm  x [sum_B, D], y [sum_B, T] -> out [B, D, T]:  out[b] = sum over i < L_b of x[s_b + i, :]^T y[s_b + i, :]
+ *                          (a zero block for an empty sample).  It is the gradient of jagged_dense_bmm with respect
+ *                          to w; jagged_dense_bmm with w transposed is the gradient with respect to x.
+ *   jfa_jagged_softmax     x [sum_B, D] -> y [sum_B, D]: softmax along the rows of each sample, one column at a
+ *                          time:  y[s_b + i, d] = exp(x[s_b + i, d]) / sum over j < L_b of exp(x[s_b + j, d])
+ *   jfa_jagged_softmax_backward  y, dy [sum_B, D] -> dx = y (dy - sum over j < L_b of dy[s_b + j, :] y[s_b + j, :])
+ * Outputs are rounded to bf16 once, from fp32.  Rows at and past offsets[B] are neither read nor written.
+ * max_len is an upper bound on L_b as elsewhere.  Errors, streams and ownership as for the calls above.
+ */
+int jfa_jagged_dense_bmm(const void *x, const void *w, const int64_t *offsets, int64_t B, int64_t max_len, int D, int T,
+                         void *out, void *stream);
+int jfa_jagged_jagged_bmm(const void *x, const void *y, const int64_t *offsets, int64_t B, int64_t max_len, int D, int T,
+                          void *out, void *stream);
+int jfa_jagged_softmax(const void *x, const int64_t *offsets, int64_t B, int64_t max_len, int D, void *y, void *stream);
+int jfa_jagged_softmax_backward(const void *y, const void *dy, const int64_t *offsets, int64_t B, int64_t max_len, int D,
+                                void *dx, void *stream);
+
+/*
  * The offsets-driven work schedule on its own (the first kernel of every call above), for
  * inspection and tests.  For row blocks of block_rows rows it writes, on the device,
  *   order      int32 [B]    sample ids, samples with more row blocks first

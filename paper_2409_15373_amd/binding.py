@@ -26,7 +26,8 @@ EXPORTS = (
     "jfa_forward", "jfa_forward_f32", "jfa_backward", "jfa_backward_f32", "jfa_build_schedule",
     "jfa_check_offsets", "jfa_workspace_bytes", "jfa_last_error", "jfa_version", "jfa_timing_enable",
     "jfa_timing_read", "jfa_square_offsets", "jfa_unfused_scores", "jfa_unfused_softmax", "jfa_unfused_apply",
-    "jfa_jagged_to_dense", "jfa_dense_to_jagged",
+    "jfa_jagged_to_dense", "jfa_dense_to_jagged", "jfa_jagged_dense_bmm", "jfa_jagged_jagged_bmm",
+    "jfa_jagged_softmax", "jfa_jagged_softmax_backward",
 )
 
 
@@ -81,6 +82,14 @@ def load() -> ctypes.CDLL:
     lib.jfa_jagged_to_dense.argtypes = [vp, vp, i64, i64, i64, ctypes.c_uint32, vp, vp]
     lib.jfa_dense_to_jagged.restype = i32
     lib.jfa_dense_to_jagged.argtypes = [vp, vp, i64, i64, i64, vp, vp]
+    lib.jfa_jagged_dense_bmm.restype = i32
+    lib.jfa_jagged_dense_bmm.argtypes = [vp, vp, vp, i64, i64, i32, i32, vp, vp]
+    lib.jfa_jagged_jagged_bmm.restype = i32
+    lib.jfa_jagged_jagged_bmm.argtypes = [vp, vp, vp, i64, i64, i32, i32, vp, vp]
+    lib.jfa_jagged_softmax.restype = i32
+    lib.jfa_jagged_softmax.argtypes = [vp, vp, i64, i64, i32, vp, vp]
+    lib.jfa_jagged_softmax_backward.restype = i32
+    lib.jfa_jagged_softmax_backward.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp]
     _lib = lib
     return lib
 
@@ -224,6 +233,40 @@ def jfa_dense_to_jagged(dense: torch.Tensor, offsets: torch.Tensor, values: torc
     assert offsets.numel() - 1 == B and _row_bytes(dense, 2) == _row_bytes(values, 1)
     _check(load().jfa_dense_to_jagged(_ptr(dense), _ptr(offsets), B, max_len, _row_bytes(dense, 2), _ptr(values), _stream()))
     return values
+
+
+def jfa_jagged_dense_bmm(x: torch.Tensor, w: torch.Tensor, offsets: torch.Tensor, max_len: int,
+                         out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """out [sum_B, T] = x [sum_B, D] times w [B, D, T], sample by sample (bf16)."""
+    B, D, T = w.shape
+    assert offsets.numel() - 1 == B and x.shape[1] == D
+    out = torch.empty((x.shape[0], T), dtype=x.dtype, device=x.device) if out is None else out
+    _check(load().jfa_jagged_dense_bmm(_ptr(x), _ptr(w), _ptr(offsets), B, max_len, D, T, _ptr(out), _stream()))
+    return out
+
+
+def jfa_jagged_jagged_bmm(x: torch.Tensor, y: torch.Tensor, offsets: torch.Tensor, max_len: int,
+                          out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """out [B, D, T] = per-sample x^T y for x [sum_B, D], y [sum_B, T] (bf16)."""
+    B, D, T = offsets.numel() - 1, x.shape[1], y.shape[1]
+    out = torch.empty((B, D, T), dtype=x.dtype, device=x.device) if out is None else out
+    _check(load().jfa_jagged_jagged_bmm(_ptr(x), _ptr(y), _ptr(offsets), B, max_len, D, T, _ptr(out), _stream()))
+    return out
+
+
+def jfa_jagged_softmax(x: torch.Tensor, offsets: torch.Tensor, max_len: int, y: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Softmax along each sample's rows, per column, of x [sum_B, D] (bf16)."""
+    y = torch.empty_like(x) if y is None else y
+    _check(load().jfa_jagged_softmax(_ptr(x), _ptr(offsets), offsets.numel() - 1, max_len, x.shape[1], _ptr(y), _stream()))
+    return y
+
+
+def jfa_jagged_softmax_backward(y: torch.Tensor, dy: torch.Tensor, offsets: torch.Tensor, max_len: int,
+                                dx: Optional[torch.Tensor] = None) -> torch.Tensor:
+    dx = torch.empty_like(y) if dx is None else dx
+    _check(load().jfa_jagged_softmax_backward(_ptr(y), _ptr(dy), _ptr(offsets), offsets.numel() - 1, max_len, y.shape[1],
+                                              _ptr(dx), _stream()))
+    return dx
 
 
 def jfa_check_offsets(offsets: torch.Tensor, max_len: int) -> int:

@@ -94,6 +94,14 @@ __device__ inline int64_t uniform64(int64_t x) {
     return (int64_t)(((uint64_t)hi << 32) | lo);
 }
 
+// Next work id for the whole workgroup (thread 0 claims, `slot` in LDS hands it to the others), or -1.
+__device__ inline int64_t fetch_item(int32_t *counters, WorkCursor &cur, int64_t total, int64_t *slot) {
+    __syncthreads();
+    if (threadIdx.x == 0) *slot = next_work(counters, cur, total);
+    __syncthreads();
+    return uniform64(*slot);
+}
+
 // One decoded work item.
 struct Work {
     int sample;   // sample id b
@@ -233,6 +241,12 @@ hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const voi
 constexpr int kFwdBlockRows = 128;
 constexpr int kFwdWideBlockRows = 256;
 // Unfused jagged attention (Table 1): offsets of the jagged square array, then the three operators.
+hipError_t launch_jagged_dense_bmm(const void *x, const void *w, const int64_t *offsets, int B, int D, int T, Schedule s,
+                                   void *out, int cus, hipStream_t stream);
+hipError_t launch_jagged_jagged_bmm(const void *x, const void *y, const int64_t *offsets, int B, int D, int T, Schedule s,
+                                    void *out, int cus, hipStream_t stream);
+hipError_t launch_jagged_softmax(bool backward, const void *a, const void *b, const int64_t *offsets, int B, int D,
+                                 Schedule s, void *out, int cus, hipStream_t stream);
 hipError_t launch_convert(bool to_dense, const void *src, void *dst, const int64_t *offsets, int B, int64_t max_len,
                           int64_t row_chunks, uint32_t pad, int cus, hipStream_t stream);
 hipError_t launch_square_offsets(const int64_t *offsets, int B, int64_t *sq, hipStream_t stream);

@@ -44,13 +44,6 @@ __global__ __launch_bounds__(1024) void square_offsets_kernel(const int64_t *__r
     }
 }
 
-__device__ inline int64_t fetch_item(int32_t *counters, WorkCursor &cur, int64_t total, int64_t *slot) {
-    __syncthreads();
-    if (threadIdx.x == 0) *slot = next_work(counters, cur, total);
-    __syncthreads();
-    return uniform64(*slot);
-}
-
 // All three operators keep a key index on the lane axis wherever they touch the score array: one wave-wide access
 // covers 64 (or 2 x 32) consecutive keys of a row, so every load and store of the array is coalesced.
 
