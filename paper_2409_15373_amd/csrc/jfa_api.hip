@@ -418,16 +418,11 @@ namespace {
 bool dim_ok(int d) { return d == 32 || d == 64 || d == 128; }
 
 int feature_begin(const char *who, int64_t B, int64_t max_len, int D, int T, const void *const *ptrs, int n_ptrs,
-                  const int64_t *offsets, hipStream_t s, Views *w, jfa::Schedule *sc) {
+                  hipStream_t s, Views *w) {
     if (!dim_ok(T)) return fail(JFA_ERR_UNSUPPORTED, "%s: T = %d is not one of 32, 64, 128", who, T);
     int st = check_common(who, B, max_len, 1, D, ptrs, n_ptrs);
     if (st != JFA_OK || B == 0) return st;
-    if ((st = get_table(B, s, w)) != JFA_OK) return st;
-    hipError_t e;
-    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, 128, w->order[0], w->tile_start[0], w->counters, jfa::kNumCounters, s); }
-    if (e != hipSuccess) return hip_fail("schedule kernel", e);
-    *sc = jfa::Schedule{w->order[0], w->tile_start[0], w->counters};
-    return JFA_OK;
+    return get_table(B, s, w);   // for the work counter and the compute-unit count
 }
 }  // namespace
 
@@ -436,11 +431,10 @@ int jfa_jagged_dense_bmm(const void *x, const void *w, const int64_t *offsets, i
     const void *ptrs[] = {x, w, offsets, out};
     hipStream_t s = (hipStream_t)stream;
     Views v;
-    jfa::Schedule sc;
-    int st = feature_begin("jfa_jagged_dense_bmm", B, max_len, D, T, ptrs, 4, offsets, s, &v, &sc);
+    int st = feature_begin("jfa_jagged_dense_bmm", B, max_len, D, T, ptrs, 4, s, &v);
     if (st != JFA_OK || B == 0) return st;
     hipError_t e;
-    { ScopedTimer tm("jagged_dense_bmm", s); e = jfa::launch_jagged_dense_bmm(x, w, offsets, (int)B, D, T, sc, out, v.cus, s); }
+    { ScopedTimer tm("jagged_dense_bmm", s); e = jfa::launch_jagged_dense_bmm(x, w, offsets, (int)B, D, T, v.counters, out, v.cus, s); }
     if (e != hipSuccess) return hip_fail("jagged_dense_bmm kernel", e);
     return JFA_OK;
 }
@@ -450,11 +444,10 @@ int jfa_jagged_jagged_bmm(const void *x, const void *y, const int64_t *offsets, 
     const void *ptrs[] = {x, y, offsets, out};
     hipStream_t s = (hipStream_t)stream;
     Views v;
-    jfa::Schedule sc;
-    int st = feature_begin("jfa_jagged_jagged_bmm", B, max_len, D, T, ptrs, 4, offsets, s, &v, &sc);
+    int st = feature_begin("jfa_jagged_jagged_bmm", B, max_len, D, T, ptrs, 4, s, &v);
     if (st != JFA_OK || B == 0) return st;
     hipError_t e;
-    { ScopedTimer tm("jagged_jagged_bmm", s); e = jfa::launch_jagged_jagged_bmm(x, y, offsets, (int)B, D, T, sc, out, v.cus, s); }
+    { ScopedTimer tm("jagged_jagged_bmm", s); e = jfa::launch_jagged_jagged_bmm(x, y, offsets, (int)B, D, T, v.counters, out, v.cus, s); }
     if (e != hipSuccess) return hip_fail("jagged_jagged_bmm kernel", e);
     return JFA_OK;
 }
@@ -463,11 +456,10 @@ int jfa_jagged_softmax(const void *x, const int64_t *offsets, int64_t B, int64_t
     const void *ptrs[] = {x, offsets, y};
     hipStream_t s = (hipStream_t)stream;
     Views v;
-    jfa::Schedule sc;
-    int st = feature_begin("jfa_jagged_softmax", B, max_len, D, 32, ptrs, 3, offsets, s, &v, &sc);
+    int st = feature_begin("jfa_jagged_softmax", B, max_len, D, 32, ptrs, 3, s, &v);
     if (st != JFA_OK || B == 0) return st;
     hipError_t e;
-    { ScopedTimer tm("jagged_softmax", s); e = jfa::launch_jagged_softmax(false, x, nullptr, offsets, (int)B, D, sc, y, v.cus, s); }
+    { ScopedTimer tm("jagged_softmax", s); e = jfa::launch_jagged_softmax(false, x, nullptr, offsets, (int)B, D, v.counters, y, v.cus, s); }
     if (e != hipSuccess) return hip_fail("jagged_softmax kernel", e);
     return JFA_OK;
 }
@@ -477,11 +469,10 @@ int jfa_jagged_softmax_backward(const void *y, const void *dy, const int64_t *of
     const void *ptrs[] = {y, dy, offsets, dx};
     hipStream_t s = (hipStream_t)stream;
     Views v;
-    jfa::Schedule sc;
-    int st = feature_begin("jfa_jagged_softmax_backward", B, max_len, D, 32, ptrs, 4, offsets, s, &v, &sc);
+    int st = feature_begin("jfa_jagged_softmax_backward", B, max_len, D, 32, ptrs, 4, s, &v);
     if (st != JFA_OK || B == 0) return st;
     hipError_t e;
-    { ScopedTimer tm("jagged_softmax_bwd", s); e = jfa::launch_jagged_softmax(true, y, dy, offsets, (int)B, D, sc, dx, v.cus, s); }
+    { ScopedTimer tm("jagged_softmax_bwd", s); e = jfa::launch_jagged_softmax(true, y, dy, offsets, (int)B, D, v.counters, dx, v.cus, s); }
     if (e != hipSuccess) return hip_fail("jagged_softmax backward kernel", e);
     return JFA_OK;
 }

@@ -241,12 +241,12 @@ hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const voi
 constexpr int kFwdBlockRows = 128;
 constexpr int kFwdWideBlockRows = 256;
 // Unfused jagged attention (Table 1): offsets of the jagged square array, then the three operators.
-hipError_t launch_jagged_dense_bmm(const void *x, const void *w, const int64_t *offsets, int B, int D, int T, Schedule s,
-                                   void *out, int cus, hipStream_t stream);
-hipError_t launch_jagged_jagged_bmm(const void *x, const void *y, const int64_t *offsets, int B, int D, int T, Schedule s,
-                                    void *out, int cus, hipStream_t stream);
+hipError_t launch_jagged_dense_bmm(const void *x, const void *w, const int64_t *offsets, int B, int D, int T,
+                                   int32_t *counter, void *out, int cus, hipStream_t stream);
+hipError_t launch_jagged_jagged_bmm(const void *x, const void *y, const int64_t *offsets, int B, int D, int T,
+                                    int32_t *counter, void *out, int cus, hipStream_t stream);
 hipError_t launch_jagged_softmax(bool backward, const void *a, const void *b, const int64_t *offsets, int B, int D,
-                                 Schedule s, void *out, int cus, hipStream_t stream);
+                                 int32_t *counter, void *out, int cus, hipStream_t stream);
 hipError_t launch_convert(bool to_dense, const void *src, void *dst, const int64_t *offsets, int B, int64_t max_len,
                           int64_t row_chunks, uint32_t pad, int cus, hipStream_t stream);
 hipError_t launch_square_offsets(const int64_t *offsets, int B, int64_t *sq, hipStream_t stream);

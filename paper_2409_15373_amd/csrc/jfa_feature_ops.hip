@@ -32,7 +32,10 @@ __device__ inline bf16x8 tr_operand(const char *tile, int off, int step, int blo
     return concat(lds_read_tr16(p), lds_read_tr16(p + 8 * row_bytes));
 }
 
-// Per-sample work items handed out longest sample first: the first statically, the rest by one atomic each.
+// Per-sample work items in sample order: the first statically, the rest by one atomic each (dynamic claims even out
+// samples of different lengths; an offsets-sorted order would cost a scheduler launch that takes longer than it saves).
+__global__ void reset_counter_kernel(int32_t *counter) { if (threadIdx.x == 0) *counter = 0; }
+
 __device__ inline int claim_sample(int32_t *counter, int n_claimed, int *slot) {
     __syncthreads();
     if (threadIdx.x == 0) *slot = n_claimed == 0 ? (int)blockIdx.x : (int)gridDim.x + atomicAdd(counter, 1);
@@ -40,53 +43,61 @@ __device__ inline int claim_sample(int32_t *counter, int n_claimed, int *slot) {
     return __builtin_amdgcn_readfirstlane(*slot);
 }
 
-// ---- jagged_dense_bmm: out^T = w_b^T x^T on 128-row blocks ----
+// ---- jagged_dense_bmm: out^T = w_b^T x^T, one sample per workgroup step, 128 rows at a time ----
+// w_b goes to LDS once per sample.  Wave w owns rows 32 w .. 32 w + 31 of every 128-row block: its x rows and,
+// after the product, its output rows share one private LDS region.
 template <int D, int T>
 __global__ __launch_bounds__(kFoThreads) void jagged_dense_bmm_kernel(const __bf16 *__restrict__ x,
                                                                       const __bf16 *__restrict__ w,
                                                                       const int64_t *__restrict__ offsets, int B,
-                                                                      Schedule s, __bf16 *__restrict__ out) {
+                                                                      int32_t *__restrict__ counter, __bf16 *__restrict__ out) {
     constexpr int kKSteps = D / 16, kTBlocks = T / 32;
     constexpr int kXRow = D * 2 + 8;          // x rows: the 8-byte operand reads of 32 consecutive rows hit 32 different bank pairs
     constexpr int kWRow = tr_row_bytes(T);
     constexpr int kORow = T * 2 + 16;
-    __shared__ __attribute__((aligned(16))) char xt[kFoRows * kXRow];
+    constexpr int kRegion = 32 * (kXRow > kORow ? kXRow : kORow);   // one wave's rows, as input and then as output
+    __shared__ __attribute__((aligned(16))) char xt[4 * kRegion];
     __shared__ __attribute__((aligned(16))) char wt[D * kWRow];
-    __shared__ __attribute__((aligned(16))) char ot[4][32 * kORow];
-    __shared__ int64_t slot;
+    __shared__ int slot;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, half = lane >> 5;
     const int woff = tr_lane_offset(lane, kWRow);
-    const int64_t total = s.tile_start[B];
-    WorkCursor cursor;
-    for (;;) {
-        const int64_t item = fetch_item(s.counter, cursor, total, &slot);   // also: the previous item's LDS tiles are free
-        if (item < 0) break;
-        const Work t = decode_work(s, offsets, B, 1, item);
-        const int r0 = t.block * kFoRows;                   // first row of the block inside the sample
-        const int rows = t.len - r0 < kFoRows ? t.len - r0 : kFoRows;
-        {   // the block of x is rows * D * 2 contiguous bytes; rows past the sample's end become zeros
-            const u32x4 *src = reinterpret_cast<const u32x4 *>(x + (t.row0 + r0) * D);
-#pragma unroll
-            for (int u = 0; u < kFoRows * (D / 8) / kFoThreads; ++u) {
-                const int c = tid + kFoThreads * u, r = c / (D / 8), ch = c % (D / 8);
-                u32x4 v = {0, 0, 0, 0};
-                if (r < rows) v = src[c];
-                *reinterpret_cast<u32x2 *>(xt + r * kXRow + ch * 16) = u32x2{v[0], v[1]};
-                *reinterpret_cast<u32x2 *>(xt + r * kXRow + ch * 16 + 8) = u32x2{v[2], v[3]};
-            }
-            const u32x4 *wsrc = reinterpret_cast<const u32x4 *>(w + (int64_t)t.sample * D * T);
+    char *mine = xt + wave * kRegion;
+    for (int n_claimed = 0;; ++n_claimed) {
+        const int p = claim_sample(counter, n_claimed, &slot);   // also: the previous sample's LDS tiles are free
+        if (p >= B) break;
+        const int b = p;
+        const int64_t row0 = offsets[b];
+        const int L = (int)(offsets[b + 1] - row0);
+        if (L == 0) continue;
+        {
+            const u32x4 *wsrc = reinterpret_cast<const u32x4 *>(w + (int64_t)b * D * T);
             for (int c = tid; c < D * (T / 8); c += kFoThreads)
                 *reinterpret_cast<u32x4 *>(wt + (c / (T / 8)) * kWRow + (c % (T / 8)) * 16) = wsrc[c];
         }
-        __syncthreads();
-        if (wave * 32 < rows) {
+        for (int r0 = 0; r0 < L; r0 += kFoRows) {
+            if (r0) __syncthreads();   // every wave is done with the previous block's region
+            const int rows = L - r0 < kFoRows ? L - r0 : kFoRows;
+            {   // the block of x is rows * D * 2 contiguous bytes; rows past the sample's end become zeros
+                const u32x4 *src = reinterpret_cast<const u32x4 *>(x + (row0 + r0) * D);
+#pragma unroll
+                for (int u = 0; u < kFoRows * (D / 8) / kFoThreads; ++u) {
+                    const int c = tid + kFoThreads * u, r = c / (D / 8), ch = c % (D / 8);
+                    u32x4 v = {0, 0, 0, 0};
+                    if (r < rows) v = src[c];
+                    char *dst = xt + (r >> 5) * kRegion + (r & 31) * kXRow + ch * 16;
+                    *reinterpret_cast<u32x2 *>(dst) = u32x2{v[0], v[1]};
+                    *reinterpret_cast<u32x2 *>(dst + 8) = u32x2{v[2], v[3]};
+                }
+            }
+            __syncthreads();
+            if (wave * 32 >= rows) continue;
             f32x16 acc[kTBlocks];
 #pragma unroll
             for (int tb = 0; tb < kTBlocks; ++tb)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) acc[tb][e] = 0.0f;
-            const char *xrow = xt + (wave * 32 + col) * kXRow + half * 8;
+            const char *xrow = mine + col * kXRow + half * 8;
 #pragma unroll
             for (int ks = 0; ks < kKSteps; ++ks) {
                 // B operand = x^T: this lane's row, features 16 ks + 4 half + 0..3 and 16 ks + 8 + 4 half + 0..3
@@ -97,7 +108,8 @@ __global__ __launch_bounds__(kFoThreads) void jagged_dense_bmm_kernel(const __bf
                 for (int tb = 0; tb < kTBlocks; ++tb) acc[tb] = mfma_32x32x16(tr_operand(wt, woff, ks, tb, kWRow), xop, acc[tb]);
             }
             // register 4 g + e of block tb: output column 32 tb + 8 g + 4 half + e of this lane's row
-            char *mine = ot[wave];
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int tb = 0; tb < kTBlocks; ++tb)
 #pragma unroll
@@ -110,7 +122,7 @@ __global__ __launch_bounds__(kFoThreads) void jagged_dense_bmm_kernel(const __bf
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            u32x4 *dst = reinterpret_cast<u32x4 *>(out + (t.row0 + r0 + wave * 32) * T);   // the wave's 32 rows: one contiguous block
+            u32x4 *dst = reinterpret_cast<u32x4 *>(out + (row0 + r0 + wave * 32) * T);   // the wave's 32 rows: one contiguous block
             const int mine_rows = rows - wave * 32;
 #pragma unroll
             for (int u = 0; u < 32 * (T / 8) / 64; ++u) {
@@ -126,7 +138,7 @@ template <int D, int T>
 __global__ __launch_bounds__(kFoThreads) void jagged_jagged_bmm_kernel(const __bf16 *__restrict__ x,
                                                                        const __bf16 *__restrict__ y,
                                                                        const int64_t *__restrict__ offsets, int B,
-                                                                       Schedule s, __bf16 *__restrict__ out) {
+                                                                       int32_t *__restrict__ counter, __bf16 *__restrict__ out) {
     constexpr int kDBlocks = D / 32, kTBlocks = T / 32, kBlocks = kDBlocks * kTBlocks;
     constexpr int kMine = (kBlocks + 3) / 4;   // 32 x 32 output blocks per wave
     constexpr int kXRow = tr_row_bytes(D), kYRow = tr_row_bytes(T);
@@ -139,9 +151,9 @@ __global__ __launch_bounds__(kFoThreads) void jagged_jagged_bmm_kernel(const __b
     const int col = lane & 31, half = lane >> 5;
     const int xoff = tr_lane_offset(lane, kXRow), yoff = tr_lane_offset(lane, kYRow);
     for (int n_claimed = 0;; ++n_claimed) {
-        const int p = claim_sample(s.counter, n_claimed, &slot);   // also: the previous sample's LDS tiles are free
+        const int p = claim_sample(counter, n_claimed, &slot);   // also: the previous sample's LDS tiles are free
         if (p >= B) break;
-        const int b = s.order[p];
+        const int b = p;
         const int64_t row0 = offsets[b];
         const int L = (int)(offsets[b + 1] - row0);
         f32x16 acc[kMine];
@@ -149,24 +161,41 @@ __global__ __launch_bounds__(kFoThreads) void jagged_jagged_bmm_kernel(const __b
         for (int m = 0; m < kMine; ++m)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[m][e] = 0.0f;
-        for (int i0 = 0; i0 < L; i0 += 64) {
-            if (i0) __syncthreads();
+        // the next 64 rows of x and y are on their way into registers while the current ones are multiplied
+        constexpr int kXLoads = 64 * (D / 8) / kFoThreads, kYLoads = 64 * (T / 8) / kFoThreads;
+        u32x4 xpre[kXLoads], ypre[kYLoads];
+        auto load_rows = [&](int i0) {
             const int rows = L - i0 < 64 ? L - i0 : 64;
             const u32x4 *xsrc = reinterpret_cast<const u32x4 *>(x + (row0 + i0) * D);
             const u32x4 *ysrc = reinterpret_cast<const u32x4 *>(y + (row0 + i0) * T);
-            for (int c = tid; c < 64 * (D / 8); c += kFoThreads) {
-                const int r = c / (D / 8);
-                u32x4 v = {0, 0, 0, 0};
-                if (r < rows) v = xsrc[c];
-                *reinterpret_cast<u32x4 *>(xs + r * kXRow + (c % (D / 8)) * 16) = v;
+#pragma unroll
+            for (int u = 0; u < kXLoads; ++u) {
+                const int c = tid + kFoThreads * u;
+                xpre[u] = u32x4{0, 0, 0, 0};
+                if (c / (D / 8) < rows) xpre[u] = xsrc[c];
             }
-            for (int c = tid; c < 64 * (T / 8); c += kFoThreads) {
-                const int r = c / (T / 8);
-                u32x4 v = {0, 0, 0, 0};
-                if (r < rows) v = ysrc[c];
-                *reinterpret_cast<u32x4 *>(ys + r * kYRow + (c % (T / 8)) * 16) = v;
+#pragma unroll
+            for (int u = 0; u < kYLoads; ++u) {
+                const int c = tid + kFoThreads * u;
+                ypre[u] = u32x4{0, 0, 0, 0};
+                if (c / (T / 8) < rows) ypre[u] = ysrc[c];
+            }
+        };
+        if (L > 0) load_rows(0);
+        for (int i0 = 0; i0 < L; i0 += 64) {
+            if (i0) __syncthreads();
+#pragma unroll
+            for (int u = 0; u < kXLoads; ++u) {
+                const int c = tid + kFoThreads * u;
+                *reinterpret_cast<u32x4 *>(xs + (c / (D / 8)) * kXRow + (c % (D / 8)) * 16) = xpre[u];
+            }
+#pragma unroll
+            for (int u = 0; u < kYLoads; ++u) {
+                const int c = tid + kFoThreads * u;
+                *reinterpret_cast<u32x4 *>(ys + (c / (T / 8)) * kYRow + (c % (T / 8)) * 16) = ypre[u];
             }
             __syncthreads();
+            if (i0 + 64 < L) load_rows(i0 + 64);
 #pragma unroll
             for (int m = 0; m < kMine; ++m) {
                 const int blk = wave + 4 * m;   // block (db, tb) = (blk / kTBlocks, blk % kTBlocks)
@@ -209,17 +238,18 @@ template <int D, bool BACKWARD>
 __global__ __launch_bounds__(kFoThreads) void jagged_softmax_kernel(const __bf16 *__restrict__ a,   // x, or y for the backward
                                                                     const __bf16 *__restrict__ g,   // dy (backward only)
                                                                     const int64_t *__restrict__ offsets, int B,
-                                                                    Schedule s, __bf16 *__restrict__ out) {
+                                                                    int32_t *__restrict__ counter, __bf16 *__restrict__ out) {
     constexpr int kGroups = D / 8;                  // threads per row
     constexpr int kRowLanes = kFoThreads / kGroups;   // rows per sweep step
+    constexpr int kBatch = 4;                         // rows per thread in flight
     __shared__ float stat_m[4][D], stat_l[4][D];
     __shared__ int slot;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int cg = tid % kGroups, rl = tid / kGroups;
     for (int n_claimed = 0;; ++n_claimed) {
-        const int p = claim_sample(s.counter, n_claimed, &slot);   // also: the previous sample's statistics have been read
+        const int p = claim_sample(counter, n_claimed, &slot);   // also: the previous sample's statistics have been read
         if (p >= B) break;
-        const int b = s.order[p];
+        const int b = p;
         const int64_t row0 = offsets[b];
         const int L = (int)(offsets[b + 1] - row0);
         if (L == 0) continue;
@@ -228,20 +258,56 @@ __global__ __launch_bounds__(kFoThreads) void jagged_softmax_kernel(const __bf16
         float m[8], l[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) { m[e] = -INFINITY; l[e] = 0.0f; }
-        for (int i = rl; i < L; i += kRowLanes) {
-            const bf16x8 v = arow[(int64_t)i * kGroups];
-            if (BACKWARD) {
-                const bf16x8 d = grow[(int64_t)i * kGroups];
+        // Rows go through in batches of kBatch per thread, all of a batch's loads in flight together; the first
+        // batch stays in registers for the second sweep (samples of up to kBatch * kRowLanes rows are read once).
+        bf16x8 held[kBatch], held_g[BACKWARD ? kBatch : 1];
+        auto load_batch = [&](int i0, bf16x8 (&v)[kBatch], bf16x8 (&d)[BACKWARD ? kBatch : 1]) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) l[e] += (float)v[e] * (float)d[e];
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float xv = (float)v[e], mn = fmaxf(m[e], xv);
-                    l[e] = l[e] * __expf(m[e] - mn) + __expf(xv - mn);   // exp(-inf) = 0 on the first row
-                    m[e] = mn;
+            for (int u = 0; u < kBatch; ++u) {
+                const int i = i0 + u * kRowLanes;
+                if (i < L) {
+                    v[u] = arow[(int64_t)i * kGroups];
+                    if (BACKWARD) d[u] = grow[(int64_t)i * kGroups];
                 }
             }
+        };
+        auto gather = [&](int i0, const bf16x8 (&v)[kBatch], const bf16x8 (&d)[BACKWARD ? kBatch : 1]) {
+            if (BACKWARD) {
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    if (i0 + u * kRowLanes >= L) break;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) l[e] += (float)v[u][e] * (float)d[u][e];
+                }
+            } else {   // the batch's maximum first: one rescaling of the running sum per batch, one exponential per element
+                float bm[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) bm[e] = m[e];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    if (i0 + u * kRowLanes >= L) break;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) bm[e] = fmaxf(bm[e], (float)v[u][e]);
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    l[e] = m[e] == -INFINITY ? 0.0f : l[e] * __expf(m[e] - bm[e]);
+                    m[e] = bm[e];
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    if (i0 + u * kRowLanes >= L) break;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) l[e] += __expf((float)v[u][e] - bm[e]);
+                }
+            }
+        };
+        load_batch(rl, held, held_g);
+        gather(rl, held, held_g);
+        for (int i0 = rl + kBatch * kRowLanes; i0 < L; i0 += kBatch * kRowLanes) {
+            bf16x8 v[kBatch], d[BACKWARD ? kBatch : 1];
+            load_batch(i0, v, d);
+            gather(i0, v, d);
         }
         // combine the threads of a wave that share columns (lane bits above log2(kGroups)), then the four waves
 #pragma unroll
@@ -274,18 +340,27 @@ __global__ __launch_bounds__(kFoThreads) void jagged_softmax_kernel(const __bf16
             }
         }
         bf16x8 *orow = reinterpret_cast<bf16x8 *>(out + row0 * D) + cg;
-        for (int i = rl; i < L; i += kRowLanes) {
-            const bf16x8 v = arow[(int64_t)i * kGroups];
-            bf16x8 r;
-            if (BACKWARD) {
-                const bf16x8 d = grow[(int64_t)i * kGroups];
+        auto emit = [&](int i0, const bf16x8 (&v)[kBatch], const bf16x8 (&d)[BACKWARD ? kBatch : 1]) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) r[e] = (__bf16)((float)v[e] * ((float)d[e] - l[e]));
-            } else {
+            for (int u = 0; u < kBatch; ++u) {
+                const int i = i0 + u * kRowLanes;
+                if (i >= L) break;
+                bf16x8 r;
+                if (BACKWARD) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) r[e] = (__bf16)(__expf((float)v[e] - m[e]) * l[e]);
+                    for (int e = 0; e < 8; ++e) r[e] = (__bf16)((float)v[u][e] * ((float)d[u][e] - l[e]));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) r[e] = (__bf16)(__expf((float)v[u][e] - m[e]) * l[e]);
+                }
+                orow[(int64_t)i * kGroups] = r;
             }
-            orow[(int64_t)i * kGroups] = r;
+        };
+        emit(rl, held, held_g);
+        for (int i0 = rl + kBatch * kRowLanes; i0 < L; i0 += kBatch * kRowLanes) {
+            bf16x8 v[kBatch], d[BACKWARD ? kBatch : 1];
+            load_batch(i0, v, d);
+            emit(i0, v, d);
         }
     }
 }
@@ -303,23 +378,26 @@ __global__ __launch_bounds__(kFoThreads) void jagged_softmax_kernel(const __bf16
                            stream, __VA_ARGS__);                                                                 \
         break;
 
-hipError_t launch_jagged_dense_bmm(const void *x, const void *w, const int64_t *offsets, int B, int D, int T, Schedule s,
+hipError_t launch_jagged_dense_bmm(const void *x, const void *w, const int64_t *offsets, int B, int D, int T, int32_t *counter,
                                    void *out, int cus, hipStream_t stream) {
-    JFA_DT_CASES(jagged_dense_bmm_kernel, (const __bf16 *)x, (const __bf16 *)w, offsets, B, s, (__bf16 *)out)
+    hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, stream, counter);
+    JFA_DT_CASES(jagged_dense_bmm_kernel, (const __bf16 *)x, (const __bf16 *)w, offsets, B, counter, (__bf16 *)out)
     return hipGetLastError();
 }
 
-hipError_t launch_jagged_jagged_bmm(const void *x, const void *y, const int64_t *offsets, int B, int D, int T, Schedule s,
+hipError_t launch_jagged_jagged_bmm(const void *x, const void *y, const int64_t *offsets, int B, int D, int T, int32_t *counter,
                                     void *out, int cus, hipStream_t stream) {
-    JFA_DT_CASES(jagged_jagged_bmm_kernel, (const __bf16 *)x, (const __bf16 *)y, offsets, B, s, (__bf16 *)out)
+    hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, stream, counter);
+    JFA_DT_CASES(jagged_jagged_bmm_kernel, (const __bf16 *)x, (const __bf16 *)y, offsets, B, counter, (__bf16 *)out)
     return hipGetLastError();
 }
 #undef JFA_DT_CASE
 #undef JFA_DT_CASES
 
 template <int D>
-static hipError_t launch_softmax_d(bool backward, const __bf16 *a, const __bf16 *g, const int64_t *offsets, int B, Schedule s,
+static hipError_t launch_softmax_d(bool backward, const __bf16 *a, const __bf16 *g, const int64_t *offsets, int B, int32_t *s,
                                    __bf16 *out, int cus, hipStream_t stream) {
+    hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, stream, s);
     if (backward)
         hipLaunchKernelGGL((jagged_softmax_kernel<D, true>), dim3(persistent_grid<jagged_softmax_kernel<D, true>>(kFoThreads, cus)),
                            dim3(kFoThreads), 0, stream, a, g, offsets, B, s, out);
@@ -330,7 +408,7 @@ static hipError_t launch_softmax_d(bool backward, const __bf16 *a, const __bf16 
 }
 
 hipError_t launch_jagged_softmax(bool backward, const void *a, const void *g, const int64_t *offsets, int B, int D,
-                                 Schedule s, void *out, int cus, hipStream_t stream) {
+                                 int32_t *s, void *out, int cus, hipStream_t stream) {
     switch (D) {
         case 32: return launch_softmax_d<32>(backward, (const __bf16 *)a, (const __bf16 *)g, offsets, B, s, (__bf16 *)out, cus, stream);
         case 64: return launch_softmax_d<64>(backward, (const __bf16 *)a, (const __bf16 *)g, offsets, B, s, (__bf16 *)out, cus, stream);
