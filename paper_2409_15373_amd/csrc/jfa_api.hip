@@ -132,12 +132,12 @@ void drop_timed() {
     g_timed.clear();
 }
 
-// Forward variant: JFA_FWD_VARIANT=wide selects the experimental 64-queries-per-wave kernel (D = 128 only).
-enum FwdVariant { kNarrow = 0, kWide = 1, kDma = 2 };
+// Forward variant: the direct-to-LDS kernel for long samples at D = 128, the register-staged one otherwise;
+// JFA_FWD_VARIANT=dma / narrow forces one of them where both apply (for side-by-side measurements).
+enum FwdVariant { kNarrow = 0, kDma = 2 };
 FwdVariant forward_variant(int64_t max_len, int D, int H) {
     static const int forced = [] {
         const char *v = getenv("JFA_FWD_VARIANT");
-        if (v && !strcmp(v, "wide")) return (int)kWide;
         if (v && !strcmp(v, "dma")) return (int)kDma;
         if (v && !strcmp(v, "narrow")) return (int)kNarrow;
         return -1;
@@ -269,11 +269,10 @@ int jfa_forward(const void *q, const void *k, const void *v, const int64_t *offs
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
     const FwdVariant variant = forward_variant(max_len, D, H);
-    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, variant == kNarrow ? jfa::kFwdBlockRows : jfa::kFwdWideBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
+    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, variant == kNarrow ? jfa::kFwdBlockRows : jfa::kDmaBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
-    if (variant == kWide) { ScopedTimer tm("fwd_bf16_wide", s); e = jfa::launch_fwd_bf16_wide(q, k, v, offsets, (int)B, H, D, sc, out, lse, w.cus, s); }
-    else if (variant == kDma) { ScopedTimer tm("fwd_bf16_dma", s); e = jfa::launch_fwd_bf16_dma(q, k, v, offsets, (int)B, H, D, sc, out, lse, w.cus, s); }
+    if (variant == kDma) { ScopedTimer tm("fwd_bf16_dma", s); e = jfa::launch_fwd_bf16_dma(q, k, v, offsets, (int)B, H, D, sc, out, lse, w.cus, s); }
     else { ScopedTimer tm("fwd_bf16", s); e = jfa::launch_fwd_bf16(q, k, v, offsets, (int)B, H, D, sc, out, lse, w.cus, s); }
     if (e != hipSuccess) return hip_fail("bf16 forward kernel", e);
     return JFA_OK;
@@ -290,7 +289,7 @@ int jfa_backward(const void *q, const void *k, const void *v, const void *out, c
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
     const bool dma = D == 128 && forward_variant(max_len, D, H) != kNarrow;   // long samples: direct-to-LDS kernels
-    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, dma ? jfa::kFwdWideBlockRows : jfa::kBwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
+    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, dma ? jfa::kDmaBlockRows : jfa::kBwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     { ScopedTimer tm("delta", s); e = jfa::launch_delta(out, dout, lse, offsets, (int)B, H, D, true, delta, w.cus, s); }
     if (e != hipSuccess) return hip_fail("delta kernel", e);

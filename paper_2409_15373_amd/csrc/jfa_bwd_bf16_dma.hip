@@ -151,9 +151,9 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         };
 
         // ---- stationary rows: this lane's row as B operands ----
-        const int i = t.block * kFwdWideBlockRows + wave * 32 + col;
+        const int i = t.block * kDmaBlockRows + wave * 32 + col;
         const int ic = i < L ? i : L - 1;
-        const bool wave_active = t.block * kFwdWideBlockRows + wave * 32 < L;
+        const bool wave_active = t.block * kDmaBlockRows + wave * 32 < L;
         bf16x8 xreg[kKSteps], yreg[kKSteps];   // dQ: Q, dO rows   dK: K, V rows   dV: K rows
         {
             const int64_t off = (t.row0 + ic) * row_stride + (int64_t)t.head * D + 8 * half;
@@ -371,7 +371,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                     for (int e = 0; e < 4; ++e) x[e] = (__bf16)(acc[db][4 * g + e] * out_scale);
                     *reinterpret_cast<bf16x4 *>(region + (wbase ^ (db * 64 + g * 16))) = x;
                 }
-            const int r0 = t.block * kFwdWideBlockRows + wave * 32;   // first stationary row of this wave
+            const int r0 = t.block * kDmaBlockRows + wave * 32;   // first stationary row of this wave
             __bf16 *const gbase = grad + (t.row0 + r0) * row_stride + (int64_t)t.head * D;
             const uint32_t lane_off = 2u * (uint32_t)((lane_e >> 4) * (int)row_stride + (lane_e & 15) * 8);
 #pragma unroll

@@ -222,6 +222,7 @@ hipError_t launch_schedule(const int64_t *offsets, int B, int block_rows, int32_
                            int32_t *counters, int n_counters, hipStream_t stream);
 hipError_t launch_check_offsets(const int64_t *offsets, int B, int64_t max_len, int *flags, hipStream_t stream);
 
+// fp32 path
 constexpr int kF32BlockRows = 64;
 hipError_t launch_fwd_f32(const float *q, const float *k, const float *v, const int64_t *offsets, int B, int H, int D,
                           Schedule s, float *out, float *lse, int cus, hipStream_t stream);
@@ -233,33 +234,8 @@ hipError_t launch_bwd_f32(const float *q, const float *k, const float *v, const 
 hipError_t launch_delta(const void *out, const void *dout, const float *lse, const int64_t *offsets, int B, int H,
                         int D, bool is_bf16, float *delta, int cus, hipStream_t stream);
 
-// mode: 0 = dQ, 1 = dK, 2 = dV (D = 128 only; work items are blocks of kFwdWideBlockRows stationary rows)
-hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const void *v, const void *dout,
-                               const float *lse, const float *delta, const int64_t *offsets, int B, int H, int D,
-                               Schedule s, void *grad, int cus, hipStream_t stream);
-
+// bf16 attention, register-staged kernels (any supported D, short samples)
 constexpr int kFwdBlockRows = 128;
-constexpr int kFwdWideBlockRows = 256;
-// Unfused jagged attention (Table 1): offsets of the jagged square array, then the three operators.
-hipError_t launch_jagged_dense_bmm(const void *x, const void *w, const int64_t *offsets, int B, int D, int T,
-                                   int32_t *counter, void *out, int cus, hipStream_t stream);
-hipError_t launch_jagged_jagged_bmm(const void *x, const void *y, const int64_t *offsets, int B, int D, int T,
-                                    int32_t *counter, void *out, int cus, hipStream_t stream);
-hipError_t launch_jagged_softmax(bool backward, const void *a, const void *b, const int64_t *offsets, int B, int D,
-                                 int32_t *counter, void *out, int cus, hipStream_t stream);
-hipError_t launch_convert(bool to_dense, const void *src, void *dst, const int64_t *offsets, int B, int64_t max_len,
-                          int64_t row_chunks, uint32_t pad, int cus, hipStream_t stream);
-hipError_t launch_square_offsets(const int64_t *offsets, int B, int64_t *sq, hipStream_t stream);
-hipError_t launch_unfused_scores(const void *q, const void *k, const int64_t *offsets, const int64_t *sq, int B, int H,
-                                 int D, Schedule s, float *scores, int cus, hipStream_t stream);
-hipError_t launch_unfused_softmax(const int64_t *offsets, const int64_t *sq, int B, int H, Schedule s, float *scores,
-                                  int cus, hipStream_t stream);
-hipError_t launch_unfused_apply(const float *probs, const void *v, const int64_t *offsets, const int64_t *sq, int B,
-                                int H, int D, Schedule s, void *out, int cus, hipStream_t stream);
-hipError_t launch_fwd_bf16_dma(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H,
-                               int D, Schedule s, void *out, float *lse, int cus, hipStream_t stream);
-hipError_t launch_fwd_bf16_wide(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H,
-                                int D, Schedule s, void *out, float *lse, int cus, hipStream_t stream);
 constexpr int kBwdBlockRows = 128;
 hipError_t launch_fwd_bf16(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H, int D,
                            Schedule s, void *out, float *lse, int cus, hipStream_t stream);
@@ -269,5 +245,35 @@ hipError_t launch_dkv_bf16(const void *q, const void *k, const void *v, const vo
 hipError_t launch_dq_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
                           const float *delta, const int64_t *offsets, int B, int H, int D, Schedule s, void *dq,
                           int cus, hipStream_t stream);
+
+// bf16 attention, direct-to-LDS kernels (D = 128, long samples; work items are blocks of kDmaBlockRows rows)
+constexpr int kDmaBlockRows = 256;
+hipError_t launch_fwd_bf16_dma(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H,
+                               int D, Schedule s, void *out, float *lse, int cus, hipStream_t stream);
+// mode: 0 = dQ, 1 = dK, 2 = dV
+hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const void *v, const void *dout,
+                               const float *lse, const float *delta, const int64_t *offsets, int B, int H, int D,
+                               Schedule s, void *grad, int cus, hipStream_t stream);
+
+// Unfused jagged attention (Table 1): offsets of the jagged square array, then the three operators.
+hipError_t launch_square_offsets(const int64_t *offsets, int B, int64_t *sq, hipStream_t stream);
+hipError_t launch_unfused_scores(const void *q, const void *k, const int64_t *offsets, const int64_t *sq, int B, int H,
+                                 int D, Schedule s, float *scores, int cus, hipStream_t stream);
+hipError_t launch_unfused_softmax(const int64_t *offsets, const int64_t *sq, int B, int H, Schedule s, float *scores,
+                                  int cus, hipStream_t stream);
+hipError_t launch_unfused_apply(const float *probs, const void *v, const int64_t *offsets, const int64_t *sq, int B,
+                                int H, int D, Schedule s, void *out, int cus, hipStream_t stream);
+
+// Jagged <-> padded-dense conversion (Section 2.2); rows are row_chunks 16-byte chunks long.
+hipError_t launch_convert(bool to_dense, const void *src, void *dst, const int64_t *offsets, int B, int64_t max_len,
+                          int64_t row_chunks, uint32_t pad, int cus, hipStream_t stream);
+
+// Jagged feature operators (Table 1); `counter` is one work counter, reset by the launcher.
+hipError_t launch_jagged_dense_bmm(const void *x, const void *w, const int64_t *offsets, int B, int D, int T,
+                                   int32_t *counter, void *out, int cus, hipStream_t stream);
+hipError_t launch_jagged_jagged_bmm(const void *x, const void *y, const int64_t *offsets, int B, int D, int T,
+                                    int32_t *counter, void *out, int cus, hipStream_t stream);
+hipError_t launch_jagged_softmax(bool backward, const void *a, const void *b, const int64_t *offsets, int B, int D,
+                                 int32_t *counter, void *out, int cus, hipStream_t stream);
 
 }  // namespace jfa

@@ -131,9 +131,9 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             }
         };
 
-        const int i = t.block * kFwdWideBlockRows + wave * 32 + col;   // this lane's query
+        const int i = t.block * kDmaBlockRows + wave * 32 + col;   // this lane's query
         const int iq = i < L ? i : L - 1;
-        const bool wave_active = t.block * kFwdWideBlockRows + wave * 32 < L;
+        const bool wave_active = t.block * kDmaBlockRows + wave * 32 < L;
         bf16x8 qreg[kKSteps];
         {
             const __bf16 *qrow = q + (t.row0 + iq) * row_stride + (int64_t)t.head * D + 8 * half;
@@ -382,7 +382,7 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
                     for (int e = 0; e < 4; ++e) x[e] = (__bf16)(o[db][4 * g + e] * inv);
                     *reinterpret_cast<bf16x4 *>(region + (wbase ^ (db * 64 + g * 16))) = x;
                 }
-            const int q0 = t.block * kFwdWideBlockRows + wave * 32;   // first query of this wave
+            const int q0 = t.block * kDmaBlockRows + wave * 32;   // first query of this wave
             __bf16 *const obase = out + (t.row0 + q0) * row_stride + (int64_t)t.head * D;
             const uint32_t lane_off = 2u * (uint32_t)((lane_e >> 4) * (int)row_stride + (lane_e & 15) * 8);
 #pragma unroll

@@ -77,6 +77,36 @@ def test_schedule_and_check_argument_errors(lib):
     assert lib.jfa_check_offsets(16, 4, 10, None, None) == binding.JFA_ERR_INVALID_ARG
 
 
+def test_unfused_conversion_and_feature_operator_argument_errors(lib):
+    from paper_2409_15373_amd import binding
+    OK, BAD, UNS = binding.JFA_OK, binding.JFA_ERR_INVALID_ARG, binding.JFA_ERR_UNSUPPORTED
+    assert lib.jfa_square_offsets(None, 4, None, None) == BAD
+    assert lib.jfa_square_offsets(None, -1, None, None) == BAD
+    assert lib.jfa_unfused_scores(None, None, None, None, 1, 8, 1, 48, None, None) == UNS
+    assert lib.jfa_unfused_scores(None, None, None, None, 1, 8, 1, 64, None, None) == BAD
+    assert lib.jfa_unfused_scores(None, None, None, None, 0, 8, 1, 64, None, None) == OK
+    assert lib.jfa_unfused_softmax(None, None, 1, 8, 0, None, None) == BAD                  # H = 0
+    assert lib.jfa_unfused_apply(None, None, None, None, -2, 8, 1, 64, None, None) == BAD
+    # conversions: row_bytes must be a positive multiple of 16; null and misaligned tensors are refused
+    assert lib.jfa_jagged_to_dense(16, 16, 2, 8, 24, 0, 16, None) == UNS
+    assert "multiple of 16" in binding.jfa_last_error()
+    assert lib.jfa_jagged_to_dense(None, 16, 2, 8, 32, 0, 16, None) == BAD
+    assert lib.jfa_jagged_to_dense(8, 16, 2, 8, 32, 0, 16, None) == BAD
+    assert "aligned" in binding.jfa_last_error()
+    assert lib.jfa_dense_to_jagged(16, 16, 2, -1, 32, 16, None) == BAD
+    assert lib.jfa_dense_to_jagged(None, None, 0, 8, 32, None, None) == OK                  # B == 0: nothing to do
+    assert lib.jfa_jagged_to_dense(None, None, 3, 0, 32, 0, None, None) == OK               # max_len == 0: an empty dense tensor
+    # feature operators: D and T each one of 32, 64, 128
+    assert lib.jfa_jagged_dense_bmm(None, None, None, 1, 8, 64, 48, None, None) == UNS
+    assert "T = 48" in binding.jfa_last_error()
+    assert lib.jfa_jagged_dense_bmm(None, None, None, 1, 8, 16, 64, None, None) == UNS
+    assert lib.jfa_jagged_jagged_bmm(None, None, None, 1, 8, 64, 64, None, None) == BAD
+    assert "null" in binding.jfa_last_error()
+    assert lib.jfa_jagged_jagged_bmm(None, None, None, 0, 8, 64, 64, None, None) == OK
+    assert lib.jfa_jagged_softmax(None, None, 1, 8, 96, None, None) == UNS
+    assert lib.jfa_jagged_softmax_backward(16, 16, 16, 1, 8, 64, 8, None) == BAD            # dx misaligned
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     from paper_2409_15373_amd import binding
     monkeypatch.setattr(binding, "_lib", None)
