@@ -85,6 +85,33 @@ int jfa_backward_f32(const float *q, const float *k, const float *v, const float
                      float *dk, float *dv, float *delta, void *stream);
 
 /*
+ * Cross attention on jagged tensors: the queries of sample b are rows offsets_q[b] .. offsets_q[b+1] - 1 of q (and
+ * of out, dout, dq; sum_Bq rows in all) and its keys and values are rows offsets_kv[b] .. offsets_kv[b+1] - 1 of k
+ * and v (and of dk, dv; sum_Bkv rows).  This is the shape of the paper's feature interaction (Section 2: attention
+ * between a sample's feature values and its target items); with offsets_kv equal to offsets_q it is jfa_forward /
+ * jfa_backward.  Per sample and head:  out_i = sum_j softmax_j(q_i . k_j / sqrt(D)) v_j  over the sample's keys j.
+ *
+ *   q, out, dout, dq   [sum_Bq, H, D];  k, v, dk, dv  [sum_Bkv, H, D];  bf16, or fp32 for the _f32 variants
+ *   offsets_q, offsets_kv   int64 [B+1] on the device
+ *   max_len_q, max_len_kv   upper bounds on the samples' query and key counts
+ *   lse     fp32 [H, sum_Bq];  delta as for jfa_backward with sum_B = sum_Bq
+ * A sample without keys gives out = 0, lse = -inf and dq = 0 for its queries; a sample without queries gives
+ * dk = dv = 0 for its keys.  Everything else (alignment, streams, errors, ownership) as for the calls above.
+ */
+int jfa_forward_cross(const void *q, const void *k, const void *v, const int64_t *offsets_q, const int64_t *offsets_kv,
+                      int64_t B, int64_t max_len_q, int64_t max_len_kv, int H, int D, void *out, float *lse, void *stream);
+int jfa_forward_cross_f32(const float *q, const float *k, const float *v, const int64_t *offsets_q,
+                          const int64_t *offsets_kv, int64_t B, int64_t max_len_q, int64_t max_len_kv, int H, int D,
+                          float *out, float *lse, void *stream);
+int jfa_backward_cross(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
+                       const int64_t *offsets_q, const int64_t *offsets_kv, int64_t B, int64_t max_len_q,
+                       int64_t max_len_kv, int H, int D, void *dq, void *dk, void *dv, float *delta, void *stream);
+int jfa_backward_cross_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
+                           const float *lse, const int64_t *offsets_q, const int64_t *offsets_kv, int64_t B,
+                           int64_t max_len_q, int64_t max_len_kv, int H, int D, float *dq, float *dk, float *dv,
+                           float *delta, void *stream);
+
+/*
  * Unfused jagged attention: the three separate jagged operators of the paper's Table 1 (a jagged x jagged product
  * with a jagged square output, a softmax over that output, and its product with a jagged tensor), which write the
  * score array to memory.  They are the baseline that Section 3 compares the fused kernel with, provided here

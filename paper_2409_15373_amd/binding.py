@@ -27,7 +27,8 @@ EXPORTS = (
     "jfa_check_offsets", "jfa_workspace_bytes", "jfa_last_error", "jfa_version", "jfa_timing_enable",
     "jfa_timing_read", "jfa_square_offsets", "jfa_unfused_scores", "jfa_unfused_softmax", "jfa_unfused_apply",
     "jfa_jagged_to_dense", "jfa_dense_to_jagged", "jfa_jagged_dense_bmm", "jfa_jagged_jagged_bmm",
-    "jfa_jagged_softmax", "jfa_jagged_softmax_backward",
+    "jfa_jagged_softmax", "jfa_jagged_softmax_backward", "jfa_forward_cross", "jfa_forward_cross_f32",
+    "jfa_backward_cross", "jfa_backward_cross_f32",
 )
 
 
@@ -55,6 +56,12 @@ def load() -> ctypes.CDLL:
     lib.jfa_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.jfa_backward_f32.restype = i32
     lib.jfa_backward_f32.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp]
+    for name in ("jfa_forward_cross", "jfa_forward_cross_f32"):
+        getattr(lib, name).restype = i32
+        getattr(lib, name).argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, vp, vp, vp]
+    for name in ("jfa_backward_cross", "jfa_backward_cross_f32"):
+        getattr(lib, name).restype = i32
+        getattr(lib, name).argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.jfa_build_schedule.restype = i32
     lib.jfa_build_schedule.argtypes = [vp, i64, i32, vp, vp, vp]
     lib.jfa_check_offsets.restype = i32
@@ -153,6 +160,36 @@ def jfa_backward(q, k, v, out, dout, lse, offsets, max_len: int, dq=None, dk=Non
     fn = _pick(q.dtype, "jfa_backward")
     _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(dout), _ptr(lse), _ptr(offsets), B, max_len, H, D,
               _ptr(dq), _ptr(dk), _ptr(dv), _ptr(stats), _stream()))
+    return dq, dk, dv, (stats[0] if delta is None else delta)
+
+
+def jfa_forward_cross(q, k, v, offsets_q, offsets_kv, max_len_q: int, max_len_kv: int, out=None, lse=None):
+    """Cross attention: out [sum_Bq, H, D] and lse fp32 [H, sum_Bq]; q rows follow offsets_q, k and v rows offsets_kv."""
+    sum_Bq, H, D = q.shape
+    assert k.shape == v.shape and k.shape[1:] == q.shape[1:] and k.dtype == q.dtype == v.dtype
+    assert offsets_q.numel() == offsets_kv.numel()
+    B = offsets_q.numel() - 1
+    out = torch.empty_like(q) if out is None else out
+    lse = torch.empty((H, sum_Bq), dtype=torch.float32, device=q.device) if lse is None else lse
+    fn = _pick(q.dtype, "jfa_forward_cross")
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(offsets_q), _ptr(offsets_kv), B, max_len_q, max_len_kv, H, D,
+              _ptr(out), _ptr(lse), _stream()))
+    return out, lse
+
+
+def jfa_backward_cross(q, k, v, out, dout, lse, offsets_q, offsets_kv, max_len_q: int, max_len_kv: int,
+                       dq=None, dk=None, dv=None, delta=None):
+    """dq [sum_Bq, H, D], dk, dv [sum_Bkv, H, D] and delta fp32 [H, sum_Bq] (statistics buffer as in jfa_backward)."""
+    sum_Bq, H, D = q.shape
+    B = offsets_q.numel() - 1
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    planes = 2 if q.dtype == torch.bfloat16 else 1
+    stats = torch.empty((planes, H, sum_Bq), dtype=torch.float32, device=q.device) if delta is None else delta
+    fn = _pick(q.dtype, "jfa_backward_cross")
+    _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(dout), _ptr(lse), _ptr(offsets_q), _ptr(offsets_kv), B,
+              max_len_q, max_len_kv, H, D, _ptr(dq), _ptr(dk), _ptr(dv), _ptr(stats), _stream()))
     return dq, dk, dv, (stats[0] if delta is None else delta)
 
 

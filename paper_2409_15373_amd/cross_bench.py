@@ -1,0 +1,70 @@
+#!/usr/bin/env python3
+"""Timing of jagged cross attention (jfa_forward_cross / jfa_backward_cross) against the bf16 MFMA roofline.
+
+    python -m paper_2409_15373_amd.cross_bench [--reps N]
+
+The paper's feature interaction attends from a sample's target items to its feature values: few queries, many
+keys.  Two synthetic workloads with B = 512, H = 8, D = 128 and the keys' lengths of the benchmarked self-attention
+configuration (bimodal, up to 4096): queries uniform on [1, 256] ("targets"), and queries with the keys' lengths
+shuffled across samples ("shuffled": as much work as self attention, but L_q != L_kv in every sample).
+Useful flops: 4 H D sum(L_q L_kv) forward, 10 H D sum(L_q L_kv) backward.  Prints one JSON line.
+"""
+import argparse
+import json
+
+import numpy as np
+
+PEAK_TFLOPS = 2516.6
+
+
+def _time(fn, reps):
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--reps", type=int, default=5)
+    args = ap.parse_args()
+    import torch
+    from . import binding
+    from .synthetic import CONFIGS, lengths_for, offsets_from_lengths
+    binding.load()
+    assert torch.cuda.is_available(), "needs the GPU"
+    c = CONFIGS["c4_bimodal_bf16"]
+    B, H, D = c["B"], c["H"], c["D"]
+    rng = np.random.Generator(np.random.PCG64(c["seed"]))
+    Lk = lengths_for(c["lengths"], B, c["max_len"], rng)
+    cases = {"targets": (lengths_for("uniform", B, 256, rng), 256), "shuffled": (rng.permutation(Lk), c["max_len"])}
+    result = {"dtype": "bf16", "data": "synthetic", "B": B, "H": H, "D": D, "bound": "mfma", "peak_TFLOP_per_s": PEAK_TFLOPS, "workloads": {}}
+    gen = torch.Generator(device="cuda").manual_seed(0)
+    for name, (Lq, max_q) in cases.items():
+        nq, nk = int(Lq.sum()), int(Lk.sum())
+        pairs = float((Lq.astype(np.float64) * Lk).sum())
+        oq, ok = (torch.from_numpy(offsets_from_lengths(x)).cuda() for x in (Lq, Lk))
+        mk = lambda n, s: (torch.randn(n, H, D, device="cuda", generator=gen) * s).bfloat16()
+        q, k, v, dout = mk(nq, c["sigma"]), mk(nk, c["sigma"]), mk(nk, 1.0), mk(nq, 1.0)
+        out, lse = torch.empty_like(q), torch.empty(H, nq, device="cuda")
+        dq, dk, dv, stats = torch.empty_like(q), torch.empty_like(k), torch.empty_like(k), torch.empty(2, H, nq, device="cuda")
+        fwd = lambda: binding.jfa_forward_cross(q, k, v, oq, ok, max_q, c["max_len"], out=out, lse=lse)
+        bwd = lambda: binding.jfa_backward_cross(q, k, v, out, dout, lse, oq, ok, max_q, c["max_len"], dq=dq, dk=dk, dv=dv, delta=stats)
+        t_f, t_b = _time(fwd, args.reps), _time(bwd, args.reps)
+        f_f, f_b = 4.0 * H * D * pairs, 10.0 * H * D * pairs
+        result["workloads"][name] = {
+            "sum_Bq": nq, "sum_Bkv": nk, "query_key_pairs_per_head": pairs,
+            "fwd_us": round(t_f, 1), "fwd_TFLOP_per_s": round(f_f / t_f / 1e6, 1), "fwd_frac_of_peak": round(f_f / t_f / 1e6 / PEAK_TFLOPS, 3),
+            "bwd_us": round(t_b, 1), "bwd_useful_TFLOP_per_s": round(f_b / t_b / 1e6, 1), "bwd_frac_of_peak": round(f_b / t_b / 1e6 / PEAK_TFLOPS, 3),
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

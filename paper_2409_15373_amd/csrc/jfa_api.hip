@@ -222,94 +222,153 @@ int jfa_check_offsets(const int64_t *offsets, int64_t B, int64_t max_len, void *
     return JFA_OK;
 }
 
-int jfa_forward_f32(const float *q, const float *k, const float *v, const int64_t *offsets, int64_t B,
-                    int64_t max_len, int H, int D, float *out, float *lse, void *stream) {
+}  // extern "C"
+
+namespace {
+// Forward and backward behind the self- and cross-attention entry points.  offsets_kv == nullptr: self attention
+// (keys and values share the queries' offsets).  Work schedules are built over the offsets of the rows a kernel's
+// work items are blocks of: the queries' for the forward and dQ, the keys' for dK and dV.
+hipError_t schedule(const int64_t *offsets, int64_t B, int block_rows, const Views &w, int which, hipStream_t s) {
+    ScopedTimer tm("schedule", s);
+    return jfa::launch_schedule(offsets, (int)B, block_rows, w.order[which], w.tile_start[which], w.counters, jfa::kNumCounters, s);
+}
+
+int forward_impl(const char *who, bool f32, const void *q, const void *k, const void *v, const int64_t *offsets,
+                 const int64_t *offsets_kv, int64_t B, int64_t max_len, int64_t max_len_kv, int H, int D, void *out,
+                 float *lse, hipStream_t s) {
     const void *ptrs[] = {q, k, v, offsets, out, lse};
-    int st = check_common("jfa_forward_f32", B, max_len, H, D, ptrs, 6);
+    int st = check_common(who, B, max_len, H, D, ptrs, 6);
     if (st != JFA_OK || B == 0) return st;
-    hipStream_t s = (hipStream_t)stream;
+    if (max_len_kv < 0) return fail(JFA_ERR_INVALID_ARG, "%s: max_len_kv = %lld is negative", who, (long long)max_len_kv);
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
-    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, jfa::kF32BlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
+    const FwdVariant variant = f32 ? kNarrow : forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H);
+    e = schedule(offsets, B, f32 ? jfa::kF32BlockRows : (variant == kNarrow ? jfa::kFwdBlockRows : jfa::kDmaBlockRows), w, 0, s);
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
-    { ScopedTimer tm("fwd_f32", s); e = jfa::launch_fwd_f32(q, k, v, offsets, (int)B, H, D, sc, out, lse, w.cus, s); }
-    if (e != hipSuccess) return hip_fail("fp32 forward kernel", e);
+    if (f32) { ScopedTimer tm("fwd_f32", s); e = jfa::launch_fwd_f32((const float *)q, (const float *)k, (const float *)v, offsets, offsets_kv, (int)B, H, D, sc, (float *)out, lse, w.cus, s); }
+    else if (variant == kDma) { ScopedTimer tm("fwd_bf16_dma", s); e = jfa::launch_fwd_bf16_dma(q, k, v, offsets, offsets_kv, (int)B, H, D, sc, out, lse, w.cus, s); }
+    else { ScopedTimer tm("fwd_bf16", s); e = jfa::launch_fwd_bf16(q, k, v, offsets, offsets_kv, (int)B, H, D, sc, out, lse, w.cus, s); }
+    if (e != hipSuccess) return hip_fail("forward kernel", e);
     return JFA_OK;
 }
 
-int jfa_backward_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
-                     const float *lse, const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, float *dq,
-                     float *dk, float *dv, float *delta, void *stream) {
+int backward_impl(const char *who, bool f32, const void *q, const void *k, const void *v, const void *out,
+                  const void *dout, const float *lse, const int64_t *offsets, const int64_t *offsets_kv, int64_t B,
+                  int64_t max_len, int64_t max_len_kv, int H, int D, void *dq, void *dk, void *dv, float *delta,
+                  hipStream_t s) {
     const void *ptrs[] = {q, k, v, out, dout, lse, offsets, dq, dk, dv, delta};
-    int st = check_common("jfa_backward_f32", B, max_len, H, D, ptrs, 11);
+    int st = check_common(who, B, max_len, H, D, ptrs, 11);
     if (st != JFA_OK || B == 0) return st;
-    hipStream_t s = (hipStream_t)stream;
+    if (max_len_kv < 0) return fail(JFA_ERR_INVALID_ARG, "%s: max_len_kv = %lld is negative", who, (long long)max_len_kv);
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
-    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, jfa::kF32BlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
+    const bool dma = !f32 && D == 128 && forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H) != kNarrow;
+    const int block_rows = f32 ? jfa::kF32BlockRows : (dma ? jfa::kDmaBlockRows : jfa::kBwdBlockRows);
+    // Schedule 0: blocks of queries.  Schedule 1: blocks of keys, only different from schedule 0 for cross attention.
+    // Both launches clear all work counters, and both run before the first kernel that uses one.
+    e = schedule(offsets, B, block_rows, w, 0, s);
+    if (e == hipSuccess && offsets_kv) e = schedule(offsets_kv, B, block_rows, w, 1, s);
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
-    jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
-    jfa::Schedule s_dkv{w.order[0], w.tile_start[0], w.counters + jfa::kXcds};
-    ScopedTimer tm_bwd("bwd_f32", s);
-    e = jfa::launch_bwd_f32(q, k, v, out, dout, lse, offsets, (int)B, H, D, s_dq, s_dkv, dq, dk, dv, delta, w.cus, s);
-    if (e != hipSuccess) return hip_fail("fp32 backward kernels", e);
-    return JFA_OK;
-}
-
-int jfa_forward(const void *q, const void *k, const void *v, const int64_t *offsets, int64_t B, int64_t max_len,
-                int H, int D, void *out, float *lse, void *stream) {
-    const void *ptrs[] = {q, k, v, offsets, out, lse};
-    int st = check_common("jfa_forward", B, max_len, H, D, ptrs, 6);
-    if (st != JFA_OK || B == 0) return st;
-    hipStream_t s = (hipStream_t)stream;
-    Views w;
-    if ((st = get_table(B, s, &w)) != JFA_OK) return st;
-    hipError_t e;
-    const FwdVariant variant = forward_variant(max_len, D, H);
-    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, variant == kNarrow ? jfa::kFwdBlockRows : jfa::kDmaBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
-    if (e != hipSuccess) return hip_fail("schedule kernel", e);
-    jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
-    if (variant == kDma) { ScopedTimer tm("fwd_bf16_dma", s); e = jfa::launch_fwd_bf16_dma(q, k, v, offsets, (int)B, H, D, sc, out, lse, w.cus, s); }
-    else { ScopedTimer tm("fwd_bf16", s); e = jfa::launch_fwd_bf16(q, k, v, offsets, (int)B, H, D, sc, out, lse, w.cus, s); }
-    if (e != hipSuccess) return hip_fail("bf16 forward kernel", e);
-    return JFA_OK;
-}
-
-int jfa_backward(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
-                 const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, void *dq, void *dk, void *dv,
-                 float *delta, void *stream) {
-    const void *ptrs[] = {q, k, v, out, dout, lse, offsets, dq, dk, dv, delta};
-    int st = check_common("jfa_backward", B, max_len, H, D, ptrs, 11);
-    if (st != JFA_OK || B == 0) return st;
-    hipStream_t s = (hipStream_t)stream;
-    Views w;
-    if ((st = get_table(B, s, &w)) != JFA_OK) return st;
-    hipError_t e;
-    const bool dma = D == 128 && forward_variant(max_len, D, H) != kNarrow;   // long samples: direct-to-LDS kernels
-    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, dma ? jfa::kDmaBlockRows : jfa::kBwdBlockRows, w.order[0], w.tile_start[0], w.counters, jfa::kNumCounters, s); }
-    if (e != hipSuccess) return hip_fail("schedule kernel", e);
+    const int kv = offsets_kv ? 1 : 0;
+    const int64_t *const offsets_k = offsets_kv ? offsets_kv : offsets;   // the keys' offsets
+    const int64_t *const offsets_q_other = offsets_kv ? offsets : nullptr;   // the queries', as the second array of dK / dV
+    if (f32) {
+        jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
+        jfa::Schedule s_dkv{w.order[kv], w.tile_start[kv], w.counters + jfa::kXcds};
+        ScopedTimer tm_bwd("bwd_f32", s);
+        e = jfa::launch_bwd_f32((const float *)q, (const float *)k, (const float *)v, (const float *)out, (const float *)dout, lse,
+                                offsets, offsets_kv, (int)B, H, D, s_dq, s_dkv, (float *)dq, (float *)dk, (float *)dv, delta, w.cus, s);
+        if (e != hipSuccess) return hip_fail("fp32 backward kernels", e);
+        return JFA_OK;
+    }
     { ScopedTimer tm("delta", s); e = jfa::launch_delta(out, dout, lse, offsets, (int)B, H, D, true, delta, w.cus, s); }
     if (e != hipSuccess) return hip_fail("delta kernel", e);
     if (dma) {
         static const char *const names[3] = {"dq_bf16_dma", "dk_bf16_dma", "dv_bf16_dma"};
         void *const grads[3] = {dq, dk, dv};
         for (int mode = 0; mode < 3; ++mode) {
-            jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters + mode * jfa::kXcds};
-            { ScopedTimer tm(names[mode], s); e = jfa::launch_bwd_bf16_dma(mode, q, k, v, dout, lse, delta, offsets, (int)B, H, D, sc, grads[mode], w.cus, s); }
+            const int which = mode == 0 ? 0 : kv;
+            jfa::Schedule sc{w.order[which], w.tile_start[which], w.counters + mode * jfa::kXcds};
+            { ScopedTimer tm(names[mode], s); e = jfa::launch_bwd_bf16_dma(mode, q, k, v, dout, lse, delta, mode == 0 ? offsets : offsets_k, mode == 0 ? offsets_kv : offsets_q_other, (int)B, H, D, sc, grads[mode], w.cus, s); }
             if (e != hipSuccess) return hip_fail(names[mode], e);
         }
         return JFA_OK;
     }
     jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
-    jfa::Schedule s_dkv{w.order[0], w.tile_start[0], w.counters + jfa::kXcds};
-    { ScopedTimer tm("dkv_bf16", s); e = jfa::launch_dkv_bf16(q, k, v, dout, lse, delta, offsets, (int)B, H, D, s_dkv, dk, dv, w.cus, s); }
+    jfa::Schedule s_dkv{w.order[kv], w.tile_start[kv], w.counters + jfa::kXcds};
+    { ScopedTimer tm("dkv_bf16", s); e = jfa::launch_dkv_bf16(q, k, v, dout, lse, delta, offsets_k, offsets_q_other, (int)B, H, D, s_dkv, dk, dv, w.cus, s); }
     if (e != hipSuccess) return hip_fail("bf16 dK/dV kernel", e);
-    { ScopedTimer tm("dq_bf16", s); e = jfa::launch_dq_bf16(q, k, v, dout, lse, delta, offsets, (int)B, H, D, s_dq, dq, w.cus, s); }
+    { ScopedTimer tm("dq_bf16", s); e = jfa::launch_dq_bf16(q, k, v, dout, lse, delta, offsets, offsets_kv, (int)B, H, D, s_dq, dq, w.cus, s); }
     if (e != hipSuccess) return hip_fail("bf16 dQ kernel", e);
     return JFA_OK;
+}
+
+int need_kv(const char *who, const int64_t *offsets_kv, int64_t B) {
+    if (B > 0 && !offsets_kv) return fail(JFA_ERR_INVALID_ARG, "%s: offsets_kv is null", who);
+    if (B > 0 && misaligned(offsets_kv)) return fail(JFA_ERR_INVALID_ARG, "%s: offsets_kv is not 16-byte aligned", who);
+    return JFA_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int jfa_forward_f32(const float *q, const float *k, const float *v, const int64_t *offsets, int64_t B,
+                    int64_t max_len, int H, int D, float *out, float *lse, void *stream) {
+    return forward_impl("jfa_forward_f32", true, q, k, v, offsets, nullptr, B, max_len, max_len, H, D, out, lse, (hipStream_t)stream);
+}
+
+int jfa_backward_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
+                     const float *lse, const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, float *dq,
+                     float *dk, float *dv, float *delta, void *stream) {
+    return backward_impl("jfa_backward_f32", true, q, k, v, out, dout, lse, offsets, nullptr, B, max_len, max_len, H, D, dq, dk, dv, delta, (hipStream_t)stream);
+}
+
+int jfa_forward(const void *q, const void *k, const void *v, const int64_t *offsets, int64_t B, int64_t max_len,
+                int H, int D, void *out, float *lse, void *stream) {
+    return forward_impl("jfa_forward", false, q, k, v, offsets, nullptr, B, max_len, max_len, H, D, out, lse, (hipStream_t)stream);
+}
+
+int jfa_backward(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
+                 const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, void *dq, void *dk, void *dv,
+                 float *delta, void *stream) {
+    return backward_impl("jfa_backward", false, q, k, v, out, dout, lse, offsets, nullptr, B, max_len, max_len, H, D, dq, dk, dv, delta, (hipStream_t)stream);
+}
+
+// ---- cross attention: queries and keys of a sample come from two offsets arrays ----
+
+int jfa_forward_cross(const void *q, const void *k, const void *v, const int64_t *offsets_q, const int64_t *offsets_kv,
+                      int64_t B, int64_t max_len_q, int64_t max_len_kv, int H, int D, void *out, float *lse, void *stream) {
+    int st = need_kv("jfa_forward_cross", offsets_kv, B);
+    if (st != JFA_OK) return st;
+    return forward_impl("jfa_forward_cross", false, q, k, v, offsets_q, offsets_kv, B, max_len_q, max_len_kv, H, D, out, lse, (hipStream_t)stream);
+}
+
+int jfa_forward_cross_f32(const float *q, const float *k, const float *v, const int64_t *offsets_q,
+                          const int64_t *offsets_kv, int64_t B, int64_t max_len_q, int64_t max_len_kv, int H, int D,
+                          float *out, float *lse, void *stream) {
+    int st = need_kv("jfa_forward_cross_f32", offsets_kv, B);
+    if (st != JFA_OK) return st;
+    return forward_impl("jfa_forward_cross_f32", true, q, k, v, offsets_q, offsets_kv, B, max_len_q, max_len_kv, H, D, out, lse, (hipStream_t)stream);
+}
+
+int jfa_backward_cross(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
+                       const int64_t *offsets_q, const int64_t *offsets_kv, int64_t B, int64_t max_len_q,
+                       int64_t max_len_kv, int H, int D, void *dq, void *dk, void *dv, float *delta, void *stream) {
+    int st = need_kv("jfa_backward_cross", offsets_kv, B);
+    if (st != JFA_OK) return st;
+    return backward_impl("jfa_backward_cross", false, q, k, v, out, dout, lse, offsets_q, offsets_kv, B, max_len_q, max_len_kv, H, D, dq, dk, dv, delta, (hipStream_t)stream);
+}
+
+int jfa_backward_cross_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
+                           const float *lse, const int64_t *offsets_q, const int64_t *offsets_kv, int64_t B,
+                           int64_t max_len_q, int64_t max_len_kv, int H, int D, float *dq, float *dk, float *dv,
+                           float *delta, void *stream) {
+    int st = need_kv("jfa_backward_cross_f32", offsets_kv, B);
+    if (st != JFA_OK) return st;
+    return backward_impl("jfa_backward_cross_f32", true, q, k, v, out, dout, lse, offsets_q, offsets_kv, B, max_len_q, max_len_kv, H, D, dq, dk, dv, delta, (hipStream_t)stream);
 }
 
 // ---- unfused jagged attention (paper Table 1): the baseline of Section 3 ----

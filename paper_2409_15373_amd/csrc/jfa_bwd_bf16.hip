@@ -74,14 +74,16 @@ __device__ inline void store_rows(__bf16 *dst_row, const f32x16 (&acc)[D / 32], 
         }
 }
 
-template <int D>
+// CROSS: keys and values are the rows of a second offsets array (offsets_kv); see the forward kernel.
+template <int D, bool CROSS>
 __global__ __launch_bounds__(kBwdThreads, 2) void dq_bf16_kernel(const __bf16 *__restrict__ q,
                                                                  const __bf16 *__restrict__ k,
                                                                  const __bf16 *__restrict__ v,
                                                                  const __bf16 *__restrict__ dout,
                                                                  const float *__restrict__ lse,
                                                                  const float *__restrict__ delta,
-                                                                 const int64_t *__restrict__ offsets, int B, int H,
+                                                                 const int64_t *__restrict__ offsets,
+                                                                 const int64_t *__restrict__ offsets_kv, int B, int H,
                                                                  Schedule s, __bf16 *__restrict__ dq) {
     constexpr int kKSteps = D / 16, kDBlocks = D / 32;
     using Smem = BwdSmem<D>;
@@ -101,14 +103,16 @@ __global__ __launch_bounds__(kBwdThreads, 2) void dq_bf16_kernel(const __bf16 *_
         __syncthreads();
         const int64_t w = uniform64(sm.slot);
         if (w < 0) break;
-        const Work t = decode_work(s, offsets, B, H, w);
-        const int L = t.len;
-        const __bf16 *kbase = k + t.row0 * row_stride + (int64_t)t.head * D;
-        const __bf16 *vbase = v + t.row0 * row_stride + (int64_t)t.head * D;
+        const Work t = decode_work(s, offsets, B, H, w, CROSS ? offsets_kv : nullptr);
+        const int Lq = t.len;                      // queries of the sample
+        const int L = CROSS ? t.olen : t.len;      // keys of the sample
+        const int64_t krow0 = CROSS ? t.orow0 : t.row0;
+        const __bf16 *kbase = k + krow0 * row_stride + (int64_t)t.head * D;
+        const __bf16 *vbase = v + krow0 * row_stride + (int64_t)t.head * D;
 
         const int i = t.block * kBwdBlockRows + wave * 32 + col;
-        const int iq = i < L ? i : L - 1;
-        const bool wave_active = t.block * kBwdBlockRows + wave * 32 < L;
+        const int iq = i < Lq ? i : Lq - 1;
+        const bool wave_active = t.block * kBwdBlockRows + wave * 32 < Lq;
         bf16x8 qreg[kKSteps], doreg[kKSteps];
         {
             const int64_t off = (t.row0 + iq) * row_stride + (int64_t)t.head * D + 8 * half;
@@ -128,8 +132,10 @@ __global__ __launch_bounds__(kBwdThreads, 2) void dq_bf16_kernel(const __bf16 *_
             for (int e = 0; e < 16; ++e) acc[db][e] = 0.0f;
 
         Stage<D> sk, sv;
-        sk.prefetch(kbase, row_stride, 0, L);
-        sv.prefetch(vbase, row_stride, 0, L);
+        if (!CROSS || L > 0) {   // a sample without keys: nothing streams, dq = 0
+            sk.prefetch(kbase, row_stride, 0, L);
+            sv.prefetch(vbase, row_stride, 0, L);
+        }
         for (int j0 = 0; j0 < L; j0 += kBwdStage) {
             __syncthreads();
             sk.commit(sm.a, Smem::kStride);
@@ -175,18 +181,21 @@ __global__ __launch_bounds__(kBwdThreads, 2) void dq_bf16_kernel(const __bf16 *_
                 }
             }
         }
-        if (i < L) store_rows<D>(dq + (t.row0 + i) * row_stride + (int64_t)t.head * D, acc, scale, half);
+        if (i < Lq) store_rows<D>(dq + (t.row0 + i) * row_stride + (int64_t)t.head * D, acc, scale, half);
     }
 }
 
-template <int D>
+// CROSS: `offsets` are the keys' offsets (the work items are blocks of keys) and the queries, with dout, lse and
+// delta, are the rows of offsets_q.
+template <int D, bool CROSS>
 __global__ __launch_bounds__(kBwdThreads, 1) void dkv_bf16_kernel(const __bf16 *__restrict__ q,
                                                                   const __bf16 *__restrict__ k,
                                                                   const __bf16 *__restrict__ v,
                                                                   const __bf16 *__restrict__ dout,
                                                                   const float *__restrict__ lse,
                                                                   const float *__restrict__ delta,
-                                                                  const int64_t *__restrict__ offsets, int B, int H,
+                                                                  const int64_t *__restrict__ offsets,
+                                                                  const int64_t *__restrict__ offsets_q, int B, int H,
                                                                   Schedule s, __bf16 *__restrict__ dk,
                                                                   __bf16 *__restrict__ dv) {
     constexpr int kKSteps = D / 16, kDBlocks = D / 32;
@@ -197,7 +206,7 @@ __global__ __launch_bounds__(kBwdThreads, 1) void dkv_bf16_kernel(const __bf16 *
     const float scale = 1.0f / sqrtf((float)D);
     const float c = 1.4426950408889634f * scale;
     const int64_t total = (int64_t)s.tile_start[B] * H;
-    const int64_t sum_B = offsets[B];
+    const int64_t sum_B = CROSS ? offsets_q[B] : offsets[B];   // lse and delta are indexed by query rows
     const int64_t row_stride = (int64_t)H * D;
 
     WorkCursor cursor;
@@ -207,16 +216,18 @@ __global__ __launch_bounds__(kBwdThreads, 1) void dkv_bf16_kernel(const __bf16 *
         __syncthreads();
         const int64_t w = uniform64(sm.slot);
         if (w < 0) break;
-        const Work t = decode_work(s, offsets, B, H, w);
-        const int L = t.len;
-        const __bf16 *qbase = q + t.row0 * row_stride + (int64_t)t.head * D;
-        const __bf16 *dobase = dout + t.row0 * row_stride + (int64_t)t.head * D;
-        const float *lse_base = lse + (int64_t)t.head * sum_B + t.row0;
-        const float *delta_base = delta + (int64_t)t.head * sum_B + t.row0;
+        const Work t = decode_work(s, offsets, B, H, w, CROSS ? offsets_q : nullptr);
+        const int Lk = t.len;                      // keys of the sample
+        const int L = CROSS ? t.olen : t.len;      // queries of the sample
+        const int64_t qrow0 = CROSS ? t.orow0 : t.row0;
+        const __bf16 *qbase = q + qrow0 * row_stride + (int64_t)t.head * D;
+        const __bf16 *dobase = dout + qrow0 * row_stride + (int64_t)t.head * D;
+        const float *lse_base = lse + (int64_t)t.head * sum_B + qrow0;
+        const float *delta_base = delta + (int64_t)t.head * sum_B + qrow0;
 
         const int j = t.block * kBwdBlockRows + wave * 32 + col;  // this lane's key
-        const int jk = j < L ? j : L - 1;
-        const bool wave_active = t.block * kBwdBlockRows + wave * 32 < L;
+        const int jk = j < Lk ? j : Lk - 1;
+        const bool wave_active = t.block * kBwdBlockRows + wave * 32 < Lk;
         bf16x8 kreg[kKSteps], vreg[kKSteps];
         {
             const int64_t off = (t.row0 + jk) * row_stride + (int64_t)t.head * D + 8 * half;
@@ -243,7 +254,7 @@ __global__ __launch_bounds__(kBwdThreads, 1) void dkv_bf16_kernel(const __bf16 *
                 delta_pre = ok ? delta_base[i0 + tid] : 0.0f;
             }
         };
-        prefetch_rows(0);
+        if (!CROSS || L > 0) prefetch_rows(0);   // a sample without queries: nothing streams, dk = dv = 0
         for (int i0 = 0; i0 < L; i0 += kBwdStage) {
             __syncthreads();
             sq.commit(sm.a, Smem::kStride);
@@ -296,7 +307,7 @@ __global__ __launch_bounds__(kBwdThreads, 1) void dkv_bf16_kernel(const __bf16 *
                 }
             }
         }
-        if (j < L) {
+        if (j < Lk) {
             const int64_t off = (t.row0 + j) * row_stride + (int64_t)t.head * D;
             store_rows<D>(dk + off, acck, scale, half);
             store_rows<D>(dv + off, accv, 1.0f, half);
@@ -305,13 +316,18 @@ __global__ __launch_bounds__(kBwdThreads, 1) void dkv_bf16_kernel(const __bf16 *
 }
 
 hipError_t launch_dkv_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
-                           const float *delta, const int64_t *offsets, int B, int H, int D, Schedule s, void *dk,
-                           void *dv, int cus, hipStream_t stream) {
+                           const float *delta, const int64_t *offsets, const int64_t *offsets_q, int B, int H, int D,
+                           Schedule s, void *dk, void *dv, int cus, hipStream_t stream) {
 #define JFA_CASE(DD)                                                                                             \
     case DD:                                                                                                     \
-        hipLaunchKernelGGL(dkv_bf16_kernel<DD>, dim3(persistent_grid<dkv_bf16_kernel<DD>>(kBwdThreads, cus)), dim3(kBwdThreads), 0, stream, (const __bf16 *)q,     \
-                           (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, lse, delta, offsets, B, H, \
-                           s, (__bf16 *)dk, (__bf16 *)dv);                                                       \
+        if (offsets_q)                                                                                           \
+            hipLaunchKernelGGL((dkv_bf16_kernel<DD, true>), dim3(persistent_grid<dkv_bf16_kernel<DD, true>>(kBwdThreads, cus)), dim3(kBwdThreads), 0, stream, \
+                               (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, lse, delta, offsets, offsets_q, B, H, \
+                               s, (__bf16 *)dk, (__bf16 *)dv);                                                   \
+        else                                                                                                     \
+            hipLaunchKernelGGL((dkv_bf16_kernel<DD, false>), dim3(persistent_grid<dkv_bf16_kernel<DD, false>>(kBwdThreads, cus)), dim3(kBwdThreads), 0, stream, \
+                               (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, lse, delta, offsets, offsets_q, B, H, \
+                               s, (__bf16 *)dk, (__bf16 *)dv);                                                   \
         break;
     switch (D) {
         JFA_CASE(32) JFA_CASE(64) JFA_CASE(128)
@@ -322,13 +338,18 @@ hipError_t launch_dkv_bf16(const void *q, const void *k, const void *v, const vo
 }
 
 hipError_t launch_dq_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
-                          const float *delta, const int64_t *offsets, int B, int H, int D, Schedule s, void *dq,
-                          int cus, hipStream_t stream) {
+                          const float *delta, const int64_t *offsets, const int64_t *offsets_kv, int B, int H, int D,
+                          Schedule s, void *dq, int cus, hipStream_t stream) {
 #define JFA_CASE(DD)                                                                                             \
     case DD:                                                                                                     \
-        hipLaunchKernelGGL(dq_bf16_kernel<DD>, dim3(persistent_grid<dq_bf16_kernel<DD>>(kBwdThreads, cus)), dim3(kBwdThreads), 0, stream, (const __bf16 *)q,      \
-                           (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, lse, delta, offsets, B, H, \
-                           s, (__bf16 *)dq);                                                                     \
+        if (offsets_kv)                                                                                          \
+            hipLaunchKernelGGL((dq_bf16_kernel<DD, true>), dim3(persistent_grid<dq_bf16_kernel<DD, true>>(kBwdThreads, cus)), dim3(kBwdThreads), 0, stream, \
+                               (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, lse, delta, offsets, offsets_kv, B, H, \
+                               s, (__bf16 *)dq);                                                                 \
+        else                                                                                                     \
+            hipLaunchKernelGGL((dq_bf16_kernel<DD, false>), dim3(persistent_grid<dq_bf16_kernel<DD, false>>(kBwdThreads, cus)), dim3(kBwdThreads), 0, stream, \
+                               (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, lse, delta, offsets, offsets_kv, B, H, \
+                               s, (__bf16 *)dq);                                                                 \
         break;
     switch (D) {
         JFA_CASE(32) JFA_CASE(64) JFA_CASE(128)

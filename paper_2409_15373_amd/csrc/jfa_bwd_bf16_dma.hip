@@ -47,14 +47,17 @@ __device__ inline void bd_dma4(const void *base, uint32_t byte_offset, char *lds
                                      (__attribute__((address_space(3))) void *)lds_wave_base, 4, 0, 0);
 }
 
-template <int MODE>
+// CROSS (cross attention): `offsets` belongs to the stationary rows (queries for dQ, keys for dK and dV) and
+// offsets_other to the rows that stream past them; otherwise offsets_other is not looked at.
+template <int MODE, bool CROSS>
 __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf16 *__restrict__ q,
                                                                      const __bf16 *__restrict__ k,
                                                                      const __bf16 *__restrict__ v,
                                                                      const __bf16 *__restrict__ dout,
                                                                      const float *__restrict__ lse,
                                                                      const float *__restrict__ delta,
-                                                                     const int64_t *__restrict__ offsets, int B, int H,
+                                                                     const int64_t *__restrict__ offsets,
+                                                                     const int64_t *__restrict__ offsets_other, int B, int H,
                                                                      Schedule s, __bf16 *__restrict__ grad) {
     constexpr int D = kBdD;
     constexpr int kKSteps = D / 16;
@@ -84,7 +87,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
     const float scale = 1.0f / sqrtf((float)D);
     const float c = 1.4426950408889634f * scale;
     const int64_t total = (int64_t)s.tile_start[B] * H;
-    const int64_t sum_B = offsets[B];
+    const int64_t sum_B = (CROSS && kRowStats) ? offsets_other[B] : offsets[B];   // query rows: lse and delta are indexed by them
     const int64_t row_stride = (int64_t)H * D;
 
     // LDS read addresses inside a tile
@@ -102,20 +105,33 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                 taddr[h2][db] = (r + 8 * h2) * 256 + (((db * 4 + chunk_in_group) ^ swz(r + 8 * h2)) << 4) + byte_in_chunk;
     }
     WorkCursor cursor;
-    if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor);
+    if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_other : nullptr);
     for (;;) {
         __syncthreads();   // the slot is written; the previous tile is finished
         Work t;
-        if (!load_work(&slot, t)) break;
+        if (!load_work<CROSS>(&slot, t)) break;
         __syncthreads();   // every wave has read the slot before wave 0 refills it
-        const int L = t.len;
+        const int Ls = t.len;                      // stationary rows of the sample
+        const int L = CROSS ? t.olen : t.len;      // streamed rows of the sample
+        const int64_t srow0 = CROSS ? t.orow0 : t.row0;
         const int n_stages = (L + kBdBN - 1) / kBdBN;
-        const int64_t head_off = t.row0 * row_stride + (int64_t)t.head * D;
+        const int64_t head_off = srow0 * row_stride + (int64_t)t.head * D;
+        if (CROSS && L == 0) {   // nothing streams past these rows: their gradient is zero
+            if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, offsets_other);
+            const int i = t.block * kDmaBlockRows + wave * 32 + (lane & 31);
+            if (i < Ls) {
+                __bf16 *grow = grad + (t.row0 + i) * row_stride + (int64_t)t.head * D + (lane >> 5) * (D / 2);
+#pragma unroll
+                for (int e = 0; e < D / 2; e += 8) *reinterpret_cast<u32x4 *>(grow + e) = u32x4{0, 0, 0, 0};
+            }
+            continue;
+        }
         const __bf16 *abase = (MODE == kModeDQ ? k : q) + head_off;
         const __bf16 *bbase = (MODE == kModeDQ ? v : dout) + head_off;
         // plane 0 of the statistics buffer: delta; plane 1: -lse * log2(e), written by the delta kernel
-        const float *delta_rows = delta + (int64_t)t.head * sum_B + t.row0;
-        const float *lse2_rows = delta + (int64_t)(H + t.head) * sum_B + t.row0;
+        const int64_t qrow0 = kRowStats ? srow0 : t.row0;   // first query row of the sample
+        const float *delta_rows = delta + (int64_t)t.head * sum_B + qrow0;
+        const float *lse2_rows = delta + (int64_t)(H + t.head) * sum_B + qrow0;
 
         // The per-lane byte offsets of the two DMA chunks of a stage are rebuilt from the thread id at every
         // issue (a handful of VALU operations per stage) instead of living in registers across the stage: values
@@ -152,8 +168,8 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
 
         // ---- stationary rows: this lane's row as B operands ----
         const int i = t.block * kDmaBlockRows + wave * 32 + col;
-        const int ic = i < L ? i : L - 1;
-        const bool wave_active = t.block * kDmaBlockRows + wave * 32 < L;
+        const int ic = i < Ls ? i : Ls - 1;
+        const bool wave_active = t.block * kDmaBlockRows + wave * 32 < Ls;
         bf16x8 xreg[kKSteps], yreg[kKSteps];   // dQ: Q, dO rows   dK: K, V rows   dV: K rows
         {
             const int64_t off = (t.row0 + ic) * row_stride + (int64_t)t.head * D + 8 * half;
@@ -320,7 +336,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
 
         issue_stage(IntB<0>{}, 0);
         if (n_stages > 1) issue_stage(IntB<1>{}, 1);
-        if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor);   // overlaps with the loads in flight
+        if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_other : nullptr);   // overlaps with the loads in flight
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) {
             asm volatile("" : "+v"(xreg[ks]));   // stationary-row loads complete here
@@ -379,7 +395,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                 const int r = it * 4 + (lane_e >> 4);
                 const u32x4 rowpiece = *reinterpret_cast<const u32x4 *>(region + r * 256 + (((lane_e & 15) ^ (r & 15)) << 4));
                 char *dst = reinterpret_cast<char *>(gbase + (int64_t)it * 4 * row_stride) + lane_off;
-                if (r0 + r < L) *reinterpret_cast<u32x4 *>(dst) = rowpiece;
+                if (r0 + r < Ls) *reinterpret_cast<u32x4 *>(dst) = rowpiece;
             }
         }
     }
@@ -387,22 +403,28 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
 
 template <int MODE>
 static hipError_t launch_mode(const void *q, const void *k, const void *v, const void *dout, const float *lse,
-                              const float *delta, const int64_t *offsets, int B, int H, Schedule s, void *grad, int cus,
-                              hipStream_t stream) {
-    hipLaunchKernelGGL(bwd_bf16_dma_kernel<MODE>, dim3(persistent_grid<bwd_bf16_dma_kernel<MODE>>(kBdThreads, cus)),
-                       dim3(kBdThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,
-                       (const __bf16 *)dout, lse, delta, offsets, B, H, s, (__bf16 *)grad);
+                              const float *delta, const int64_t *offsets, const int64_t *offsets_other, int B, int H,
+                              Schedule s, void *grad, int cus, hipStream_t stream) {
+    if (offsets_other)
+        hipLaunchKernelGGL((bwd_bf16_dma_kernel<MODE, true>), dim3(persistent_grid<bwd_bf16_dma_kernel<MODE, true>>(kBdThreads, cus)),
+                           dim3(kBdThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,
+                           (const __bf16 *)dout, lse, delta, offsets, offsets_other, B, H, s, (__bf16 *)grad);
+    else
+        hipLaunchKernelGGL((bwd_bf16_dma_kernel<MODE, false>), dim3(persistent_grid<bwd_bf16_dma_kernel<MODE, false>>(kBdThreads, cus)),
+                           dim3(kBdThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,
+                           (const __bf16 *)dout, lse, delta, offsets, offsets_other, B, H, s, (__bf16 *)grad);
     return hipGetLastError();
 }
 
 hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const void *v, const void *dout,
-                               const float *lse, const float *delta, const int64_t *offsets, int B, int H, int D,
-                               Schedule s, void *grad, int cus, hipStream_t stream) {
+                               const float *lse, const float *delta, const int64_t *offsets,
+                               const int64_t *offsets_other, int B, int H, int D, Schedule s, void *grad, int cus,
+                               hipStream_t stream) {
     if (D != kBdD) return hipErrorInvalidValue;
     switch (mode) {
-        case kModeDQ: return launch_mode<kModeDQ>(q, k, v, dout, lse, delta, offsets, B, H, s, grad, cus, stream);
-        case kModeDK: return launch_mode<kModeDK>(q, k, v, dout, lse, delta, offsets, B, H, s, grad, cus, stream);
-        case kModeDV: return launch_mode<kModeDV>(q, k, v, dout, lse, delta, offsets, B, H, s, grad, cus, stream);
+        case kModeDQ: return launch_mode<kModeDQ>(q, k, v, dout, lse, delta, offsets, offsets_other, B, H, s, grad, cus, stream);
+        case kModeDK: return launch_mode<kModeDK>(q, k, v, dout, lse, delta, offsets, offsets_other, B, H, s, grad, cus, stream);
+        case kModeDV: return launch_mode<kModeDV>(q, k, v, dout, lse, delta, offsets, offsets_other, B, H, s, grad, cus, stream);
         default: return hipErrorInvalidValue;
     }
 }

@@ -109,6 +109,10 @@ struct Work {
     int block;    // row-block index inside the sample
     int64_t row0; // offsets[b]
     int len;      // L_b
+    // Cross attention: the sample's rows on the other side (the rows that stream past the block: keys for a
+    // block of queries, queries for a block of keys), from a second offsets array.  Equal to row0 / len otherwise.
+    int64_t orow0;
+    int olen;
 };
 
 // Largest p in [0, B) with tile_start[p] * H <= w, for w < tile_start[B] * H.
@@ -121,7 +125,8 @@ __device__ inline int find_position(const int32_t *tile_start, int B, int H, int
     return lo;
 }
 
-__device__ inline Work decode_work(const Schedule &s, const int64_t *offsets, int B, int H, int64_t w) {
+__device__ inline Work decode_work(const Schedule &s, const int64_t *offsets, int B, int H, int64_t w,
+                                   const int64_t *offsets_other = nullptr) {
     Work t;
     const int p = find_position(s.tile_start, B, H, w);
     const int t0 = s.tile_start[p];
@@ -132,6 +137,12 @@ __device__ inline Work decode_work(const Schedule &s, const int64_t *offsets, in
     t.block = r - t.head * n;
     t.row0 = offsets[t.sample];
     t.len = (int)(offsets[t.sample + 1] - t.row0);
+    t.orow0 = t.row0;
+    t.olen = t.len;
+    if (offsets_other) {
+        t.orow0 = offsets_other[t.sample];
+        t.olen = (int)(offsets_other[t.sample + 1] - t.orow0);
+    }
     return t;
 }
 
@@ -154,6 +165,7 @@ struct WorkSlot {
     int valid;   // 0: nothing left
     int sample, head, block, len;
     int row0_lo, row0_hi;
+    int olen, orow0_lo, orow0_hi;   // the other side's rows (cross attention only)
 };
 
 // Largest p in [0, B) with tile_start[p] * H <= w, found by one wave: 64 probes per round instead of one.
@@ -175,7 +187,7 @@ __device__ inline int find_position_wave(const int32_t *tile_start, int B, int H
 // made by its lane 0, whose registers hold `cur`); meant to be issued right after a tile's first loads so
 // that its latency chain (atomic, search, offsets) overlaps with theirs.
 __device__ inline void claim_and_decode(WorkSlot *slot, const Schedule &s, const int64_t *offsets, int B, int H,
-                                        int64_t total, WorkCursor &cur) {
+                                        int64_t total, WorkCursor &cur, const int64_t *offsets_other = nullptr) {
     const int lane = threadIdx.x & 63;
     int64_t w = -1;
     if (lane == 0) w = next_work(s.counter, cur, total);
@@ -191,6 +203,15 @@ __device__ inline void claim_and_decode(WorkSlot *slot, const Schedule &s, const
     const int sample = s.order[p];
     const int64_t row0 = offsets[sample];
     const int len = (int)(offsets[sample + 1] - row0);
+    if (offsets_other) {
+        const int64_t orow0 = offsets_other[sample];
+        const int olen = (int)(offsets_other[sample + 1] - orow0);
+        if (lane == 0) {
+            slot->olen = olen;
+            slot->orow0_lo = (int)(uint32_t)orow0;
+            slot->orow0_hi = (int)(uint32_t)((uint64_t)orow0 >> 32);
+        }
+    }
     if (lane == 0) {
         slot->valid = 1;
         slot->sample = sample;
@@ -202,7 +223,9 @@ __device__ inline void claim_and_decode(WorkSlot *slot, const Schedule &s, const
     }
 }
 
-// Read the parked work item into scalar registers; returns false when nothing is left.
+// Read the parked work item into scalar registers; returns false when nothing is left.  CROSS: the slot also holds
+// the other side's rows.
+template <bool CROSS = false>
 __device__ inline bool load_work(const WorkSlot *slot, Work &t) {
     if (__builtin_amdgcn_readfirstlane(slot->valid) == 0) return false;
     t.sample = __builtin_amdgcn_readfirstlane(slot->sample);
@@ -212,6 +235,14 @@ __device__ inline bool load_work(const WorkSlot *slot, Work &t) {
     const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane(slot->row0_lo);
     const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane(slot->row0_hi);
     t.row0 = (int64_t)(((uint64_t)hi << 32) | lo);
+    t.orow0 = t.row0;
+    t.olen = t.len;
+    if (CROSS) {
+        t.olen = __builtin_amdgcn_readfirstlane(slot->olen);
+        const uint32_t olo = (uint32_t)__builtin_amdgcn_readfirstlane(slot->orow0_lo);
+        const uint32_t ohi = (uint32_t)__builtin_amdgcn_readfirstlane(slot->orow0_hi);
+        t.orow0 = (int64_t)(((uint64_t)ohi << 32) | olo);
+    }
     return true;
 }
 
@@ -224,11 +255,14 @@ hipError_t launch_check_offsets(const int64_t *offsets, int B, int64_t max_len, 
 
 // fp32 path
 constexpr int kF32BlockRows = 64;
-hipError_t launch_fwd_f32(const float *q, const float *k, const float *v, const int64_t *offsets, int B, int H, int D,
-                          Schedule s, float *out, float *lse, int cus, hipStream_t stream);
+// Cross attention: offsets = the queries' offsets, offsets_kv = the keys' (nullptr: the same array); schedules are
+// built over the stationary side's offsets (s, s_dq: queries; s_dkv: keys).
+hipError_t launch_fwd_f32(const float *q, const float *k, const float *v, const int64_t *offsets,
+                          const int64_t *offsets_kv, int B, int H, int D, Schedule s, float *out, float *lse, int cus,
+                          hipStream_t stream);
 hipError_t launch_bwd_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
-                          const float *lse, const int64_t *offsets, int B, int H, int D, Schedule s_dq,
-                          Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int cus,
+                          const float *lse, const int64_t *offsets, const int64_t *offsets_kv, int B, int H, int D,
+                          Schedule s_dq, Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int cus,
                           hipStream_t stream);
 // delta[h, row] = sum_d dout * out, for T = float or bf16 (is_bf16)
 hipError_t launch_delta(const void *out, const void *dout, const float *lse, const int64_t *offsets, int B, int H,
@@ -237,23 +271,28 @@ hipError_t launch_delta(const void *out, const void *dout, const float *lse, con
 // bf16 attention, register-staged kernels (any supported D, short samples)
 constexpr int kFwdBlockRows = 128;
 constexpr int kBwdBlockRows = 128;
-hipError_t launch_fwd_bf16(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H, int D,
-                           Schedule s, void *out, float *lse, int cus, hipStream_t stream);
+// In all bf16 launchers `offsets` belongs to the rows the schedule `s` was built over (queries for the forward and
+// dQ, keys for dK / dV) and the second array to the rows that stream past them (cross attention; nullptr: the same).
+hipError_t launch_fwd_bf16(const void *q, const void *k, const void *v, const int64_t *offsets,
+                           const int64_t *offsets_kv, int B, int H, int D, Schedule s, void *out, float *lse, int cus,
+                           hipStream_t stream);
 hipError_t launch_dkv_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
-                           const float *delta, const int64_t *offsets, int B, int H, int D, Schedule s, void *dk,
-                           void *dv, int cus, hipStream_t stream);
+                           const float *delta, const int64_t *offsets, const int64_t *offsets_q, int B, int H, int D,
+                           Schedule s, void *dk, void *dv, int cus, hipStream_t stream);
 hipError_t launch_dq_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
-                          const float *delta, const int64_t *offsets, int B, int H, int D, Schedule s, void *dq,
-                          int cus, hipStream_t stream);
+                          const float *delta, const int64_t *offsets, const int64_t *offsets_kv, int B, int H, int D,
+                          Schedule s, void *dq, int cus, hipStream_t stream);
 
 // bf16 attention, direct-to-LDS kernels (D = 128, long samples; work items are blocks of kDmaBlockRows rows)
 constexpr int kDmaBlockRows = 256;
-hipError_t launch_fwd_bf16_dma(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H,
-                               int D, Schedule s, void *out, float *lse, int cus, hipStream_t stream);
+hipError_t launch_fwd_bf16_dma(const void *q, const void *k, const void *v, const int64_t *offsets,
+                               const int64_t *offsets_kv, int B, int H, int D, Schedule s, void *out, float *lse, int cus,
+                               hipStream_t stream);
 // mode: 0 = dQ, 1 = dK, 2 = dV
 hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const void *v, const void *dout,
-                               const float *lse, const float *delta, const int64_t *offsets, int B, int H, int D,
-                               Schedule s, void *grad, int cus, hipStream_t stream);
+                               const float *lse, const float *delta, const int64_t *offsets,
+                               const int64_t *offsets_other, int B, int H, int D, Schedule s, void *grad, int cus,
+                               hipStream_t stream);
 
 // Unfused jagged attention (Table 1): offsets of the jagged square array, then the three operators.
 hipError_t launch_square_offsets(const int64_t *offsets, int B, int64_t *sq, hipStream_t stream);

@@ -39,7 +39,8 @@ __device__ inline int64_t fetch_work(int32_t *counters, WorkCursor &probe, int64
 template <int D>
 __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(const float *__restrict__ q, const float *__restrict__ k,
                                                            const float *__restrict__ v,
-                                                           const int64_t *__restrict__ offsets, int B, int H,
+                                                           const int64_t *__restrict__ offsets,
+                                                           const int64_t *__restrict__ offsets_kv, int B, int H,
                                                            Schedule s, float *__restrict__ out,
                                                            float *__restrict__ lse) {
     constexpr int kPer = D / 4;
@@ -54,7 +55,7 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(const float *__restri
     const int64_t sum_B = offsets[B];
 
     for (int64_t w = fetch_work(s.counter, probe, total, &slot); w >= 0; w = fetch_work(s.counter, probe, total, &slot)) {
-        const Work t = decode_work(s, offsets, B, H, w);
+        const Work t = decode_work(s, offsets, B, H, w, offsets_kv);   // keys: rows orow0 .. orow0 + olen - 1
         const int i = t.block * kRows + r;                    // query index inside the sample
         const int iq = i < t.len ? i : t.len - 1;             // rows past the end recompute the last row
         float qr[kPer], acc[kPer];
@@ -63,11 +64,11 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(const float *__restri
             acc[e] = 0.0f;
         }
         float m = -INFINITY, l = 0.0f;
-        for (int j0 = 0; j0 < t.len; j0 += kCols) {
-            const int n = t.len - j0 < kCols ? t.len - j0 : kCols;
+        for (int j0 = 0; j0 < t.olen; j0 += kCols) {
+            const int n = t.olen - j0 < kCols ? t.olen - j0 : kCols;
             __syncthreads();
-            stage_rows<D>(Ks, k, t.row0 + j0, n, t.head, H);
-            stage_rows<D>(Vs, v, t.row0 + j0, n, t.head, H);
+            stage_rows<D>(Ks, k, t.orow0 + j0, n, t.head, H);
+            stage_rows<D>(Vs, v, t.orow0 + j0, n, t.head, H);
             __syncthreads();
             for (int j = 0; j < n; ++j) {
                 float part = 0.0f;
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(const float *__restri
             }
         }
         if (i < t.len) {
-            const float inv = 1.0f / l;
+            const float inv = l > 0.0f ? 1.0f / l : 0.0f;   // a sample without keys: out = 0, lse = -inf
             for (int e = 0; e < kPer; ++e) out[((t.row0 + i) * H + t.head) * (int64_t)D + 4 * e + c] = acc[e] * inv;
             if (c == 0) lse[(int64_t)t.head * sum_B + t.row0 + i] = m + logf(l);
         }
@@ -96,7 +97,8 @@ __global__ __launch_bounds__(kThreads) void dq_f32_kernel(const float *__restric
                                                           const float *__restrict__ dout,
                                                           const float *__restrict__ lse,
                                                           const float *__restrict__ delta,
-                                                          const int64_t *__restrict__ offsets, int B, int H,
+                                                          const int64_t *__restrict__ offsets,
+                                                          const int64_t *__restrict__ offsets_kv, int B, int H,
                                                           Schedule s, float *__restrict__ dq) {
     constexpr int kPer = D / 4;
     constexpr int kCols = cols_for<D>();
@@ -110,7 +112,7 @@ __global__ __launch_bounds__(kThreads) void dq_f32_kernel(const float *__restric
     const int64_t sum_B = offsets[B];
 
     for (int64_t w = fetch_work(s.counter, probe, total, &slot); w >= 0; w = fetch_work(s.counter, probe, total, &slot)) {
-        const Work t = decode_work(s, offsets, B, H, w);
+        const Work t = decode_work(s, offsets, B, H, w, offsets_kv);
         const int i = t.block * kRows + r;
         const int iq = i < t.len ? i : t.len - 1;
         float qr[kPer], dor[kPer], acc[kPer];
@@ -122,11 +124,11 @@ __global__ __launch_bounds__(kThreads) void dq_f32_kernel(const float *__restric
         }
         const float lse_i = lse[(int64_t)t.head * sum_B + t.row0 + iq];
         const float delta_i = delta[(int64_t)t.head * sum_B + t.row0 + iq];
-        for (int j0 = 0; j0 < t.len; j0 += kCols) {
-            const int n = t.len - j0 < kCols ? t.len - j0 : kCols;
+        for (int j0 = 0; j0 < t.olen; j0 += kCols) {
+            const int n = t.olen - j0 < kCols ? t.olen - j0 : kCols;
             __syncthreads();
-            stage_rows<D>(Ks, k, t.row0 + j0, n, t.head, H);
-            stage_rows<D>(Vs, v, t.row0 + j0, n, t.head, H);
+            stage_rows<D>(Ks, k, t.orow0 + j0, n, t.head, H);
+            stage_rows<D>(Vs, v, t.orow0 + j0, n, t.head, H);
             __syncthreads();
             for (int j = 0; j < n; ++j) {
                 float ps = 0.0f, pd = 0.0f;
@@ -151,7 +153,8 @@ __global__ __launch_bounds__(kThreads) void dkv_f32_kernel(const float *__restri
                                                            const float *__restrict__ dout,
                                                            const float *__restrict__ lse,
                                                            const float *__restrict__ delta,
-                                                           const int64_t *__restrict__ offsets, int B, int H,
+                                                           const int64_t *__restrict__ offsets,   // of the keys
+                                                           const int64_t *__restrict__ offsets_q, int B, int H,
                                                            Schedule s, float *__restrict__ dk,
                                                            float *__restrict__ dv) {
     constexpr int kPer = D / 4;
@@ -165,10 +168,10 @@ __global__ __launch_bounds__(kThreads) void dkv_f32_kernel(const float *__restri
     const int r = threadIdx.x >> 2, c = threadIdx.x & 3;
     const float scale = 1.0f / sqrtf((float)D);
     const int64_t total = (int64_t)s.tile_start[B] * H;
-    const int64_t sum_B = offsets[B];
+    const int64_t sum_B = offsets_q ? offsets_q[B] : offsets[B];   // lse and delta are indexed by query rows
 
     for (int64_t w = fetch_work(s.counter, probe, total, &slot); w >= 0; w = fetch_work(s.counter, probe, total, &slot)) {
-        const Work t = decode_work(s, offsets, B, H, w);
+        const Work t = decode_work(s, offsets, B, H, w, offsets_q);   // queries: rows orow0 .. orow0 + olen - 1
         const int j = t.block * kRows + r;
         const int jk = j < t.len ? j : t.len - 1;
         float kr[kPer], vr[kPer], acck[kPer], accv[kPer];
@@ -179,14 +182,14 @@ __global__ __launch_bounds__(kThreads) void dkv_f32_kernel(const float *__restri
             acck[e] = 0.0f;
             accv[e] = 0.0f;
         }
-        for (int i0 = 0; i0 < t.len; i0 += kCols) {
-            const int n = t.len - i0 < kCols ? t.len - i0 : kCols;
+        for (int i0 = 0; i0 < t.olen; i0 += kCols) {
+            const int n = t.olen - i0 < kCols ? t.olen - i0 : kCols;
             __syncthreads();
-            stage_rows<D>(Qs, q, t.row0 + i0, n, t.head, H);
-            stage_rows<D>(Os, dout, t.row0 + i0, n, t.head, H);
+            stage_rows<D>(Qs, q, t.orow0 + i0, n, t.head, H);
+            stage_rows<D>(Os, dout, t.orow0 + i0, n, t.head, H);
             if (threadIdx.x < n) {
-                lse_s[threadIdx.x] = lse[(int64_t)t.head * sum_B + t.row0 + i0 + threadIdx.x];
-                delta_s[threadIdx.x] = delta[(int64_t)t.head * sum_B + t.row0 + i0 + threadIdx.x];
+                lse_s[threadIdx.x] = lse[(int64_t)t.head * sum_B + t.orow0 + i0 + threadIdx.x];
+                delta_s[threadIdx.x] = delta[(int64_t)t.head * sum_B + t.orow0 + i0 + threadIdx.x];
             }
             __syncthreads();
             for (int i = 0; i < n; ++i) {
@@ -263,11 +266,12 @@ hipError_t launch_delta(const void *out, const void *dout, const float *lse, con
     return hipGetLastError();
 }
 
-hipError_t launch_fwd_f32(const float *q, const float *k, const float *v, const int64_t *offsets, int B, int H, int D,
-                          Schedule s, float *out, float *lse, int cus, hipStream_t stream) {
+hipError_t launch_fwd_f32(const float *q, const float *k, const float *v, const int64_t *offsets,
+                          const int64_t *offsets_kv, int B, int H, int D, Schedule s, float *out, float *lse, int cus,
+                          hipStream_t stream) {
 #define JFA_CASE(DD)                                                                                              \
     case DD:                                                                                                      \
-        hipLaunchKernelGGL(fwd_f32_kernel<DD>, dim3(persistent_grid<fwd_f32_kernel<DD>>(kThreads, cus)), dim3(kThreads), 0, stream, q, k, v, offsets, B, H, s, \
+        hipLaunchKernelGGL(fwd_f32_kernel<DD>, dim3(persistent_grid<fwd_f32_kernel<DD>>(kThreads, cus)), dim3(kThreads), 0, stream, q, k, v, offsets, offsets_kv, B, H, s, \
                            out, lse);                                                                             \
         break;
     switch (D) {
@@ -279,17 +283,17 @@ hipError_t launch_fwd_f32(const float *q, const float *k, const float *v, const 
 }
 
 hipError_t launch_bwd_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
-                          const float *lse, const int64_t *offsets, int B, int H, int D, Schedule s_dq,
-                          Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int cus,
+                          const float *lse, const int64_t *offsets, const int64_t *offsets_kv, int B, int H, int D,
+                          Schedule s_dq, Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int cus,
                           hipStream_t stream) {
     hipError_t e = launch_delta(out, dout, nullptr, offsets, B, H, D, false, delta, cus, stream);
     if (e != hipSuccess) return e;
 #define JFA_CASE(DD)                                                                                               \
     case DD:                                                                                                       \
         hipLaunchKernelGGL(dq_f32_kernel<DD>, dim3(persistent_grid<dq_f32_kernel<DD>>(kThreads, cus)), dim3(kThreads), 0, stream, q, k, v, dout, lse, delta,   \
-                           offsets, B, H, s_dq, dq);                                                               \
+                           offsets, offsets_kv, B, H, s_dq, dq);                                                   \
         hipLaunchKernelGGL(dkv_f32_kernel<DD>, dim3(persistent_grid<dkv_f32_kernel<DD>>(kThreads, cus)), dim3(kThreads), 0, stream, q, k, v, dout, lse, delta,  \
-                           offsets, B, H, s_dkv, dk, dv);                                                          \
+                           offsets_kv ? offsets_kv : offsets, offsets_kv ? offsets : nullptr, B, H, s_dkv, dk, dv);  \
         break;
     switch (D) {
         JFA_CASE(32) JFA_CASE(64) JFA_CASE(128)

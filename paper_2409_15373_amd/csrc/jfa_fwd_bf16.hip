@@ -33,11 +33,14 @@ struct alignas(16) FwdSmem {
     int64_t slot;
 };
 
-template <int D>
+// CROSS: the keys and values of a sample are the rows of a second offsets array (cross attention); otherwise
+// offsets_kv is not looked at and the code is that of self attention.
+template <int D, bool CROSS>
 __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *__restrict__ q,
                                                                   const __bf16 *__restrict__ k,
                                                                   const __bf16 *__restrict__ v,
-                                                                  const int64_t *__restrict__ offsets, int B, int H,
+                                                                  const int64_t *__restrict__ offsets,
+                                                                  const int64_t *__restrict__ offsets_kv, int B, int H,
                                                                   Schedule s, __bf16 *__restrict__ out,
                                                                   float *__restrict__ lse) {
     constexpr int kKSteps = D / 16;               // contraction steps of S^T = K Q^T
@@ -71,15 +74,26 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
         __syncthreads();
         const int64_t w = uniform64(sm.slot);
         if (w < 0) break;
-        const Work t = decode_work(s, offsets, B, H, w);
-        const int L = t.len;
-        const __bf16 *kbase = k + t.row0 * row_stride + (int64_t)t.head * D;
-        const __bf16 *vbase = v + t.row0 * row_stride + (int64_t)t.head * D;
+        const Work t = decode_work(s, offsets, B, H, w, CROSS ? offsets_kv : nullptr);
+        const int Lq = t.len;                      // queries of the sample
+        const int L = CROSS ? t.olen : t.len;      // keys of the sample
+        const int64_t krow0 = CROSS ? t.orow0 : t.row0;
+        const __bf16 *kbase = k + krow0 * row_stride + (int64_t)t.head * D;
+        const __bf16 *vbase = v + krow0 * row_stride + (int64_t)t.head * D;
 
         // ---- this lane's query row as B operands: Q[i][16 ks + 8 half .. +7] ----
         const int i = t.block * kFwdBlockRows + wave * 32 + col;   // query index inside the sample
-        const int iq = i < L ? i : L - 1;                           // rows past the end recompute the last row
-        const bool wave_active = t.block * kFwdBlockRows + wave * 32 < L;
+        const int iq = i < Lq ? i : Lq - 1;                         // rows past the end recompute the last row
+        const bool wave_active = t.block * kFwdBlockRows + wave * 32 < Lq;
+        if (CROSS && L == 0) {   // no keys: an empty softmax, out = 0 and lse = -inf
+            if (i < Lq) {
+                __bf16 *orow = out + (t.row0 + i) * row_stride + (int64_t)t.head * D;
+#pragma unroll
+                for (int e = 0; e < D / 2; e += 4) *reinterpret_cast<bf16x4 *>(orow + half * (D / 2) + e) = bf16x4{0, 0, 0, 0};
+                if (half == 0) lse[(int64_t)t.head * sum_B + t.row0 + i] = -INFINITY;
+            }
+            continue;
+        }
         bf16x8 qreg[kKSteps];
         {
             const __bf16 *qrow = q + (t.row0 + iq) * row_stride + (int64_t)t.head * D + 8 * half;
@@ -235,7 +249,7 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
 
         // ---- epilogue: normalise, store this lane's query row and its log-sum-exp ----
         const float l_total = pair_sum(lsum);
-        if (i < L) {
+        if (i < Lq) {
             const float inv = 1.0f / l_total;
             __bf16 *orow = out + (t.row0 + i) * row_stride + (int64_t)t.head * D;
 #pragma unroll
@@ -253,12 +267,17 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
     }
 }
 
-hipError_t launch_fwd_bf16(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H, int D,
-                           Schedule s, void *out, float *lse, int cus, hipStream_t stream) {
+hipError_t launch_fwd_bf16(const void *q, const void *k, const void *v, const int64_t *offsets,
+                           const int64_t *offsets_kv, int B, int H, int D, Schedule s, void *out, float *lse, int cus,
+                           hipStream_t stream) {
 #define JFA_CASE(DD)                                                                                         \
     case DD:                                                                                                 \
-        hipLaunchKernelGGL(fwd_bf16_kernel<DD>, dim3(persistent_grid<fwd_bf16_kernel<DD>>(kFwdThreads, cus)), dim3(kFwdThreads), 0, stream, (const __bf16 *)q, \
-                           (const __bf16 *)k, (const __bf16 *)v, offsets, B, H, s, (__bf16 *)out, lse);      \
+        if (offsets_kv)                                                                                      \
+            hipLaunchKernelGGL((fwd_bf16_kernel<DD, true>), dim3(persistent_grid<fwd_bf16_kernel<DD, true>>(kFwdThreads, cus)), dim3(kFwdThreads), 0, stream, \
+                               (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, offsets, offsets_kv, B, H, s, (__bf16 *)out, lse); \
+        else                                                                                                 \
+            hipLaunchKernelGGL((fwd_bf16_kernel<DD, false>), dim3(persistent_grid<fwd_bf16_kernel<DD, false>>(kFwdThreads, cus)), dim3(kFwdThreads), 0, stream, \
+                               (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, offsets, offsets_kv, B, H, s, (__bf16 *)out, lse); \
         break;
     switch (D) {
         JFA_CASE(32) JFA_CASE(64) JFA_CASE(128)

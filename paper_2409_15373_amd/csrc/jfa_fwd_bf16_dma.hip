@@ -37,10 +37,14 @@ __device__ inline void dma16b(const __bf16 *base, uint32_t byte_offset, char *ld
                                      (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
 }
 
+// CROSS: the keys and values of a sample are the rows of a second offsets array (cross attention); otherwise
+// offsets_kv is not looked at and the code is that of self attention.
+template <bool CROSS>
 __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf16 *__restrict__ q,
                                                                       const __bf16 *__restrict__ k,
                                                                       const __bf16 *__restrict__ v,
-                                                                      const int64_t *__restrict__ offsets, int B,
+                                                                      const int64_t *__restrict__ offsets,
+                                                                      const int64_t *__restrict__ offsets_kv, int B,
                                                                       int H, Schedule s, __bf16 *__restrict__ out,
                                                                       float *__restrict__ lse) {
     constexpr int D = kDmaD;
@@ -95,16 +99,29 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
     const int pc = lane & 15;
 
     WorkCursor cursor;
-    if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor);
+    if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_kv : nullptr);
     for (;;) {
         __syncthreads();   // the slot is written; the previous tile is finished
         Work t;
-        if (!load_work(&slot, t)) break;
+        if (!load_work<CROSS>(&slot, t)) break;
         __syncthreads();   // every wave has read the slot before wave 0 refills it
-        const int L = t.len;
+        const int Lq = t.len;                      // queries of the sample
+        const int L = CROSS ? t.olen : t.len;      // keys of the sample
+        const int64_t krow0 = CROSS ? t.orow0 : t.row0;
         const int n_stages = (L + kDmaBN - 1) / kDmaBN;
-        const __bf16 *kbase = k + t.row0 * row_stride + (int64_t)t.head * D;
-        const __bf16 *vbase = v + t.row0 * row_stride + (int64_t)t.head * D;
+        const __bf16 *kbase = k + krow0 * row_stride + (int64_t)t.head * D;
+        const __bf16 *vbase = v + krow0 * row_stride + (int64_t)t.head * D;
+        if (CROSS && L == 0) {   // no keys: an empty softmax, out = 0 and lse = -inf
+            if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, offsets_kv);
+            const int i = t.block * kDmaBlockRows + wave * 32 + (lane & 31);
+            if (i < Lq) {
+                __bf16 *orow = out + (t.row0 + i) * row_stride + (int64_t)t.head * D + (lane >> 5) * (D / 2);
+#pragma unroll
+                for (int e = 0; e < D / 2; e += 8) *reinterpret_cast<u32x4 *>(orow + e) = u32x4{0, 0, 0, 0};
+                if (lane < 32) lse[(int64_t)t.head * sum_B + t.row0 + i] = -INFINITY;
+            }
+            continue;
+        }
 
         // byte offsets of this lane's DMA chunks inside a full stage (K and V differ in the swizzle)
         uint32_t koffs[2], voffs[2];
@@ -132,8 +149,8 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         };
 
         const int i = t.block * kDmaBlockRows + wave * 32 + col;   // this lane's query
-        const int iq = i < L ? i : L - 1;
-        const bool wave_active = t.block * kDmaBlockRows + wave * 32 < L;
+        const int iq = i < Lq ? i : Lq - 1;
+        const bool wave_active = t.block * kDmaBlockRows + wave * 32 < Lq;
         bf16x8 qreg[kKSteps];
         {
             const __bf16 *qrow = q + (t.row0 + iq) * row_stride + (int64_t)t.head * D + 8 * half;
@@ -294,7 +311,7 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         if (tid == 0) restart = 0;
         issue_stage(IntC<0>{}, 0);
         if (n_stages > 1) issue_stage(IntC<1>{}, 1);
-        if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor);   // overlaps with the loads in flight
+        if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_kv : nullptr);   // overlaps with the loads in flight
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qreg[ks]));   // Q loads complete here
         // The softmax scale and the change to base-2 exponentials go into Q once per tile (q * log2(e) / sqrt(D),
@@ -390,20 +407,26 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
                 const int r = it * 4 + (lane_e >> 4);
                 const u32x4 rowpiece = *reinterpret_cast<const u32x4 *>(region + r * 256 + (((lane_e & 15) ^ (r & 15)) << 4));
                 char *dst = reinterpret_cast<char *>(obase + (int64_t)it * 4 * row_stride) + lane_off;   // scalar base + 32-bit lane offset
-                if (q0 + r < L) *reinterpret_cast<u32x4 *>(dst) = rowpiece;
+                if (q0 + r < Lq) *reinterpret_cast<u32x4 *>(dst) = rowpiece;
             }
         }
-        if (i < L && half == 0)
+        if (i < Lq && half == 0)
             lse[(int64_t)t.head * sum_B + t.row0 + i] = (m + fast_log2(l_total)) * 0.6931471805599453f;
     }
 }
 
-hipError_t launch_fwd_bf16_dma(const void *q, const void *k, const void *v, const int64_t *offsets, int B, int H,
-                               int D, Schedule s, void *out, float *lse, int cus, hipStream_t stream) {
+hipError_t launch_fwd_bf16_dma(const void *q, const void *k, const void *v, const int64_t *offsets,
+                               const int64_t *offsets_kv, int B, int H, int D, Schedule s, void *out, float *lse, int cus,
+                               hipStream_t stream) {
     if (D != kDmaD) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(fwd_bf16_dma_kernel, dim3(persistent_grid<fwd_bf16_dma_kernel>(kDmaThreads, cus)),
-                       dim3(kDmaThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, offsets,
-                       B, H, s, (__bf16 *)out, lse);
+    if (offsets_kv)
+        hipLaunchKernelGGL(fwd_bf16_dma_kernel<true>, dim3(persistent_grid<fwd_bf16_dma_kernel<true>>(kDmaThreads, cus)),
+                           dim3(kDmaThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, offsets,
+                           offsets_kv, B, H, s, (__bf16 *)out, lse);
+    else
+        hipLaunchKernelGGL(fwd_bf16_dma_kernel<false>, dim3(persistent_grid<fwd_bf16_dma_kernel<false>>(kDmaThreads, cus)),
+                           dim3(kDmaThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, offsets,
+                           offsets_kv, B, H, s, (__bf16 *)out, lse);
     return hipGetLastError();
 }
 

@@ -1,0 +1,126 @@
+"""Jagged cross attention (separate query and key offsets) on the GPU vs oracle/cross.py, forward and backward.
+
+Gates as for self attention: fp32 1e-5 (relative to max(1, |ref|)), bf16 2e-2 absolute and 1e-2 of the tensor's
+maximum.  Samples without keys must give out = 0, lse = -inf, dq = 0; samples without queries dk = dv = 0; guard rows
+after the last query and key rows must stay untouched.  Through the cross entry points with equal offsets the
+results must equal the self-attention entry points bit for bit (same arithmetic, other template instance).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import cross
+from paper_2409_15373_amd.synthetic import offsets_from_lengths, round_to_bf16_bits, bf16_bits_to_f32
+from helpers import f64, gate_bf16, gate_f32
+
+pytestmark = pytest.mark.gpu
+GUARD = 2
+
+
+def make(Lq, Lk, H, D, dtype, seed, sigma=1.0):
+    """Host arrays (float32 holding the exact values) and guarded device tensors for q, k, v, dout."""
+    rng = np.random.default_rng(seed)
+    oq, ok = offsets_from_lengths(np.array(Lq)), offsets_from_lengths(np.array(Lk))
+    host, dev = {}, {}
+    for name, n, s in (("q", oq[-1], sigma), ("k", ok[-1], sigma), ("v", ok[-1], 1.0), ("dout", oq[-1], 1.0)):
+        x = (rng.standard_normal((int(n), H, D)) * s).astype(np.float32)
+        if dtype == "bf16":
+            bits = round_to_bf16_bits(x)
+            x = bf16_bits_to_f32(bits)
+            t = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16)
+        else:
+            t = torch.from_numpy(x)
+        host[name] = x
+        dev[name] = torch.cat([t, torch.full((GUARD, H, D), float("nan"), dtype=t.dtype)]).cuda()   # rows past the end: never read
+    return host, dev, oq, ok
+
+
+def run(Lq, Lk, H, D, dtype, seed, max_len_q, max_len_kv, sigma=1.0):
+    from paper_2409_15373_amd import binding
+    host, dev, oq, ok = make(Lq, Lk, H, D, dtype, seed, sigma)
+    nq, nk = int(oq[-1]), int(ok[-1])
+    oqd, okd = torch.from_numpy(oq).cuda(), torch.from_numpy(ok).cuda()
+    tdt = dev["q"].dtype
+    out = torch.full((nq + GUARD, H, D), 777.0, dtype=tdt, device="cuda")
+    lse = torch.full((H, nq), 777.0, dtype=torch.float32, device="cuda")
+    binding.jfa_forward_cross(dev["q"], dev["k"], dev["v"], oqd, okd, max_len_q, max_len_kv, out=out, lse=lse)
+    torch.cuda.synchronize()
+    assert (out[nq:] == 777.0).all(), "guard rows of out were written"
+    dq = torch.full((nq + GUARD, H, D), 555.0, dtype=tdt, device="cuda")
+    dk = torch.full((nk + GUARD, H, D), 555.0, dtype=tdt, device="cuda")
+    dv = torch.full((nk + GUARD, H, D), 555.0, dtype=tdt, device="cuda")
+    out_in = out.clone(); out_in[nq:] = float("nan")
+    stats = torch.empty((2 if dtype == "bf16" else 1, H, nq), dtype=torch.float32, device="cuda")   # sized by the real row count
+    binding.jfa_backward_cross(dev["q"], dev["k"], dev["v"], out_in, dev["dout"], lse, oqd, okd, max_len_q, max_len_kv,
+                               dq=dq, dk=dk, dv=dv, delta=stats)
+    torch.cuda.synchronize()
+    delta = stats[0]
+    assert (dq[nq:] == 555.0).all() and (dk[nk:] == 555.0).all() and (dv[nk:] == 555.0).all(), "guard rows of a gradient were written"
+    got = dict(out=f64(out[:nq]), lse=f64(lse), dq=f64(dq[:nq]), dk=f64(dk[:nk]), dv=f64(dv[:nk]), delta=f64(delta))
+    r_out, r_lse = cross.forward(host["q"], host["k"], host["v"], oq, ok)
+    # the backward consumed the GPU's own out and lse: the oracle's gradients are those of the exact forward
+    r_dq, r_dk, r_dv, r_delta = cross.backward(host["q"], host["k"], host["v"], host["dout"], oq, ok)
+    ref = dict(out=r_out, lse=r_lse, dq=r_dq, dk=r_dk, dv=r_dv, delta=r_delta)
+    return got, ref, oq, ok
+
+
+def compare(got, ref, dtype, oq, ok, Lq, Lk):
+    empty_q_rows = np.concatenate([np.arange(oq[b], oq[b + 1]) for b in range(len(Lq)) if Lk[b] == 0] + [np.array([], dtype=np.int64)]).astype(np.int64)
+    fin = np.ones(ref["lse"].shape[1], dtype=bool); fin[empty_q_rows] = False
+    assert np.isneginf(got["lse"][:, ~fin]).all() and np.isneginf(ref["lse"][:, ~fin]).all()
+    assert (got["out"][~fin] == 0).all() and (got["dq"][~fin] == 0).all()
+    for b in range(len(Lq)):
+        if Lq[b] == 0:
+            assert (got["dk"][ok[b]:ok[b + 1]] == 0).all() and (got["dv"][ok[b]:ok[b + 1]] == 0).all()
+    pairs = [("out", got["out"], ref["out"]), ("lse", got["lse"][:, fin], ref["lse"][:, fin]), ("dq", got["dq"], ref["dq"]),
+             ("dk", got["dk"], ref["dk"]), ("dv", got["dv"], ref["dv"]), ("delta", got["delta"][:, fin], ref["delta"][:, fin])]
+    for name, g, r in pairs:
+        if dtype == "f32":
+            gate_f32(name, g, r, tol=2e-5, relative_to_one=True)
+        else:
+            gate_bf16(name, g, r, abs_tol=2e-2 * max(1.0, float(np.abs(r).max()) / 4))
+
+
+LQ = [37, 1, 0, 70, 64, 5, 130]
+LK = [5, 90, 12, 0, 64, 129, 1]
+
+
+@pytest.mark.parametrize("D", [32, 128])
+def test_cross_fp32(D):
+    got, ref, oq, ok = run(LQ, LK, 2, D, "f32", 1, 130, 129)
+    compare(got, ref, "f32", oq, ok, LQ, LK)
+
+
+@pytest.mark.parametrize("D,H", [(32, 1), (64, 3), (128, 2)])
+def test_cross_bf16_register_staged_kernels(D, H):
+    Lq = [300, 1, 0, 129, 128, 33, 65, 200]
+    Lk = [40, 257, 12, 0, 128, 300, 1, 64]
+    got, ref, oq, ok = run(Lq, Lk, H, D, "bf16", 2, 256, 256)      # max_len <= 256 keeps D = 128 on these kernels too
+    compare(got, ref, "bf16", oq, ok, Lq, Lk)
+
+
+def test_cross_bf16_direct_to_lds_kernels():
+    Lq = [300, 1, 0, 129, 700, 33, 257, 64]
+    Lk = [513, 64, 40, 0, 65, 1000, 31, 1]
+    got, ref, oq, ok = run(Lq, Lk, 2, 128, "bf16", 3, 1024, 1024)   # D = 128 and max_len > 256: the long-sample kernels
+    compare(got, ref, "bf16", oq, ok, Lq, Lk)
+
+
+@pytest.mark.parametrize("max_len", [256, 1024])
+def test_cross_with_equal_offsets_is_self_attention_bit_for_bit(max_len):
+    from paper_2409_15373_amd import binding
+    L = [300, 1, 0, 129, 64, 700 if max_len > 256 else 250]
+    host, dev, oq, _ = make(L, L, 2, 128, "bf16", 4)
+    od = torch.from_numpy(oq).cuda()
+    n = int(oq[-1])
+    lse_s, lse_x = (torch.empty((2, n), dtype=torch.float32, device="cuda") for _ in range(2))   # sized by the real row count
+    out_s, _ = binding.jfa_forward(dev["q"], dev["k"], dev["v"], od, max_len, lse=lse_s)
+    out_x, _ = binding.jfa_forward_cross(dev["q"], dev["k"], dev["v"], od, od.clone(), max_len, max_len, lse=lse_x)
+    torch.cuda.synchronize()
+    assert torch.equal(out_s[:n].view(torch.int16), out_x[:n].view(torch.int16)) and torch.equal(lse_s, lse_x)
+    st_s, st_x = (torch.empty((2, 2, n), dtype=torch.float32, device="cuda") for _ in range(2))
+    gs = binding.jfa_backward(dev["q"], dev["k"], dev["v"], out_s, dev["dout"], lse_s, od, max_len, delta=st_s)
+    gx = binding.jfa_backward_cross(dev["q"], dev["k"], dev["v"], out_s, dev["dout"], lse_s, od, od.clone(), max_len, max_len, delta=st_x)
+    torch.cuda.synchronize()
+    for a, b in zip(gs[:3], gx[:3]):
+        assert torch.equal(a[:n].view(torch.int16), b[:n].view(torch.int16))

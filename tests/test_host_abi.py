@@ -107,6 +107,25 @@ def test_unfused_conversion_and_feature_operator_argument_errors(lib):
     assert lib.jfa_jagged_softmax_backward(16, 16, 16, 1, 8, 64, 8, None) == BAD            # dx misaligned
 
 
+@pytest.mark.parametrize("suffix", ["", "_f32"])
+def test_cross_attention_argument_errors(lib, suffix):
+    from paper_2409_15373_amd import binding
+    OK, BAD, UNS = binding.JFA_OK, binding.JFA_ERR_INVALID_ARG, binding.JFA_ERR_UNSUPPORTED
+    fwd, bwd = getattr(lib, "jfa_forward_cross" + suffix), getattr(lib, "jfa_backward_cross" + suffix)
+    assert fwd(16, 16, 16, 16, None, 1, 8, 8, 1, 64, 16, 16, None) == BAD                    # offsets_kv is null
+    assert "offsets_kv" in binding.jfa_last_error()
+    assert fwd(16, 16, 16, 16, 8, 1, 8, 8, 1, 64, 16, 16, None) == BAD                       # offsets_kv misaligned
+    assert fwd(16, 16, 16, 16, 16, 1, 8, -8, 1, 64, 16, 16, None) == BAD
+    assert "max_len_kv" in binding.jfa_last_error()
+    assert fwd(16, 16, 16, 16, 16, 1, 8, 8, 1, 80, 16, 16, None) == UNS
+    assert fwd(None, None, None, None, None, 0, 8, 8, 1, 64, None, None, None) == OK         # B == 0: nothing to do
+    n = [16] * 6
+    assert bwd(*n, 16, None, 1, 8, 8, 1, 64, 16, 16, 16, 16, None) == BAD
+    assert bwd(*n, 16, 16, -1, 8, 8, 1, 64, 16, 16, 16, 16, None) == BAD
+    assert bwd(*n, 16, 16, 1, 8, 8, 0, 64, 16, 16, 16, 16, None) == BAD                      # H = 0
+    assert bwd(*([None] * 8), 0, 8, 8, 1, 64, None, None, None, None, None) == OK
+
+
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     from paper_2409_15373_amd import binding
     monkeypatch.setattr(binding, "_lib", None)
