@@ -112,6 +112,23 @@ int jfa_backward_cross_f32(const float *q, const float *k, const float *v, const
                            float *delta, void *stream);
 
 /*
+ * Causal self attention on jagged tensors: row i of a sample attends to rows 0 .. i of the same sample (the order
+ * of a sample's rows is the order of its sequence), as sequential recommendation models use it.  Arguments, layouts,
+ * lse and delta exactly as for jfa_forward / jfa_backward (and their _f32 variants); lse_i is the log-sum-exp over
+ * the keys j <= i.
+ */
+int jfa_forward_causal(const void *q, const void *k, const void *v, const int64_t *offsets, int64_t B, int64_t max_len,
+                       int H, int D, void *out, float *lse, void *stream);
+int jfa_forward_causal_f32(const float *q, const float *k, const float *v, const int64_t *offsets, int64_t B,
+                           int64_t max_len, int H, int D, float *out, float *lse, void *stream);
+int jfa_backward_causal(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
+                        const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, void *dq, void *dk, void *dv,
+                        float *delta, void *stream);
+int jfa_backward_causal_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
+                            const float *lse, const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, float *dq,
+                            float *dk, float *dv, float *delta, void *stream);
+
+/*
  * Unfused jagged attention: the three separate jagged operators of the paper's Table 1 (a jagged x jagged product
  * with a jagged square output, a softmax over that output, and its product with a jagged tensor), which write the
  * score array to memory.  They are the baseline that Section 3 compares the fused kernel with, provided here

@@ -28,7 +28,8 @@ EXPORTS = (
     "jfa_timing_read", "jfa_square_offsets", "jfa_unfused_scores", "jfa_unfused_softmax", "jfa_unfused_apply",
     "jfa_jagged_to_dense", "jfa_dense_to_jagged", "jfa_jagged_dense_bmm", "jfa_jagged_jagged_bmm",
     "jfa_jagged_softmax", "jfa_jagged_softmax_backward", "jfa_forward_cross", "jfa_forward_cross_f32",
-    "jfa_backward_cross", "jfa_backward_cross_f32",
+    "jfa_backward_cross", "jfa_backward_cross_f32", "jfa_forward_causal", "jfa_forward_causal_f32",
+    "jfa_backward_causal", "jfa_backward_causal_f32",
 )
 
 
@@ -62,6 +63,12 @@ def load() -> ctypes.CDLL:
     for name in ("jfa_backward_cross", "jfa_backward_cross_f32"):
         getattr(lib, name).restype = i32
         getattr(lib, name).argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp]
+    for name in ("jfa_forward_causal", "jfa_forward_causal_f32"):
+        getattr(lib, name).restype = i32
+        getattr(lib, name).argtypes = lib.jfa_forward.argtypes
+    for name in ("jfa_backward_causal", "jfa_backward_causal_f32"):
+        getattr(lib, name).restype = i32
+        getattr(lib, name).argtypes = lib.jfa_backward.argtypes
     lib.jfa_build_schedule.restype = i32
     lib.jfa_build_schedule.argtypes = [vp, i64, i32, vp, vp, vp]
     lib.jfa_check_offsets.restype = i32
@@ -127,9 +134,10 @@ def _pick(dtype: torch.dtype, bf16_name: str):
 
 
 def jfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, offsets: torch.Tensor, max_len: int,
-                out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None
+                out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None, causal: bool = False
                 ) -> Tuple[torch.Tensor, torch.Tensor]:
-    """out [sum_B, H, D] (dtype of q) and lse fp32 [H, sum_B]; dispatches on q.dtype (bf16 / fp32)."""
+    """out [sum_B, H, D] (dtype of q) and lse fp32 [H, sum_B]; dispatches on q.dtype (bf16 / fp32).
+    causal: row i of a sample attends to rows 0 .. i only (jfa_forward_causal)."""
     sum_B, H, D = q.shape
     assert k.shape == q.shape and v.shape == q.shape and k.dtype == q.dtype and v.dtype == q.dtype
     assert offsets.dtype == torch.int64 and offsets.is_cuda and offsets.dim() == 1
@@ -138,12 +146,13 @@ def jfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, offsets: torc
         out = torch.empty_like(q)
     if lse is None:
         lse = torch.empty((H, sum_B), dtype=torch.float32, device=q.device)
-    fn = _pick(q.dtype, "jfa_forward")
+    fn = _pick(q.dtype, "jfa_forward_causal" if causal else "jfa_forward")
     _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(offsets), B, max_len, H, D, _ptr(out), _ptr(lse), _stream()))
     return out, lse
 
 
-def jfa_backward(q, k, v, out, dout, lse, offsets, max_len: int, dq=None, dk=None, dv=None, delta=None):
+def jfa_backward(q, k, v, out, dout, lse, offsets, max_len: int, dq=None, dk=None, dv=None, delta=None,
+                 causal: bool = False):
     """dq, dk, dv [sum_B, H, D] (dtype of q) and delta fp32 [H, sum_B].
 
     The statistics buffer handed to the library is fp32 [H, sum_B] for fp32 inputs and fp32 [2, H, sum_B] for
@@ -157,7 +166,7 @@ def jfa_backward(q, k, v, out, dout, lse, offsets, max_len: int, dq=None, dk=Non
     dv = torch.empty_like(q) if dv is None else dv
     planes = 2 if q.dtype == torch.bfloat16 else 1
     stats = torch.empty((planes, H, sum_B), dtype=torch.float32, device=q.device) if delta is None else delta
-    fn = _pick(q.dtype, "jfa_backward")
+    fn = _pick(q.dtype, "jfa_backward_causal" if causal else "jfa_backward")
     _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(dout), _ptr(lse), _ptr(offsets), B, max_len, H, D,
               _ptr(dq), _ptr(dk), _ptr(dv), _ptr(stats), _stream()))
     return dq, dk, dv, (stats[0] if delta is None else delta)

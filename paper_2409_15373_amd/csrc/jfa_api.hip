@@ -233,7 +233,7 @@ hipError_t schedule(const int64_t *offsets, int64_t B, int block_rows, const Vie
     return jfa::launch_schedule(offsets, (int)B, block_rows, w.order[which], w.tile_start[which], w.counters, jfa::kNumCounters, s);
 }
 
-int forward_impl(const char *who, bool f32, const void *q, const void *k, const void *v, const int64_t *offsets,
+int forward_impl(const char *who, bool f32, bool causal, const void *q, const void *k, const void *v, const int64_t *offsets,
                  const int64_t *offsets_kv, int64_t B, int64_t max_len, int64_t max_len_kv, int H, int D, void *out,
                  float *lse, hipStream_t s) {
     const void *ptrs[] = {q, k, v, offsets, out, lse};
@@ -243,18 +243,19 @@ int forward_impl(const char *who, bool f32, const void *q, const void *k, const 
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
-    const FwdVariant variant = f32 ? kNarrow : forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H);
+    // causal attention runs on the register-staged kernels at every length (the direct-to-LDS kernels have no causal form)
+    const FwdVariant variant = (f32 || causal) ? kNarrow : forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H);
     e = schedule(offsets, B, f32 ? jfa::kF32BlockRows : (variant == kNarrow ? jfa::kFwdBlockRows : jfa::kDmaBlockRows), w, 0, s);
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
-    if (f32) { ScopedTimer tm("fwd_f32", s); e = jfa::launch_fwd_f32((const float *)q, (const float *)k, (const float *)v, offsets, offsets_kv, (int)B, H, D, sc, (float *)out, lse, w.cus, s); }
+    if (f32) { ScopedTimer tm("fwd_f32", s); e = jfa::launch_fwd_f32((const float *)q, (const float *)k, (const float *)v, offsets, offsets_kv, causal, (int)B, H, D, sc, (float *)out, lse, w.cus, s); }
     else if (variant == kDma) { ScopedTimer tm("fwd_bf16_dma", s); e = jfa::launch_fwd_bf16_dma(q, k, v, offsets, offsets_kv, (int)B, H, D, sc, out, lse, w.cus, s); }
-    else { ScopedTimer tm("fwd_bf16", s); e = jfa::launch_fwd_bf16(q, k, v, offsets, offsets_kv, (int)B, H, D, sc, out, lse, w.cus, s); }
+    else { ScopedTimer tm("fwd_bf16", s); e = jfa::launch_fwd_bf16(q, k, v, offsets, offsets_kv, causal, (int)B, H, D, sc, out, lse, w.cus, s); }
     if (e != hipSuccess) return hip_fail("forward kernel", e);
     return JFA_OK;
 }
 
-int backward_impl(const char *who, bool f32, const void *q, const void *k, const void *v, const void *out,
+int backward_impl(const char *who, bool f32, bool causal, const void *q, const void *k, const void *v, const void *out,
                   const void *dout, const float *lse, const int64_t *offsets, const int64_t *offsets_kv, int64_t B,
                   int64_t max_len, int64_t max_len_kv, int H, int D, void *dq, void *dk, void *dv, float *delta,
                   hipStream_t s) {
@@ -265,7 +266,7 @@ int backward_impl(const char *who, bool f32, const void *q, const void *k, const
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
-    const bool dma = !f32 && D == 128 && forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H) != kNarrow;
+    const bool dma = !f32 && !causal && D == 128 && forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H) != kNarrow;
     const int block_rows = f32 ? jfa::kF32BlockRows : (dma ? jfa::kDmaBlockRows : jfa::kBwdBlockRows);
     // Schedule 0: blocks of queries.  Schedule 1: blocks of keys, only different from schedule 0 for cross attention.
     // Both launches clear all work counters, and both run before the first kernel that uses one.
@@ -280,7 +281,7 @@ int backward_impl(const char *who, bool f32, const void *q, const void *k, const
         jfa::Schedule s_dkv{w.order[kv], w.tile_start[kv], w.counters + jfa::kXcds};
         ScopedTimer tm_bwd("bwd_f32", s);
         e = jfa::launch_bwd_f32((const float *)q, (const float *)k, (const float *)v, (const float *)out, (const float *)dout, lse,
-                                offsets, offsets_kv, (int)B, H, D, s_dq, s_dkv, (float *)dq, (float *)dk, (float *)dv, delta, w.cus, s);
+                                offsets, offsets_kv, causal, (int)B, H, D, s_dq, s_dkv, (float *)dq, (float *)dk, (float *)dv, delta, w.cus, s);
         if (e != hipSuccess) return hip_fail("fp32 backward kernels", e);
         return JFA_OK;
     }
@@ -299,9 +300,9 @@ int backward_impl(const char *who, bool f32, const void *q, const void *k, const
     }
     jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
     jfa::Schedule s_dkv{w.order[kv], w.tile_start[kv], w.counters + jfa::kXcds};
-    { ScopedTimer tm("dkv_bf16", s); e = jfa::launch_dkv_bf16(q, k, v, dout, lse, delta, offsets_k, offsets_q_other, (int)B, H, D, s_dkv, dk, dv, w.cus, s); }
+    { ScopedTimer tm("dkv_bf16", s); e = jfa::launch_dkv_bf16(q, k, v, dout, lse, delta, offsets_k, offsets_q_other, causal, (int)B, H, D, s_dkv, dk, dv, w.cus, s); }
     if (e != hipSuccess) return hip_fail("bf16 dK/dV kernel", e);
-    { ScopedTimer tm("dq_bf16", s); e = jfa::launch_dq_bf16(q, k, v, dout, lse, delta, offsets, offsets_kv, (int)B, H, D, s_dq, dq, w.cus, s); }
+    { ScopedTimer tm("dq_bf16", s); e = jfa::launch_dq_bf16(q, k, v, dout, lse, delta, offsets, offsets_kv, causal, (int)B, H, D, s_dq, dq, w.cus, s); }
     if (e != hipSuccess) return hip_fail("bf16 dQ kernel", e);
     return JFA_OK;
 }
@@ -317,24 +318,24 @@ extern "C" {
 
 int jfa_forward_f32(const float *q, const float *k, const float *v, const int64_t *offsets, int64_t B,
                     int64_t max_len, int H, int D, float *out, float *lse, void *stream) {
-    return forward_impl("jfa_forward_f32", true, q, k, v, offsets, nullptr, B, max_len, max_len, H, D, out, lse, (hipStream_t)stream);
+    return forward_impl("jfa_forward_f32", true, false, q, k, v, offsets, nullptr, B, max_len, max_len, H, D, out, lse, (hipStream_t)stream);
 }
 
 int jfa_backward_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
                      const float *lse, const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, float *dq,
                      float *dk, float *dv, float *delta, void *stream) {
-    return backward_impl("jfa_backward_f32", true, q, k, v, out, dout, lse, offsets, nullptr, B, max_len, max_len, H, D, dq, dk, dv, delta, (hipStream_t)stream);
+    return backward_impl("jfa_backward_f32", true, false, q, k, v, out, dout, lse, offsets, nullptr, B, max_len, max_len, H, D, dq, dk, dv, delta, (hipStream_t)stream);
 }
 
 int jfa_forward(const void *q, const void *k, const void *v, const int64_t *offsets, int64_t B, int64_t max_len,
                 int H, int D, void *out, float *lse, void *stream) {
-    return forward_impl("jfa_forward", false, q, k, v, offsets, nullptr, B, max_len, max_len, H, D, out, lse, (hipStream_t)stream);
+    return forward_impl("jfa_forward", false, false, q, k, v, offsets, nullptr, B, max_len, max_len, H, D, out, lse, (hipStream_t)stream);
 }
 
 int jfa_backward(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
                  const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, void *dq, void *dk, void *dv,
                  float *delta, void *stream) {
-    return backward_impl("jfa_backward", false, q, k, v, out, dout, lse, offsets, nullptr, B, max_len, max_len, H, D, dq, dk, dv, delta, (hipStream_t)stream);
+    return backward_impl("jfa_backward", false, false, q, k, v, out, dout, lse, offsets, nullptr, B, max_len, max_len, H, D, dq, dk, dv, delta, (hipStream_t)stream);
 }
 
 // ---- cross attention: queries and keys of a sample come from two offsets arrays ----
@@ -343,7 +344,7 @@ int jfa_forward_cross(const void *q, const void *k, const void *v, const int64_t
                       int64_t B, int64_t max_len_q, int64_t max_len_kv, int H, int D, void *out, float *lse, void *stream) {
     int st = need_kv("jfa_forward_cross", offsets_kv, B);
     if (st != JFA_OK) return st;
-    return forward_impl("jfa_forward_cross", false, q, k, v, offsets_q, offsets_kv, B, max_len_q, max_len_kv, H, D, out, lse, (hipStream_t)stream);
+    return forward_impl("jfa_forward_cross", false, false, q, k, v, offsets_q, offsets_kv, B, max_len_q, max_len_kv, H, D, out, lse, (hipStream_t)stream);
 }
 
 int jfa_forward_cross_f32(const float *q, const float *k, const float *v, const int64_t *offsets_q,
@@ -351,7 +352,7 @@ int jfa_forward_cross_f32(const float *q, const float *k, const float *v, const 
                           float *out, float *lse, void *stream) {
     int st = need_kv("jfa_forward_cross_f32", offsets_kv, B);
     if (st != JFA_OK) return st;
-    return forward_impl("jfa_forward_cross_f32", true, q, k, v, offsets_q, offsets_kv, B, max_len_q, max_len_kv, H, D, out, lse, (hipStream_t)stream);
+    return forward_impl("jfa_forward_cross_f32", true, false, q, k, v, offsets_q, offsets_kv, B, max_len_q, max_len_kv, H, D, out, lse, (hipStream_t)stream);
 }
 
 int jfa_backward_cross(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
@@ -359,7 +360,7 @@ int jfa_backward_cross(const void *q, const void *k, const void *v, const void *
                        int64_t max_len_kv, int H, int D, void *dq, void *dk, void *dv, float *delta, void *stream) {
     int st = need_kv("jfa_backward_cross", offsets_kv, B);
     if (st != JFA_OK) return st;
-    return backward_impl("jfa_backward_cross", false, q, k, v, out, dout, lse, offsets_q, offsets_kv, B, max_len_q, max_len_kv, H, D, dq, dk, dv, delta, (hipStream_t)stream);
+    return backward_impl("jfa_backward_cross", false, false, q, k, v, out, dout, lse, offsets_q, offsets_kv, B, max_len_q, max_len_kv, H, D, dq, dk, dv, delta, (hipStream_t)stream);
 }
 
 int jfa_backward_cross_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
@@ -368,7 +369,31 @@ int jfa_backward_cross_f32(const float *q, const float *k, const float *v, const
                            float *delta, void *stream) {
     int st = need_kv("jfa_backward_cross_f32", offsets_kv, B);
     if (st != JFA_OK) return st;
-    return backward_impl("jfa_backward_cross_f32", true, q, k, v, out, dout, lse, offsets_q, offsets_kv, B, max_len_q, max_len_kv, H, D, dq, dk, dv, delta, (hipStream_t)stream);
+    return backward_impl("jfa_backward_cross_f32", true, false, q, k, v, out, dout, lse, offsets_q, offsets_kv, B, max_len_q, max_len_kv, H, D, dq, dk, dv, delta, (hipStream_t)stream);
+}
+
+// ---- causal self attention: row i attends to rows 0 .. i of its sample ----
+
+int jfa_forward_causal(const void *q, const void *k, const void *v, const int64_t *offsets, int64_t B, int64_t max_len,
+                       int H, int D, void *out, float *lse, void *stream) {
+    return forward_impl("jfa_forward_causal", false, true, q, k, v, offsets, nullptr, B, max_len, max_len, H, D, out, lse, (hipStream_t)stream);
+}
+
+int jfa_forward_causal_f32(const float *q, const float *k, const float *v, const int64_t *offsets, int64_t B,
+                           int64_t max_len, int H, int D, float *out, float *lse, void *stream) {
+    return forward_impl("jfa_forward_causal_f32", true, true, q, k, v, offsets, nullptr, B, max_len, max_len, H, D, out, lse, (hipStream_t)stream);
+}
+
+int jfa_backward_causal(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
+                        const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, void *dq, void *dk, void *dv,
+                        float *delta, void *stream) {
+    return backward_impl("jfa_backward_causal", false, true, q, k, v, out, dout, lse, offsets, nullptr, B, max_len, max_len, H, D, dq, dk, dv, delta, (hipStream_t)stream);
+}
+
+int jfa_backward_causal_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
+                            const float *lse, const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, float *dq,
+                            float *dk, float *dv, float *delta, void *stream) {
+    return backward_impl("jfa_backward_causal_f32", true, true, q, k, v, out, dout, lse, offsets, nullptr, B, max_len, max_len, H, D, dq, dk, dv, delta, (hipStream_t)stream);
 }
 
 // ---- unfused jagged attention (paper Table 1): the baseline of Section 3 ----

@@ -74,8 +74,9 @@ __device__ inline void store_rows(__bf16 *dst_row, const f32x16 (&acc)[D / 32], 
         }
 }
 
-// CROSS: keys and values are the rows of a second offsets array (offsets_kv); see the forward kernel.
-template <int D, bool CROSS>
+// CROSS: keys and values are the rows of a second offsets array (offsets_kv); CAUSAL: query i sees keys 0 .. i.
+// See the forward kernel.
+template <int D, bool CROSS, bool CAUSAL>
 __global__ __launch_bounds__(kBwdThreads, 2) void dq_bf16_kernel(const __bf16 *__restrict__ q,
                                                                  const __bf16 *__restrict__ k,
                                                                  const __bf16 *__restrict__ v,
@@ -107,6 +108,7 @@ __global__ __launch_bounds__(kBwdThreads, 2) void dq_bf16_kernel(const __bf16 *_
         const int Lq = t.len;                      // queries of the sample
         const int L = CROSS ? t.olen : t.len;      // keys of the sample
         const int64_t krow0 = CROSS ? t.orow0 : t.row0;
+        const int Lc = CAUSAL && (t.block + 1) * kBwdBlockRows < L ? (t.block + 1) * kBwdBlockRows : L;   // keys this tile needs
         const __bf16 *kbase = k + krow0 * row_stride + (int64_t)t.head * D;
         const __bf16 *vbase = v + krow0 * row_stride + (int64_t)t.head * D;
 
@@ -136,19 +138,19 @@ __global__ __launch_bounds__(kBwdThreads, 2) void dq_bf16_kernel(const __bf16 *_
             sk.prefetch(kbase, row_stride, 0, L);
             sv.prefetch(vbase, row_stride, 0, L);
         }
-        for (int j0 = 0; j0 < L; j0 += kBwdStage) {
+        for (int j0 = 0; j0 < Lc; j0 += kBwdStage) {
             __syncthreads();
             sk.commit(sm.a, Smem::kStride);
             sv.commit(sm.b, Smem::kStride);
             __syncthreads();
-            if (j0 + kBwdStage < L) {
+            if (j0 + kBwdStage < Lc) {
                 sk.prefetch(kbase, row_stride, j0 + kBwdStage, L);
                 sv.prefetch(vbase, row_stride, j0 + kBwdStage, L);
             }
             if (!wave_active) continue;
 #pragma unroll
             for (int mb = 0; mb < 2; ++mb) {
-                if (j0 + mb * 32 >= L) break;
+                if (j0 + mb * 32 >= Lc) break;
                 f32x16 st, dpt;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) { st[e] = 0.0f; dpt[e] = 0.0f; }
@@ -158,12 +160,14 @@ __global__ __launch_bounds__(kBwdThreads, 2) void dq_bf16_kernel(const __bf16 *_
                 for (int ks = 0; ks < kKSteps; ++ks) st = mfma_32x32x16(lds_read_b128(krow + ks * 32), qreg[ks], st);
 #pragma unroll
                 for (int ks = 0; ks < kKSteps; ++ks) dpt = mfma_32x32x16(lds_read_b128(vrow + ks * 32), doreg[ks], dpt);
-                // dS^T = P^T o (dP^T - delta); keys past the end of the sample get P = 0
-                const bool tail = j0 + mb * 32 + 32 > L;
+                // dS^T = P^T o (dP^T - delta); keys past the end of the sample (and, if causal, above the diagonal) get P = 0
+                const int first_q = t.block * kBwdBlockRows + wave * 32;   // no lane of this wave masks a key below first_q + 1
+                const bool tail = j0 + mb * 32 + 32 > (CAUSAL && first_q + 1 < L ? first_q + 1 : L);
+                const int lim = CAUSAL && iq + 1 < L ? iq + 1 : L;         // this lane's query sees keys 0 .. lim - 1
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     float p = fast_exp2(fmaf(st[e], c, -lse2));
-                    if (tail && j0 + mb * 32 + acc_row(e, half) >= L) p = 0.0f;
+                    if (tail && j0 + mb * 32 + acc_row(e, half) >= lim) p = 0.0f;
                     st[e] = p * (dpt[e] - delta_i);
                 }
                 // dQ^T += K^T dS^T
@@ -186,8 +190,9 @@ __global__ __launch_bounds__(kBwdThreads, 2) void dq_bf16_kernel(const __bf16 *_
 }
 
 // CROSS: `offsets` are the keys' offsets (the work items are blocks of keys) and the queries, with dout, lse and
-// delta, are the rows of offsets_q.
-template <int D, bool CROSS>
+// delta, are the rows of offsets_q.  CAUSAL: key j is seen by queries j .. L - 1: the stream starts at the stage that
+// holds the tile's first key, and streamed rows below the lane's key get P = 0.
+template <int D, bool CROSS, bool CAUSAL>
 __global__ __launch_bounds__(kBwdThreads, 1) void dkv_bf16_kernel(const __bf16 *__restrict__ q,
                                                                   const __bf16 *__restrict__ k,
                                                                   const __bf16 *__restrict__ v,
@@ -254,8 +259,9 @@ __global__ __launch_bounds__(kBwdThreads, 1) void dkv_bf16_kernel(const __bf16 *
                 delta_pre = ok ? delta_base[i0 + tid] : 0.0f;
             }
         };
-        if (!CROSS || L > 0) prefetch_rows(0);   // a sample without queries: nothing streams, dk = dv = 0
-        for (int i0 = 0; i0 < L; i0 += kBwdStage) {
+        const int istart = CAUSAL ? (t.block * kBwdBlockRows / kBwdStage) * kBwdStage : 0;
+        if (!CROSS || L > 0) prefetch_rows(istart);   // a sample without queries: nothing streams, dk = dv = 0
+        for (int i0 = istart; i0 < L; i0 += kBwdStage) {
             __syncthreads();
             sq.commit(sm.a, Smem::kStride);
             sdo.commit(sm.b, Smem::kStride);
@@ -283,7 +289,8 @@ __global__ __launch_bounds__(kBwdThreads, 1) void dkv_bf16_kernel(const __bf16 *
                     const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, dl[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        const float p = fast_exp2(fmaf(sc[4 * g + e], c, -lv[e]));
+                        float p = fast_exp2(fmaf(sc[4 * g + e], c, -lv[e]));
+                        if (CAUSAL && i0 + mb * 32 + g * 8 + half * 4 + e < jk) p = 0.0f;   // queries before this lane's key
                         sc[4 * g + e] = p;
                         dp[4 * g + e] = p * (dp[4 * g + e] - dl[e]);
                     }
@@ -316,46 +323,48 @@ __global__ __launch_bounds__(kBwdThreads, 1) void dkv_bf16_kernel(const __bf16 *
 }
 
 hipError_t launch_dkv_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
-                           const float *delta, const int64_t *offsets, const int64_t *offsets_q, int B, int H, int D,
-                           Schedule s, void *dk, void *dv, int cus, hipStream_t stream) {
+                           const float *delta, const int64_t *offsets, const int64_t *offsets_q, bool causal, int B, int H,
+                           int D, Schedule s, void *dk, void *dv, int cus, hipStream_t stream) {
+    if (causal && offsets_q) return hipErrorInvalidValue;
+#define JFA_LAUNCH(DD, CROSS, CAUSAL)                                                                            \
+    hipLaunchKernelGGL((dkv_bf16_kernel<DD, CROSS, CAUSAL>), dim3(persistent_grid<dkv_bf16_kernel<DD, CROSS, CAUSAL>>(kBwdThreads, cus)), \
+                       dim3(kBwdThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, lse, \
+                       delta, offsets, offsets_q, B, H, s, (__bf16 *)dk, (__bf16 *)dv)
 #define JFA_CASE(DD)                                                                                             \
     case DD:                                                                                                     \
-        if (offsets_q)                                                                                           \
-            hipLaunchKernelGGL((dkv_bf16_kernel<DD, true>), dim3(persistent_grid<dkv_bf16_kernel<DD, true>>(kBwdThreads, cus)), dim3(kBwdThreads), 0, stream, \
-                               (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, lse, delta, offsets, offsets_q, B, H, \
-                               s, (__bf16 *)dk, (__bf16 *)dv);                                                   \
-        else                                                                                                     \
-            hipLaunchKernelGGL((dkv_bf16_kernel<DD, false>), dim3(persistent_grid<dkv_bf16_kernel<DD, false>>(kBwdThreads, cus)), dim3(kBwdThreads), 0, stream, \
-                               (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, lse, delta, offsets, offsets_q, B, H, \
-                               s, (__bf16 *)dk, (__bf16 *)dv);                                                   \
+        if (offsets_q) JFA_LAUNCH(DD, true, false);                                                              \
+        else if (causal) JFA_LAUNCH(DD, false, true);                                                            \
+        else JFA_LAUNCH(DD, false, false);                                                                       \
         break;
     switch (D) {
         JFA_CASE(32) JFA_CASE(64) JFA_CASE(128)
         default: return hipErrorInvalidValue;
     }
 #undef JFA_CASE
+#undef JFA_LAUNCH
     return hipGetLastError();
 }
 
 hipError_t launch_dq_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
-                          const float *delta, const int64_t *offsets, const int64_t *offsets_kv, int B, int H, int D,
-                          Schedule s, void *dq, int cus, hipStream_t stream) {
+                          const float *delta, const int64_t *offsets, const int64_t *offsets_kv, bool causal, int B, int H,
+                          int D, Schedule s, void *dq, int cus, hipStream_t stream) {
+    if (causal && offsets_kv) return hipErrorInvalidValue;
+#define JFA_LAUNCH(DD, CROSS, CAUSAL)                                                                            \
+    hipLaunchKernelGGL((dq_bf16_kernel<DD, CROSS, CAUSAL>), dim3(persistent_grid<dq_bf16_kernel<DD, CROSS, CAUSAL>>(kBwdThreads, cus)), \
+                       dim3(kBwdThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, lse, \
+                       delta, offsets, offsets_kv, B, H, s, (__bf16 *)dq)
 #define JFA_CASE(DD)                                                                                             \
     case DD:                                                                                                     \
-        if (offsets_kv)                                                                                          \
-            hipLaunchKernelGGL((dq_bf16_kernel<DD, true>), dim3(persistent_grid<dq_bf16_kernel<DD, true>>(kBwdThreads, cus)), dim3(kBwdThreads), 0, stream, \
-                               (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, lse, delta, offsets, offsets_kv, B, H, \
-                               s, (__bf16 *)dq);                                                                 \
-        else                                                                                                     \
-            hipLaunchKernelGGL((dq_bf16_kernel<DD, false>), dim3(persistent_grid<dq_bf16_kernel<DD, false>>(kBwdThreads, cus)), dim3(kBwdThreads), 0, stream, \
-                               (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, lse, delta, offsets, offsets_kv, B, H, \
-                               s, (__bf16 *)dq);                                                                 \
+        if (offsets_kv) JFA_LAUNCH(DD, true, false);                                                             \
+        else if (causal) JFA_LAUNCH(DD, false, true);                                                            \
+        else JFA_LAUNCH(DD, false, false);                                                                       \
         break;
     switch (D) {
         JFA_CASE(32) JFA_CASE(64) JFA_CASE(128)
         default: return hipErrorInvalidValue;
     }
 #undef JFA_CASE
+#undef JFA_LAUNCH
     return hipGetLastError();
 }
 

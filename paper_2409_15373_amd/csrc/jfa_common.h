@@ -257,12 +257,13 @@ hipError_t launch_check_offsets(const int64_t *offsets, int B, int64_t max_len, 
 constexpr int kF32BlockRows = 64;
 // Cross attention: offsets = the queries' offsets, offsets_kv = the keys' (nullptr: the same array); schedules are
 // built over the stationary side's offsets (s, s_dq: queries; s_dkv: keys).
+// causal (self attention only, offsets_kv == nullptr): row i attends to rows 0 .. i of its sample.
 hipError_t launch_fwd_f32(const float *q, const float *k, const float *v, const int64_t *offsets,
-                          const int64_t *offsets_kv, int B, int H, int D, Schedule s, float *out, float *lse, int cus,
-                          hipStream_t stream);
+                          const int64_t *offsets_kv, bool causal, int B, int H, int D, Schedule s, float *out, float *lse,
+                          int cus, hipStream_t stream);
 hipError_t launch_bwd_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
-                          const float *lse, const int64_t *offsets, const int64_t *offsets_kv, int B, int H, int D,
-                          Schedule s_dq, Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int cus,
+                          const float *lse, const int64_t *offsets, const int64_t *offsets_kv, bool causal, int B, int H,
+                          int D, Schedule s_dq, Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int cus,
                           hipStream_t stream);
 // delta[h, row] = sum_d dout * out, for T = float or bf16 (is_bf16)
 hipError_t launch_delta(const void *out, const void *dout, const float *lse, const int64_t *offsets, int B, int H,
@@ -273,15 +274,16 @@ constexpr int kFwdBlockRows = 128;
 constexpr int kBwdBlockRows = 128;
 // In all bf16 launchers `offsets` belongs to the rows the schedule `s` was built over (queries for the forward and
 // dQ, keys for dK / dV) and the second array to the rows that stream past them (cross attention; nullptr: the same).
+// causal: self attention in which row i attends to rows 0 .. i of its sample (not together with a second array).
 hipError_t launch_fwd_bf16(const void *q, const void *k, const void *v, const int64_t *offsets,
-                           const int64_t *offsets_kv, int B, int H, int D, Schedule s, void *out, float *lse, int cus,
-                           hipStream_t stream);
+                           const int64_t *offsets_kv, bool causal, int B, int H, int D, Schedule s, void *out, float *lse,
+                           int cus, hipStream_t stream);
 hipError_t launch_dkv_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
-                           const float *delta, const int64_t *offsets, const int64_t *offsets_q, int B, int H, int D,
-                           Schedule s, void *dk, void *dv, int cus, hipStream_t stream);
+                           const float *delta, const int64_t *offsets, const int64_t *offsets_q, bool causal, int B, int H,
+                           int D, Schedule s, void *dk, void *dv, int cus, hipStream_t stream);
 hipError_t launch_dq_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
-                          const float *delta, const int64_t *offsets, const int64_t *offsets_kv, int B, int H, int D,
-                          Schedule s, void *dq, int cus, hipStream_t stream);
+                          const float *delta, const int64_t *offsets, const int64_t *offsets_kv, bool causal, int B, int H,
+                          int D, Schedule s, void *dq, int cus, hipStream_t stream);
 
 // bf16 attention, direct-to-LDS kernels (D = 128, long samples; work items are blocks of kDmaBlockRows rows)
 constexpr int kDmaBlockRows = 256;

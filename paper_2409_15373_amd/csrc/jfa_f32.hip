@@ -40,8 +40,8 @@ template <int D>
 __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(const float *__restrict__ q, const float *__restrict__ k,
                                                            const float *__restrict__ v,
                                                            const int64_t *__restrict__ offsets,
-                                                           const int64_t *__restrict__ offsets_kv, int B, int H,
-                                                           Schedule s, float *__restrict__ out,
+                                                           const int64_t *__restrict__ offsets_kv, bool causal,
+                                                           int B, int H, Schedule s, float *__restrict__ out,
                                                            float *__restrict__ lse) {
     constexpr int kPer = D / 4;
     constexpr int kCols = cols_for<D>();
@@ -64,8 +64,10 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(const float *__restri
             acc[e] = 0.0f;
         }
         float m = -INFINITY, l = 0.0f;
-        for (int j0 = 0; j0 < t.olen; j0 += kCols) {
-            const int n = t.olen - j0 < kCols ? t.olen - j0 : kCols;
+        // causal (self attention only): query i sees keys 0 .. i, so the tile needs the keys up to its last query
+        const int kend = causal && (t.block + 1) * kRows < t.olen ? (t.block + 1) * kRows : t.olen;
+        for (int j0 = 0; j0 < kend; j0 += kCols) {
+            const int n = kend - j0 < kCols ? kend - j0 : kCols;
             __syncthreads();
             stage_rows<D>(Ks, k, t.orow0 + j0, n, t.head, H);
             stage_rows<D>(Vs, v, t.orow0 + j0, n, t.head, H);
@@ -73,7 +75,7 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(const float *__restri
             for (int j = 0; j < n; ++j) {
                 float part = 0.0f;
                 for (int e = 0; e < kPer; ++e) part = fmaf(qr[e], Ks[j * D + 4 * e + c], part);
-                const float sc = quad_sum(part) * scale;
+                const float sc = causal && j0 + j > iq ? -INFINITY : quad_sum(part) * scale;   // key 0 is never masked: m stays finite
                 const float m_new = fmaxf(m, sc);
                 const float a = expf(m - m_new);              // exp(-inf) = 0 on the first key
                 const float p = expf(sc - m_new);
@@ -98,8 +100,8 @@ __global__ __launch_bounds__(kThreads) void dq_f32_kernel(const float *__restric
                                                           const float *__restrict__ lse,
                                                           const float *__restrict__ delta,
                                                           const int64_t *__restrict__ offsets,
-                                                          const int64_t *__restrict__ offsets_kv, int B, int H,
-                                                          Schedule s, float *__restrict__ dq) {
+                                                          const int64_t *__restrict__ offsets_kv, bool causal,
+                                                          int B, int H, Schedule s, float *__restrict__ dq) {
     constexpr int kPer = D / 4;
     constexpr int kCols = cols_for<D>();
     __shared__ float Ks[kCols * D];
@@ -124,8 +126,10 @@ __global__ __launch_bounds__(kThreads) void dq_f32_kernel(const float *__restric
         }
         const float lse_i = lse[(int64_t)t.head * sum_B + t.row0 + iq];
         const float delta_i = delta[(int64_t)t.head * sum_B + t.row0 + iq];
-        for (int j0 = 0; j0 < t.olen; j0 += kCols) {
-            const int n = t.olen - j0 < kCols ? t.olen - j0 : kCols;
+        // causal (self attention only): query i sees keys 0 .. i, so the tile needs the keys up to its last query
+        const int kend = causal && (t.block + 1) * kRows < t.olen ? (t.block + 1) * kRows : t.olen;
+        for (int j0 = 0; j0 < kend; j0 += kCols) {
+            const int n = kend - j0 < kCols ? kend - j0 : kCols;
             __syncthreads();
             stage_rows<D>(Ks, k, t.orow0 + j0, n, t.head, H);
             stage_rows<D>(Vs, v, t.orow0 + j0, n, t.head, H);
@@ -136,7 +140,7 @@ __global__ __launch_bounds__(kThreads) void dq_f32_kernel(const float *__restric
                     ps = fmaf(qr[e], Ks[j * D + 4 * e + c], ps);
                     pd = fmaf(dor[e], Vs[j * D + 4 * e + c], pd);
                 }
-                const float p = expf(quad_sum(ps) * scale - lse_i);
+                const float p = causal && j0 + j > iq ? 0.0f : expf(quad_sum(ps) * scale - lse_i);
                 const float ds = p * (quad_sum(pd) - delta_i);
                 for (int e = 0; e < kPer; ++e) acc[e] = fmaf(ds, Ks[j * D + 4 * e + c], acc[e]);
             }
@@ -154,8 +158,8 @@ __global__ __launch_bounds__(kThreads) void dkv_f32_kernel(const float *__restri
                                                            const float *__restrict__ lse,
                                                            const float *__restrict__ delta,
                                                            const int64_t *__restrict__ offsets,   // of the keys
-                                                           const int64_t *__restrict__ offsets_q, int B, int H,
-                                                           Schedule s, float *__restrict__ dk,
+                                                           const int64_t *__restrict__ offsets_q, bool causal,
+                                                           int B, int H, Schedule s, float *__restrict__ dk,
                                                            float *__restrict__ dv) {
     constexpr int kPer = D / 4;
     constexpr int kCols = cols_for<D>();
@@ -182,7 +186,9 @@ __global__ __launch_bounds__(kThreads) void dkv_f32_kernel(const float *__restri
             acck[e] = 0.0f;
             accv[e] = 0.0f;
         }
-        for (int i0 = 0; i0 < t.olen; i0 += kCols) {
+        // causal: key j is seen by queries j .. L - 1, so the stream starts at the stage that holds the tile's first key
+        const int istart = causal ? (t.block * kRows / kCols) * kCols : 0;
+        for (int i0 = istart; i0 < t.olen; i0 += kCols) {
             const int n = t.olen - i0 < kCols ? t.olen - i0 : kCols;
             __syncthreads();
             stage_rows<D>(Qs, q, t.orow0 + i0, n, t.head, H);
@@ -198,7 +204,7 @@ __global__ __launch_bounds__(kThreads) void dkv_f32_kernel(const float *__restri
                     ps = fmaf(Qs[i * D + 4 * e + c], kr[e], ps);
                     pd = fmaf(Os[i * D + 4 * e + c], vr[e], pd);
                 }
-                const float p = expf(quad_sum(ps) * scale - lse_s[i]);
+                const float p = causal && i0 + i < jk ? 0.0f : expf(quad_sum(ps) * scale - lse_s[i]);
                 const float ds = p * (quad_sum(pd) - delta_s[i]);
                 for (int e = 0; e < kPer; ++e) {
                     accv[e] = fmaf(p, Os[i * D + 4 * e + c], accv[e]);
@@ -267,11 +273,11 @@ hipError_t launch_delta(const void *out, const void *dout, const float *lse, con
 }
 
 hipError_t launch_fwd_f32(const float *q, const float *k, const float *v, const int64_t *offsets,
-                          const int64_t *offsets_kv, int B, int H, int D, Schedule s, float *out, float *lse, int cus,
-                          hipStream_t stream) {
+                          const int64_t *offsets_kv, bool causal, int B, int H, int D, Schedule s, float *out, float *lse,
+                          int cus, hipStream_t stream) {
 #define JFA_CASE(DD)                                                                                              \
     case DD:                                                                                                      \
-        hipLaunchKernelGGL(fwd_f32_kernel<DD>, dim3(persistent_grid<fwd_f32_kernel<DD>>(kThreads, cus)), dim3(kThreads), 0, stream, q, k, v, offsets, offsets_kv, B, H, s, \
+        hipLaunchKernelGGL(fwd_f32_kernel<DD>, dim3(persistent_grid<fwd_f32_kernel<DD>>(kThreads, cus)), dim3(kThreads), 0, stream, q, k, v, offsets, offsets_kv, causal, B, H, s, \
                            out, lse);                                                                             \
         break;
     switch (D) {
@@ -283,17 +289,17 @@ hipError_t launch_fwd_f32(const float *q, const float *k, const float *v, const 
 }
 
 hipError_t launch_bwd_f32(const float *q, const float *k, const float *v, const float *out, const float *dout,
-                          const float *lse, const int64_t *offsets, const int64_t *offsets_kv, int B, int H, int D,
-                          Schedule s_dq, Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int cus,
+                          const float *lse, const int64_t *offsets, const int64_t *offsets_kv, bool causal, int B, int H,
+                          int D, Schedule s_dq, Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int cus,
                           hipStream_t stream) {
     hipError_t e = launch_delta(out, dout, nullptr, offsets, B, H, D, false, delta, cus, stream);
     if (e != hipSuccess) return e;
 #define JFA_CASE(DD)                                                                                               \
     case DD:                                                                                                       \
         hipLaunchKernelGGL(dq_f32_kernel<DD>, dim3(persistent_grid<dq_f32_kernel<DD>>(kThreads, cus)), dim3(kThreads), 0, stream, q, k, v, dout, lse, delta,   \
-                           offsets, offsets_kv, B, H, s_dq, dq);                                                   \
+                           offsets, offsets_kv, causal, B, H, s_dq, dq);                                           \
         hipLaunchKernelGGL(dkv_f32_kernel<DD>, dim3(persistent_grid<dkv_f32_kernel<DD>>(kThreads, cus)), dim3(kThreads), 0, stream, q, k, v, dout, lse, delta,  \
-                           offsets_kv ? offsets_kv : offsets, offsets_kv ? offsets : nullptr, B, H, s_dkv, dk, dv);  \
+                           offsets_kv ? offsets_kv : offsets, offsets_kv ? offsets : nullptr, causal, B, H, s_dkv, dk, dv);  \
         break;
     switch (D) {
         JFA_CASE(32) JFA_CASE(64) JFA_CASE(128)

@@ -34,8 +34,9 @@ struct alignas(16) FwdSmem {
 };
 
 // CROSS: the keys and values of a sample are the rows of a second offsets array (cross attention); otherwise
-// offsets_kv is not looked at and the code is that of self attention.
-template <int D, bool CROSS>
+// offsets_kv is not looked at and the code is that of self attention.  CAUSAL (self attention only): query i
+// attends to keys 0 .. i of its sample; a tile streams the keys up to its last query and masks above the diagonal.
+template <int D, bool CROSS, bool CAUSAL>
 __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *__restrict__ q,
                                                                   const __bf16 *__restrict__ k,
                                                                   const __bf16 *__restrict__ v,
@@ -78,6 +79,7 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
         const int Lq = t.len;                      // queries of the sample
         const int L = CROSS ? t.olen : t.len;      // keys of the sample
         const int64_t krow0 = CROSS ? t.orow0 : t.row0;
+        const int Lc = CAUSAL && (t.block + 1) * kFwdBlockRows < L ? (t.block + 1) * kFwdBlockRows : L;   // keys this tile needs
         const __bf16 *kbase = k + krow0 * row_stride + (int64_t)t.head * D;
         const __bf16 *vbase = v + krow0 * row_stride + (int64_t)t.head * D;
 
@@ -156,8 +158,8 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
         for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qreg[ks]));
         __syncthreads();
         int buf = 0;
-        for (int j0 = 0; j0 < L; j0 += kFwdBN, buf ^= 1) {
-            const bool more = j0 + kFwdBN < L;
+        for (int j0 = 0; j0 < Lc; j0 += kFwdBN, buf ^= 1) {
+            const bool more = j0 + kFwdBN < Lc;
             if (more) prefetch(j0 + kFwdBN);
             if (wave_active) {
                 const char *kt = sm.k[buf] + koff;
@@ -186,13 +188,15 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
                 }
                 __builtin_amdgcn_sched_group_barrier(0x008, kKSteps, 0);
 
-                // ---- mask keys past the end of the sample (last block only) ----
-                if (j0 + kFwdBN > L) {
+                // ---- mask keys past the end of the sample (last block only) and, if causal, above the diagonal ----
+                const int first_q = t.block * kFwdBlockRows + wave * 32;   // no lane of this wave masks a key below first_q + 1
+                if (j0 + kFwdBN > (CAUSAL && first_q + 1 < L ? first_q + 1 : L)) {
+                    const int lim = CAUSAL && iq + 1 < L ? iq + 1 : L;     // this lane's query sees keys 0 .. lim - 1
 #pragma unroll
                     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
                         for (int e = 0; e < 16; ++e)
-                            if (j0 + mb * 32 + acc_row(e, half) >= L) st[mb][e] = -INFINITY;
+                            if (j0 + mb * 32 + acc_row(e, half) >= lim) st[mb][e] = -INFINITY;
                 }
 
                 // ---- online softmax for this lane's query ----
@@ -268,22 +272,25 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
 }
 
 hipError_t launch_fwd_bf16(const void *q, const void *k, const void *v, const int64_t *offsets,
-                           const int64_t *offsets_kv, int B, int H, int D, Schedule s, void *out, float *lse, int cus,
-                           hipStream_t stream) {
+                           const int64_t *offsets_kv, bool causal, int B, int H, int D, Schedule s, void *out, float *lse,
+                           int cus, hipStream_t stream) {
+    if (causal && offsets_kv) return hipErrorInvalidValue;
+#define JFA_LAUNCH(DD, CROSS, CAUSAL)                                                                        \
+    hipLaunchKernelGGL((fwd_bf16_kernel<DD, CROSS, CAUSAL>), dim3(persistent_grid<fwd_bf16_kernel<DD, CROSS, CAUSAL>>(kFwdThreads, cus)), \
+                       dim3(kFwdThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, offsets, offsets_kv, B, H, s, \
+                       (__bf16 *)out, lse)
 #define JFA_CASE(DD)                                                                                         \
     case DD:                                                                                                 \
-        if (offsets_kv)                                                                                      \
-            hipLaunchKernelGGL((fwd_bf16_kernel<DD, true>), dim3(persistent_grid<fwd_bf16_kernel<DD, true>>(kFwdThreads, cus)), dim3(kFwdThreads), 0, stream, \
-                               (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, offsets, offsets_kv, B, H, s, (__bf16 *)out, lse); \
-        else                                                                                                 \
-            hipLaunchKernelGGL((fwd_bf16_kernel<DD, false>), dim3(persistent_grid<fwd_bf16_kernel<DD, false>>(kFwdThreads, cus)), dim3(kFwdThreads), 0, stream, \
-                               (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, offsets, offsets_kv, B, H, s, (__bf16 *)out, lse); \
+        if (offsets_kv) JFA_LAUNCH(DD, true, false);                                                         \
+        else if (causal) JFA_LAUNCH(DD, false, true);                                                        \
+        else JFA_LAUNCH(DD, false, false);                                                                   \
         break;
     switch (D) {
         JFA_CASE(32) JFA_CASE(64) JFA_CASE(128)
         default: return hipErrorInvalidValue;
     }
 #undef JFA_CASE
+#undef JFA_LAUNCH
     return hipGetLastError();
 }
 

@@ -1,13 +1,15 @@
 #!/usr/bin/env python3
-"""Timing of jagged cross attention (jfa_forward_cross / jfa_backward_cross) against the bf16 MFMA roofline.
+"""Timing of the cross and causal variants of jagged attention against the bf16 MFMA roofline.
 
-    python -m paper_2409_15373_amd.cross_bench [--reps N]
+    python -m paper_2409_15373_amd.variants_bench [--reps N]
 
 The paper's feature interaction attends from a sample's target items to its feature values: few queries, many
 keys.  Two synthetic workloads with B = 512, H = 8, D = 128 and the keys' lengths of the benchmarked self-attention
 configuration (bimodal, up to 4096): queries uniform on [1, 256] ("targets"), and queries with the keys' lengths
 shuffled across samples ("shuffled": as much work as self attention, but L_q != L_kv in every sample).
-Useful flops: 4 H D sum(L_q L_kv) forward, 10 H D sum(L_q L_kv) backward.  Prints one JSON line.
+Useful flops: 4 H D sum(L_q L_kv) forward, 10 H D sum(L_q L_kv) backward.  A third workload runs causal self
+attention (jfa_forward_causal / jfa_backward_causal) on that configuration itself: sum L (L + 1) / 2 query-key
+pairs per head.  Prints one JSON line.
 """
 import argparse
 import json
@@ -63,6 +65,23 @@ def main():
             "fwd_us": round(t_f, 1), "fwd_TFLOP_per_s": round(f_f / t_f / 1e6, 1), "fwd_frac_of_peak": round(f_f / t_f / 1e6 / PEAK_TFLOPS, 3),
             "bwd_us": round(t_b, 1), "bwd_useful_TFLOP_per_s": round(f_b / t_b / 1e6, 1), "bwd_frac_of_peak": round(f_b / t_b / 1e6 / PEAK_TFLOPS, 3),
         }
+    # causal self attention on the benchmarked configuration
+    n = int(Lk.sum())
+    pairs = float((Lk.astype(np.float64) * (Lk + 1) / 2).sum())
+    off = torch.from_numpy(offsets_from_lengths(Lk)).cuda()
+    mk = lambda s: (torch.randn(n, H, D, device="cuda", generator=gen) * s).bfloat16()
+    q, k, v, dout = mk(c["sigma"]), mk(c["sigma"]), mk(1.0), mk(1.0)
+    out, lse = torch.empty_like(q), torch.empty(H, n, device="cuda")
+    dq, dk, dv, stats = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q), torch.empty(2, H, n, device="cuda")
+    fwd = lambda: binding.jfa_forward(q, k, v, off, c["max_len"], out=out, lse=lse, causal=True)
+    bwd = lambda: binding.jfa_backward(q, k, v, out, dout, lse, off, c["max_len"], dq=dq, dk=dk, dv=dv, delta=stats, causal=True)
+    t_f, t_b = _time(fwd, args.reps), _time(bwd, args.reps)
+    f_f, f_b = 4.0 * H * D * pairs, 10.0 * H * D * pairs
+    result["workloads"]["causal"] = {
+        "sum_B": n, "query_key_pairs_per_head": pairs,
+        "fwd_us": round(t_f, 1), "fwd_TFLOP_per_s": round(f_f / t_f / 1e6, 1), "fwd_frac_of_peak": round(f_f / t_f / 1e6 / PEAK_TFLOPS, 3),
+        "bwd_us": round(t_b, 1), "bwd_useful_TFLOP_per_s": round(f_b / t_b / 1e6, 1), "bwd_frac_of_peak": round(f_b / t_b / 1e6 / PEAK_TFLOPS, 3),
+    }
     print(json.dumps(result))
 
 

@@ -1,0 +1,78 @@
+"""Causal jagged self attention on the GPU vs oracle/causal.py, forward and backward, fp32 and bf16.
+
+Gates as for the non-causal path (fp32 2e-5 relative to max(1, |ref|); bf16 2e-2 absolute and 1e-2 of the tensor's
+maximum).  Lengths cover several 128-row tiles and 64-key stages, tiles whose diagonal crosses stage boundaries,
+ragged tails, and samples of length 0 and 1.  Causal attention runs on the register-staged kernels at every length,
+so one case is long (max_len > 256 at D = 128, where the non-causal path would pick the direct-to-LDS kernels).
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import causal
+from paper_2409_15373_amd.synthetic import make_custom
+from helpers import f64, gate_bf16, gate_f32, to_device
+
+pytestmark = pytest.mark.gpu
+GUARD = 2
+
+
+def run(w, max_len):
+    from paper_2409_15373_amd import binding
+    d = to_device(w, names=("q", "k", "v", "dout"), pad_rows=GUARD)
+    n, H = w.sum_B, w.H
+    out = torch.full_like(d["q"], 777.0)
+    lse = torch.full((H, n), 777.0, dtype=torch.float32, device="cuda")
+    binding.jfa_forward(d["q"], d["k"], d["v"], d["offsets"], max_len, out=out, lse=lse, causal=True)
+    torch.cuda.synchronize()
+    assert (out[n:] == 777.0).all()
+    grads = [torch.full_like(d["q"], 555.0) for _ in range(3)]
+    stats = torch.empty((2 if w.dtype == "bf16" else 1, H, n), dtype=torch.float32, device="cuda")
+    out_in = out.clone(); out_in[n:] = float("nan")
+    binding.jfa_backward(d["q"], d["k"], d["v"], out_in, d["dout"], lse, d["offsets"], max_len, dq=grads[0], dk=grads[1],
+                         dv=grads[2], delta=stats, causal=True)
+    torch.cuda.synchronize()
+    for g in grads:
+        assert (g[n:] == 555.0).all(), "guard rows of a gradient were written"
+    got = dict(out=f64(out[:n]), lse=f64(lse), dq=f64(grads[0][:n]), dk=f64(grads[1][:n]), dv=f64(grads[2][:n]), delta=f64(stats[0]))
+    r_out, r_lse = causal.forward(w.q, w.k, w.v, w.offsets)
+    r_dq, r_dk, r_dv, r_delta = causal.backward(w.q, w.k, w.v, w.dout, w.offsets)
+    ref = dict(out=r_out, lse=r_lse, dq=r_dq, dk=r_dk, dv=r_dv, delta=r_delta)
+    for name in got:
+        if w.dtype == "f32":
+            gate_f32(name, got[name], ref[name], tol=2e-5, relative_to_one=True)
+        else:
+            gate_bf16(name, got[name], ref[name], abs_tol=2e-2 * max(1.0, float(np.abs(ref[name]).max()) / 4))
+
+
+LENGTHS = [300, 1, 0, 129, 128, 127, 64, 33, 257, 2, 65, 0, 200]
+
+
+@pytest.mark.parametrize("D", [32, 128])
+def test_causal_fp32(D):
+    run(make_custom("causal", [70, 1, 0, 64, 65, 130], 2, D, dtype="f32", seed=21 + D), 130)
+
+
+@pytest.mark.parametrize("D,H", [(32, 1), (64, 3), (128, 2)])
+def test_causal_bf16(D, H):
+    run(make_custom("causal", LENGTHS, H, D, dtype="bf16", seed=22 + D), 512 if D != 128 else 256)
+
+
+def test_causal_bf16_long_samples():
+    run(make_custom("causal", [1000, 513, 64, 700, 1], 2, 128, dtype="bf16", seed=23), 1024)
+
+
+def test_causal_first_row_returns_v_and_later_rows_ignore_the_future():
+    """Exact properties: row 0 of every sample returns its value row (p = 1); changing rows after i leaves row i as it was."""
+    from paper_2409_15373_amd import binding
+    w = make_custom("causal", [150, 40], 2, 64, dtype="bf16", seed=24, dout=False)
+    d = to_device(w, names=("q", "k", "v"))
+    out, lse = binding.jfa_forward(d["q"], d["k"], d["v"], d["offsets"], 256, causal=True)
+    k2, v2 = d["k"].clone(), d["v"].clone()
+    k2[100:150] = 3.0; v2[100:150] = -7.0                      # the future of rows 0 .. 99 of sample 0
+    out2, lse2 = binding.jfa_forward(d["q"], k2, v2, d["offsets"], 256, causal=True)
+    torch.cuda.synchronize()
+    for s in (0, 150):
+        assert torch.equal(out[s].view(torch.int16), d["v"][s].view(torch.int16))
+    assert torch.equal(out[:100].view(torch.int16), out2[:100].view(torch.int16)) and torch.equal(lse[:, :100], lse2[:, :100])
+    assert not torch.equal(out[100:150].view(torch.int16), out2[100:150].view(torch.int16))

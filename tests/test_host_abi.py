@@ -41,7 +41,7 @@ def test_version_and_workspace_depend_on_B_only(lib):
     assert binding.jfa_workspace_bytes(0, 10, 1, 32) == 0
 
 
-@pytest.mark.parametrize("fn", ["jfa_forward", "jfa_forward_f32"])
+@pytest.mark.parametrize("fn", ["jfa_forward", "jfa_forward_f32", "jfa_forward_causal", "jfa_forward_causal_f32"])
 def test_forward_argument_errors(lib, fn):
     from paper_2409_15373_amd import binding
     f = getattr(lib, fn)
@@ -58,7 +58,7 @@ def test_forward_argument_errors(lib, fn):
     assert f(None, None, None, None, 0, 8, 1, 64, None, None, None) == binding.JFA_OK        # B == 0: nothing to do
 
 
-@pytest.mark.parametrize("fn", ["jfa_backward", "jfa_backward_f32"])
+@pytest.mark.parametrize("fn", ["jfa_backward", "jfa_backward_f32", "jfa_backward_causal", "jfa_backward_causal_f32"])
 def test_backward_argument_errors(lib, fn):
     from paper_2409_15373_amd import binding
     f = getattr(lib, fn)
