@@ -197,7 +197,7 @@ int jfa_build_schedule(const int64_t *offsets, int64_t B, int block_rows, int32_
     Views v;
     int st = get_table(B, (hipStream_t)stream, &v);
     if (st != JFA_OK) return st;
-    hipError_t e = jfa::launch_schedule(offsets, (int)B, block_rows, order, tile_start, v.counters, jfa::kNumCounters, (hipStream_t)stream);
+    hipError_t e = jfa::launch_schedule(offsets, nullptr, (int)B, block_rows, order, tile_start, v.counters, jfa::kNumCounters, (hipStream_t)stream);
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     return JFA_OK;
 }
@@ -228,9 +228,10 @@ namespace {
 // Forward and backward behind the self- and cross-attention entry points.  offsets_kv == nullptr: self attention
 // (keys and values share the queries' offsets).  Work schedules are built over the offsets of the rows a kernel's
 // work items are blocks of: the queries' for the forward and dQ, the keys' for dK and dV.
-hipError_t schedule(const int64_t *offsets, int64_t B, int block_rows, const Views &w, int which, hipStream_t s) {
+hipError_t schedule(const int64_t *offsets, const int64_t *offsets_other, int64_t B, int block_rows, const Views &w, int which,
+                    hipStream_t s) {
     ScopedTimer tm("schedule", s);
-    return jfa::launch_schedule(offsets, (int)B, block_rows, w.order[which], w.tile_start[which], w.counters, jfa::kNumCounters, s);
+    return jfa::launch_schedule(offsets, offsets_other, (int)B, block_rows, w.order[which], w.tile_start[which], w.counters, jfa::kNumCounters, s);
 }
 
 int forward_impl(const char *who, bool f32, bool causal, const void *q, const void *k, const void *v, const int64_t *offsets,
@@ -245,7 +246,7 @@ int forward_impl(const char *who, bool f32, bool causal, const void *q, const vo
     hipError_t e;
     // causal attention runs on the register-staged kernels at every length (the direct-to-LDS kernels have no causal form)
     const FwdVariant variant = (f32 || causal) ? kNarrow : forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H);
-    e = schedule(offsets, B, f32 ? jfa::kF32BlockRows : (variant == kNarrow ? jfa::kFwdBlockRows : jfa::kDmaBlockRows), w, 0, s);
+    e = schedule(offsets, offsets_kv, B, f32 ? jfa::kF32BlockRows : (variant == kNarrow ? jfa::kFwdBlockRows : jfa::kDmaBlockRows), w, 0, s);
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
     if (f32) { ScopedTimer tm("fwd_f32", s); e = jfa::launch_fwd_f32((const float *)q, (const float *)k, (const float *)v, offsets, offsets_kv, causal, (int)B, H, D, sc, (float *)out, lse, w.cus, s); }
@@ -270,8 +271,8 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
     const int block_rows = f32 ? jfa::kF32BlockRows : (dma ? jfa::kDmaBlockRows : jfa::kBwdBlockRows);
     // Schedule 0: blocks of queries.  Schedule 1: blocks of keys, only different from schedule 0 for cross attention.
     // Both launches clear all work counters, and both run before the first kernel that uses one.
-    e = schedule(offsets, B, block_rows, w, 0, s);
-    if (e == hipSuccess && offsets_kv) e = schedule(offsets_kv, B, block_rows, w, 1, s);
+    e = schedule(offsets, offsets_kv, B, block_rows, w, 0, s);
+    if (e == hipSuccess && offsets_kv) e = schedule(offsets_kv, offsets, B, block_rows, w, 1, s);
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     const int kv = offsets_kv ? 1 : 0;
     const int64_t *const offsets_k = offsets_kv ? offsets_kv : offsets;   // the keys' offsets
@@ -414,7 +415,7 @@ int unfused_begin(const char *who, int64_t B, int64_t max_len, int H, int D, con
     if (st != JFA_OK || B == 0) return st;
     if ((st = get_table(B, s, w)) != JFA_OK) return st;
     hipError_t e;
-    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, (int)B, 128, w->order[0], w->tile_start[0], w->counters, jfa::kNumCounters, s); }
+    { ScopedTimer tm("schedule", s); e = jfa::launch_schedule(offsets, nullptr, (int)B, 128, w->order[0], w->tile_start[0], w->counters, jfa::kNumCounters, s); }
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     *sc = jfa::Schedule{w->order[0], w->tile_start[0], w->counters};
     return JFA_OK;

@@ -248,9 +248,11 @@ __device__ inline bool load_work(const WorkSlot *slot, Work &t) {
 
 // ---- launchers (each enqueues on `stream` and returns the launch status; `cus` = compute units of the device) ----
 
-// Scheduler: fills order / tile_start for the given row-block size and zeroes `n_counters` counters.
-hipError_t launch_schedule(const int64_t *offsets, int B, int block_rows, int32_t *order, int32_t *tile_start,
-                           int32_t *counters, int n_counters, hipStream_t stream);
+// Scheduler: fills order / tile_start for the given row-block size and zeroes `n_counters` counters.  Blocks are
+// counted over `offsets`; samples are ordered by the length of the rows that stream past a block (offsets_other:
+// cross attention; nullptr: the sample's own length).
+hipError_t launch_schedule(const int64_t *offsets, const int64_t *offsets_other, int B, int block_rows, int32_t *order,
+                           int32_t *tile_start, int32_t *counters, int n_counters, hipStream_t stream);
 hipError_t launch_check_offsets(const int64_t *offsets, int B, int64_t max_len, int *flags, hipStream_t stream);
 
 // fp32 path

@@ -30,7 +30,10 @@ __device__ inline int block_inclusive_scan(int x, int *wave_sums) {
     return x + base;
 }
 
-__global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int64_t *__restrict__ offsets, int B,
+// offsets_other (cross attention, else nullptr): the offsets of the rows that stream past a block.  Blocks are
+// counted over `offsets`, but a block's cost grows with the length of the stream, so samples are ordered by that.
+__global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int64_t *__restrict__ offsets,
+                                                                 const int64_t *__restrict__ offsets_other, int B,
                                                                  int block_rows, int32_t *__restrict__ order,
                                                                  int32_t *__restrict__ tile_start,
                                                                  int32_t *__restrict__ counters, int n_counters) {
@@ -44,12 +47,13 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int64_t *
     for (int i = tid; i < kSchedBins; i += kSchedThreads) { hist[i] = 0; cursor[i] = 0; }
     __syncthreads();
 
-    // 1. histogram of row-block counts
-    for (int b = tid; b < B; b += kSchedThreads) {
-        const int64_t len = offsets[b + 1] - offsets[b];
-        const int64_t nq = (len + block_rows - 1) / block_rows;
-        atomicAdd(&hist[nq < kSchedBins - 1 ? (int)nq : kSchedBins - 1], 1);
-    }
+    // 1. histogram of the sort key: the row-block count of the stream (of the sample itself in self attention)
+    auto sort_key = [&](int b) {
+        const int64_t *o = offsets_other ? offsets_other : offsets;
+        const int64_t key = (o[b + 1] - o[b] + block_rows - 1) / block_rows;
+        return key < kSchedBins - 1 ? (int)key : kSchedBins - 1;
+    };
+    for (int b = tid; b < B; b += kSchedThreads) atomicAdd(&hist[sort_key(b)], 1);
     __syncthreads();
 
     // 2. bins in descending order: first position of bin i = number of samples in bins above i.
@@ -66,7 +70,7 @@ __global__ __launch_bounds__(kSchedThreads) void schedule_kernel(const int64_t *
     for (int b = tid; b < B; b += kSchedThreads) {
         const int64_t len = offsets[b + 1] - offsets[b];
         const int64_t nq = (len + block_rows - 1) / block_rows;
-        const int bin = nq < kSchedBins - 1 ? (int)nq : kSchedBins - 1;
+        const int bin = sort_key(b);
         const int pos = hist[bin] + atomicAdd(&cursor[bin], 1);
         order[pos] = b;
         tile_start[pos + 1] = (int)nq;
@@ -97,9 +101,9 @@ __global__ void check_offsets_kernel(const int64_t *__restrict__ offsets, int B,
     if (f) atomicOr(flags, f);
 }
 
-hipError_t launch_schedule(const int64_t *offsets, int B, int block_rows, int32_t *order, int32_t *tile_start,
-                           int32_t *counters, int n_counters, hipStream_t stream) {
-    hipLaunchKernelGGL(schedule_kernel, dim3(1), dim3(kSchedThreads), 0, stream, offsets, B, block_rows, order,
+hipError_t launch_schedule(const int64_t *offsets, const int64_t *offsets_other, int B, int block_rows, int32_t *order,
+                           int32_t *tile_start, int32_t *counters, int n_counters, hipStream_t stream) {
+    hipLaunchKernelGGL(schedule_kernel, dim3(1), dim3(kSchedThreads), 0, stream, offsets, offsets_other, B, block_rows, order,
                        tile_start, counters, n_counters);
     return hipGetLastError();
 }
