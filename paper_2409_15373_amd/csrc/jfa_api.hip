@@ -244,13 +244,12 @@ int forward_impl(const char *who, bool f32, bool causal, const void *q, const vo
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
-    // causal attention runs on the register-staged kernels at every length (the direct-to-LDS kernels have no causal form)
-    const FwdVariant variant = (f32 || causal) ? kNarrow : forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H);
+    const FwdVariant variant = f32 ? kNarrow : forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H);
     e = schedule(offsets, offsets_kv, B, f32 ? jfa::kF32BlockRows : (variant == kNarrow ? jfa::kFwdBlockRows : jfa::kDmaBlockRows), w, 0, s);
     if (e != hipSuccess) return hip_fail("schedule kernel", e);
     jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
     if (f32) { ScopedTimer tm("fwd_f32", s); e = jfa::launch_fwd_f32((const float *)q, (const float *)k, (const float *)v, offsets, offsets_kv, causal, (int)B, H, D, sc, (float *)out, lse, w.cus, s); }
-    else if (variant == kDma) { ScopedTimer tm("fwd_bf16_dma", s); e = jfa::launch_fwd_bf16_dma(q, k, v, offsets, offsets_kv, (int)B, H, D, sc, out, lse, w.cus, s); }
+    else if (variant == kDma) { ScopedTimer tm("fwd_bf16_dma", s); e = jfa::launch_fwd_bf16_dma(q, k, v, offsets, offsets_kv, causal, (int)B, H, D, sc, out, lse, w.cus, s); }
     else { ScopedTimer tm("fwd_bf16", s); e = jfa::launch_fwd_bf16(q, k, v, offsets, offsets_kv, causal, (int)B, H, D, sc, out, lse, w.cus, s); }
     if (e != hipSuccess) return hip_fail("forward kernel", e);
     return JFA_OK;
@@ -267,7 +266,7 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
-    const bool dma = !f32 && !causal && D == 128 && forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H) != kNarrow;
+    const bool dma = !f32 && D == 128 && forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H) != kNarrow;
     const int block_rows = f32 ? jfa::kF32BlockRows : (dma ? jfa::kDmaBlockRows : jfa::kBwdBlockRows);
     // Schedule 0: blocks of queries.  Schedule 1: blocks of keys, only different from schedule 0 for cross attention.
     // Both launches clear all work counters, and both run before the first kernel that uses one.
@@ -294,7 +293,7 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
         for (int mode = 0; mode < 3; ++mode) {
             const int which = mode == 0 ? 0 : kv;
             jfa::Schedule sc{w.order[which], w.tile_start[which], w.counters + mode * jfa::kXcds};
-            { ScopedTimer tm(names[mode], s); e = jfa::launch_bwd_bf16_dma(mode, q, k, v, dout, lse, delta, mode == 0 ? offsets : offsets_k, mode == 0 ? offsets_kv : offsets_q_other, (int)B, H, D, sc, grads[mode], w.cus, s); }
+            { ScopedTimer tm(names[mode], s); e = jfa::launch_bwd_bf16_dma(mode, q, k, v, dout, lse, delta, mode == 0 ? offsets : offsets_k, mode == 0 ? offsets_kv : offsets_q_other, causal, (int)B, H, D, sc, grads[mode], w.cus, s); }
             if (e != hipSuccess) return hip_fail(names[mode], e);
         }
         return JFA_OK;

@@ -49,7 +49,11 @@ __device__ inline void bd_dma4(const void *base, uint32_t byte_offset, char *lds
 
 // CROSS (cross attention): `offsets` belongs to the stationary rows (queries for dQ, keys for dK and dV) and
 // offsets_other to the rows that stream past them; otherwise offsets_other is not looked at.
-template <int MODE, bool CROSS>
+// CAUSAL (self attention only): query i sees keys 0 .. i.  dQ streams the keys up to the tile's last query and masks
+// above the diagonal in the stages that reach past the tile's first query; dK and dV start their stream of queries at
+// the stage of the tile's first key and zero P for the queries before the lane's key in the four stages that overlap
+// the tile.  Masking stages use the form that also handles the sample's ragged end.
+template <int MODE, bool CROSS, bool CAUSAL>
 __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf16 *__restrict__ q,
                                                                      const __bf16 *__restrict__ k,
                                                                      const __bf16 *__restrict__ v,
@@ -114,7 +118,11 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         const int Ls = t.len;                      // stationary rows of the sample
         const int L = CROSS ? t.olen : t.len;      // streamed rows of the sample
         const int64_t srow0 = CROSS ? t.orow0 : t.row0;
-        const int n_stages = (L + kBdBN - 1) / kBdBN;
+        const int tile0 = t.block * kDmaBlockRows;   // first stationary row of the tile
+        // causal: the streamed rows a tile needs are keys 0 .. (tile's last query) for dQ, queries (tile's first key) .. L - 1 for dK, dV
+        const int Lc = CAUSAL && !kRowStats && tile0 + kDmaBlockRows < L ? tile0 + kDmaBlockRows : L;
+        const int js = CAUSAL && kRowStats ? tile0 / kBdBN : 0;   // first stage of the stream
+        const int n_stages = (Lc + kBdBN - 1) / kBdBN;
         const int64_t head_off = srow0 * row_stride + (int64_t)t.head * D;
         if (CROSS && L == 0) {   // nothing streams past these rows: their gradient is zero
             if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, offsets_other);
@@ -280,7 +288,9 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     float p = fast_exp2(sc[4 * g + e]);
-                    if (ragged && j0 + mb * 32 + g * 8 + half * 4 + e >= L) p = 0.0f;   // streamed rows past the end
+                    const int r = j0 + mb * 32 + g * 8 + half * 4 + e;   // this register's streamed row
+                    if (ragged && (r >= (CAUSAL && !kRowStats && ic + 1 < L ? ic + 1 : L) || (CAUSAL && kRowStats && r < ic)))
+                        p = 0.0f;   // past the sample's end, or on the wrong side of the diagonal
                     sc[4 * g + e] = p;
                     if (MODE == kModeDK) dp[4 * g + e] = p * dp[4 * g + e];                  // = -dS
                     if (MODE == kModeDQ) dp[4 * g + e] = p * dp[4 * g + e];
@@ -326,7 +336,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                 const char *St = Bf == 0 ? S0 : (Bf == 1 ? S1 : S2);
                 const int j0 = j * kBdBN;
                 run_block(RAGGED, At, Bt, St, 0, j0);
-                if (!ragged || j0 + 32 < L) run_block(RAGGED, At, Bt, St, 1, j0);
+                if (!ragged || j0 + 32 < Lc) run_block(RAGGED, At, Bt, St, 1, j0);
             }
             asm volatile("" ::: "memory");
             if (ahead) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);
@@ -334,8 +344,8 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             asm volatile("" ::: "memory");
         };
 
-        issue_stage(IntB<0>{}, 0);
-        if (n_stages > 1) issue_stage(IntB<1>{}, 1);
+        issue_stage(IntB<0>{}, js);
+        if (n_stages - js > 1) issue_stage(IntB<1>{}, js + 1);
         if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_other : nullptr);   // overlaps with the loads in flight
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) {
@@ -348,9 +358,18 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         for (int ks = 0; ks < kKSteps; ++ks)
 #pragma unroll
             for (int e = 0; e < 8; ++e) xreg[ks][e] = (__bf16)((float)xreg[ks][e] * c);
-        if (n_stages > 1) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);
+        if (n_stages - js > 1) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);
         __syncthreads();
-        {
+        if (CAUSAL) {   // stage j lives in buffer (j - js) % 3; which stages mask depends on the side of the diagonal
+            for (int j = js; j < n_stages; ++j) {
+                const bool masking = kRowStats ? (j < js + kDmaBlockRows / kBdBN || (j + 1) * kBdBN > L)
+                                               : (j + 1) * kBdBN > (tile0 + 1 < L ? tile0 + 1 : L);
+                const int r = (j - js) % 3;
+                if (r == 0) { if (masking) run_stage(IntB<0>{}, IntB<1>{}, j); else run_stage(IntB<0>{}, IntB<0>{}, j); }
+                else if (r == 1) { if (masking) run_stage(IntB<1>{}, IntB<1>{}, j); else run_stage(IntB<1>{}, IntB<0>{}, j); }
+                else { if (masking) run_stage(IntB<2>{}, IntB<1>{}, j); else run_stage(IntB<2>{}, IntB<0>{}, j); }
+            }
+        } else {
             const int n_full = L / kBdBN;   // stages with all 64 streamed rows valid; a ragged one may follow
             int j = 0;
             for (; j + 3 <= n_full; j += 3) {
@@ -403,28 +422,29 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
 
 template <int MODE>
 static hipError_t launch_mode(const void *q, const void *k, const void *v, const void *dout, const float *lse,
-                              const float *delta, const int64_t *offsets, const int64_t *offsets_other, int B, int H,
-                              Schedule s, void *grad, int cus, hipStream_t stream) {
-    if (offsets_other)
-        hipLaunchKernelGGL((bwd_bf16_dma_kernel<MODE, true>), dim3(persistent_grid<bwd_bf16_dma_kernel<MODE, true>>(kBdThreads, cus)),
-                           dim3(kBdThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,
-                           (const __bf16 *)dout, lse, delta, offsets, offsets_other, B, H, s, (__bf16 *)grad);
-    else
-        hipLaunchKernelGGL((bwd_bf16_dma_kernel<MODE, false>), dim3(persistent_grid<bwd_bf16_dma_kernel<MODE, false>>(kBdThreads, cus)),
-                           dim3(kBdThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,
-                           (const __bf16 *)dout, lse, delta, offsets, offsets_other, B, H, s, (__bf16 *)grad);
+                              const float *delta, const int64_t *offsets, const int64_t *offsets_other, bool causal, int B,
+                              int H, Schedule s, void *grad, int cus, hipStream_t stream) {
+    if (causal && offsets_other) return hipErrorInvalidValue;
+#define JFA_LAUNCH(CROSS, CAUSAL)                                                                                           \
+    hipLaunchKernelGGL((bwd_bf16_dma_kernel<MODE, CROSS, CAUSAL>), dim3(persistent_grid<bwd_bf16_dma_kernel<MODE, CROSS, CAUSAL>>(kBdThreads, cus)), \
+                       dim3(kBdThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,                \
+                       (const __bf16 *)dout, lse, delta, offsets, offsets_other, B, H, s, (__bf16 *)grad)
+    if (offsets_other) JFA_LAUNCH(true, false);
+    else if (causal) JFA_LAUNCH(false, true);
+    else JFA_LAUNCH(false, false);
+#undef JFA_LAUNCH
     return hipGetLastError();
 }
 
 hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const void *v, const void *dout,
                                const float *lse, const float *delta, const int64_t *offsets,
-                               const int64_t *offsets_other, int B, int H, int D, Schedule s, void *grad, int cus,
-                               hipStream_t stream) {
+                               const int64_t *offsets_other, bool causal, int B, int H, int D, Schedule s, void *grad,
+                               int cus, hipStream_t stream) {
     if (D != kBdD) return hipErrorInvalidValue;
     switch (mode) {
-        case kModeDQ: return launch_mode<kModeDQ>(q, k, v, dout, lse, delta, offsets, offsets_other, B, H, s, grad, cus, stream);
-        case kModeDK: return launch_mode<kModeDK>(q, k, v, dout, lse, delta, offsets, offsets_other, B, H, s, grad, cus, stream);
-        case kModeDV: return launch_mode<kModeDV>(q, k, v, dout, lse, delta, offsets, offsets_other, B, H, s, grad, cus, stream);
+        case kModeDQ: return launch_mode<kModeDQ>(q, k, v, dout, lse, delta, offsets, offsets_other, causal, B, H, s, grad, cus, stream);
+        case kModeDK: return launch_mode<kModeDK>(q, k, v, dout, lse, delta, offsets, offsets_other, causal, B, H, s, grad, cus, stream);
+        case kModeDV: return launch_mode<kModeDV>(q, k, v, dout, lse, delta, offsets, offsets_other, causal, B, H, s, grad, cus, stream);
         default: return hipErrorInvalidValue;
     }
 }

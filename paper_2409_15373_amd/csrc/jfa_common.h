@@ -290,13 +290,13 @@ hipError_t launch_dq_bf16(const void *q, const void *k, const void *v, const voi
 // bf16 attention, direct-to-LDS kernels (D = 128, long samples; work items are blocks of kDmaBlockRows rows)
 constexpr int kDmaBlockRows = 256;
 hipError_t launch_fwd_bf16_dma(const void *q, const void *k, const void *v, const int64_t *offsets,
-                               const int64_t *offsets_kv, int B, int H, int D, Schedule s, void *out, float *lse, int cus,
-                               hipStream_t stream);
+                               const int64_t *offsets_kv, bool causal, int B, int H, int D, Schedule s, void *out, float *lse,
+                               int cus, hipStream_t stream);
 // mode: 0 = dQ, 1 = dK, 2 = dV
 hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const void *v, const void *dout,
                                const float *lse, const float *delta, const int64_t *offsets,
-                               const int64_t *offsets_other, int B, int H, int D, Schedule s, void *grad, int cus,
-                               hipStream_t stream);
+                               const int64_t *offsets_other, bool causal, int B, int H, int D, Schedule s, void *grad,
+                               int cus, hipStream_t stream);
 
 // Unfused jagged attention (Table 1): offsets of the jagged square array, then the three operators.
 hipError_t launch_square_offsets(const int64_t *offsets, int B, int64_t *sq, hipStream_t stream);

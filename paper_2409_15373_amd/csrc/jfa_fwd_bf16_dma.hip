@@ -38,8 +38,11 @@ __device__ inline void dma16b(const __bf16 *base, uint32_t byte_offset, char *ld
 }
 
 // CROSS: the keys and values of a sample are the rows of a second offsets array (cross attention); otherwise
-// offsets_kv is not looked at and the code is that of self attention.
-template <bool CROSS>
+// offsets_kv is not looked at and the code is that of self attention.  CAUSAL (self attention only): query i attends
+// to keys 0 .. i.  A tile then streams the keys up to its last query; the stages whose keys all lie at or below the
+// tile's first query run unmasked, the others (up to five) run in the masking form of a stage with the per-lane
+// limit min(L, i + 1) in place of L.
+template <bool CROSS, bool CAUSAL>
 __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf16 *__restrict__ q,
                                                                       const __bf16 *__restrict__ k,
                                                                       const __bf16 *__restrict__ v,
@@ -108,7 +111,9 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         const int Lq = t.len;                      // queries of the sample
         const int L = CROSS ? t.olen : t.len;      // keys of the sample
         const int64_t krow0 = CROSS ? t.orow0 : t.row0;
-        const int n_stages = (L + kDmaBN - 1) / kDmaBN;
+        const int q_tile0 = t.block * kDmaBlockRows;   // first query of the tile
+        const int Lc = CAUSAL && q_tile0 + kDmaBlockRows < L ? q_tile0 + kDmaBlockRows : L;   // keys this tile needs
+        const int n_stages = (Lc + kDmaBN - 1) / kDmaBN;
         const __bf16 *kbase = k + krow0 * row_stride + (int64_t)t.head * D;
         const __bf16 *vbase = v + krow0 * row_stride + (int64_t)t.head * D;
         if (CROSS && L == 0) {   // no keys: an empty softmax, out = 0 and lse = -inf
@@ -208,10 +213,10 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
                 p[ts] = __builtin_bit_cast(bf16x8, pw);
             }
         };
-        auto mask = [&](f32x16 &st, int key0) {   // keys past the end of the sample
+        auto mask = [&](f32x16 &st, int key0) {   // keys past the end of the sample (causal: and above the diagonal)
             int h = half;
             asm volatile("" : "+v"(h));   // keeps the sixteen thresholds from being computed at tile start and spilled
-            const int lim = L - key0 - 4 * h;   // accumulator register e holds key key0 + (e / 4) * 8 + 4 * half + e % 4
+            const int lim = (CAUSAL && iq + 1 < L ? iq + 1 : L) - key0 - 4 * h;   // accumulator register e holds key key0 + (e / 4) * 8 + 4 * half + e % 4
 #pragma unroll
             for (int e = 0; e < 16; ++e)
                 if ((e >> 2) * 8 + (e & 3) >= lim) st[e] = -INFINITY;
@@ -271,7 +276,7 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             bf16x8 p0[2], p1[2];
             scores(Kc, 0, s0);
             scores(Kc, 1, s1);
-            if ((j + 1) * kDmaBN > L) { mask(s0, j * kDmaBN); mask(s1, j * kDmaBN + 32); }
+            if (CAUSAL || (j + 1) * kDmaBN > L) { mask(s0, j * kDmaBN); mask(s1, j * kDmaBN + 32); }
             const float x = pair_max(unit_max(s1, unit_max(s0, -INFINITY)));
             const float n = fmaxf(m, x);
             const float a = fast_exp2(m - n);   // 0 on the first stage
@@ -325,14 +330,16 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         if (wave_active) {   // reference maximum: the first 32 keys
             f32x16 s0;
             scores(K0, 0, s0);
-            if (L < 32) mask(s0, 0);
+            if (CAUSAL || L < 32) mask(s0, 0);
             m = pair_max(unit_max(s0, -INFINITY));
         }
 #pragma unroll
         for (int e = 0; e < 16; ++e) negm[e] = -m;
         asm volatile("" : "+v"(negm));   // sixteen real registers: the matrix product reads its addend from them
         {
-            const int n_full = L / kDmaBN;   // stages with all 64 keys valid; a ragged one may follow
+            // stages with all 64 keys valid for every query of the tile; the others follow in the masking form:
+            // the sample's ragged last stage, and if causal the stages that reach above the tile's first query
+            const int n_full = (CAUSAL && q_tile0 + 1 < L ? q_tile0 + 1 : L) / kDmaBN;
             int j = 0;
             for (; j + 3 <= n_full; j += 3) {
                 run_stage(IntC<0>{}, IntC<0>{}, j);
@@ -341,8 +348,8 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             }
             if (j < n_full) { run_stage(IntC<0>{}, IntC<0>{}, j); ++j; }
             if (j < n_full) { run_stage(IntC<1>{}, IntC<0>{}, j); ++j; }
-            if (j < n_stages) {               // the ragged last stage, in buffer n_full % 3
-                const int r = n_full % 3;
+            for (; j < n_stages; ++j) {       // masking stages (one at most unless causal), stage j in buffer j % 3
+                const int r = j % 3;
                 if (r == 0) run_stage(IntC<0>{}, IntC<1>{}, j);
                 else if (r == 1) run_stage(IntC<1>{}, IntC<1>{}, j);
                 else run_stage(IntC<2>{}, IntC<1>{}, j);
@@ -416,17 +423,17 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
 }
 
 hipError_t launch_fwd_bf16_dma(const void *q, const void *k, const void *v, const int64_t *offsets,
-                               const int64_t *offsets_kv, int B, int H, int D, Schedule s, void *out, float *lse, int cus,
-                               hipStream_t stream) {
-    if (D != kDmaD) return hipErrorInvalidValue;
-    if (offsets_kv)
-        hipLaunchKernelGGL(fwd_bf16_dma_kernel<true>, dim3(persistent_grid<fwd_bf16_dma_kernel<true>>(kDmaThreads, cus)),
-                           dim3(kDmaThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, offsets,
-                           offsets_kv, B, H, s, (__bf16 *)out, lse);
-    else
-        hipLaunchKernelGGL(fwd_bf16_dma_kernel<false>, dim3(persistent_grid<fwd_bf16_dma_kernel<false>>(kDmaThreads, cus)),
-                           dim3(kDmaThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, offsets,
-                           offsets_kv, B, H, s, (__bf16 *)out, lse);
+                               const int64_t *offsets_kv, bool causal, int B, int H, int D, Schedule s, void *out, float *lse,
+                               int cus, hipStream_t stream) {
+    if (D != kDmaD || (causal && offsets_kv)) return hipErrorInvalidValue;
+#define JFA_LAUNCH(CROSS, CAUSAL)                                                                                          \
+    hipLaunchKernelGGL((fwd_bf16_dma_kernel<CROSS, CAUSAL>), dim3(persistent_grid<fwd_bf16_dma_kernel<CROSS, CAUSAL>>(kDmaThreads, cus)), \
+                       dim3(kDmaThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, offsets,     \
+                       offsets_kv, B, H, s, (__bf16 *)out, lse)
+    if (offsets_kv) JFA_LAUNCH(true, false);
+    else if (causal) JFA_LAUNCH(false, true);
+    else JFA_LAUNCH(false, false);
+#undef JFA_LAUNCH
     return hipGetLastError();
 }
 

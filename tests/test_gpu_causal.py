@@ -1,9 +1,10 @@
 """Causal jagged self attention on the GPU vs oracle/causal.py, forward and backward, fp32 and bf16.
 
 Gates as for the non-causal path (fp32 2e-5 relative to max(1, |ref|); bf16 2e-2 absolute and 1e-2 of the tensor's
-maximum).  Lengths cover several 128-row tiles and 64-key stages, tiles whose diagonal crosses stage boundaries,
-ragged tails, and samples of length 0 and 1.  Causal attention runs on the register-staged kernels at every length,
-so one case is long (max_len > 256 at D = 128, where the non-causal path would pick the direct-to-LDS kernels).
+maximum).  Lengths cover several row tiles and 64-key stages, tiles whose diagonal crosses stage boundaries, ragged
+tails, and samples of length 0 and 1; D = 128 runs with max_len <= 256 (register-staged kernels) and with
+max_len > 256 (direct-to-LDS kernels: 256-row tiles, the masking stages around the diagonal, the stream of dK / dV
+starting at the tile's first key).
 """
 import numpy as np
 import pytest
@@ -58,8 +59,9 @@ def test_causal_bf16(D, H):
     run(make_custom("causal", LENGTHS, H, D, dtype="bf16", seed=22 + D), 512 if D != 128 else 256)
 
 
-def test_causal_bf16_long_samples():
-    run(make_custom("causal", [1000, 513, 64, 700, 1], 2, 128, dtype="bf16", seed=23), 1024)
+@pytest.mark.parametrize("lengths", [[1000, 513, 64, 700, 1], [256, 257, 0, 255, 300, 65, 2, 1281, 768]])
+def test_causal_bf16_long_samples(lengths):
+    run(make_custom("causal", lengths, 2, 128, dtype="bf16", seed=23), 2048)
 
 
 def test_causal_first_row_returns_v_and_later_rows_ignore_the_future():
