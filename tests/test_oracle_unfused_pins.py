@@ -7,6 +7,10 @@ each test checks it against something that is not itself.
       score rows give uniform probabilities; an identity probability block returns V
   U4  layout: the score of (sample b, head h, query i, key j) sits at [h, sq[b] + i * L_b + j]; zero-length
       samples take no room; nothing of one sample reaches another
+  U5  backward operators: product(q, k, 1/sqrt(D)) is scores; the chain dP = product(dout, v, 1),
+      dS = softmax_rows_backward(P, dP, 1/sqrt(D)), dV = apply_transposed(P, dout), dQ = apply(dS, k),
+      dK = apply_transposed(dS, q) equals the backward of the C attention oracle and torch autograd through the
+      unfused forward; softmax_rows_backward is the vector-Jacobian product of torch.softmax row by row
 """
 import numpy as np
 import pytest
@@ -89,3 +93,25 @@ def test_u4_layout_and_sample_isolation():
     S2 = unfused.scores(q, k2, w.offsets)
     np.testing.assert_array_equal(S2[:, :9], S[:, :9])
     assert not np.array_equal(S2[:, 9:], S[:, 9:])
+
+
+def test_u5_backward_chain(oracle):
+    w = make_custom("unfused", [9, 1, 0, 14, 4], 2, 8, "f32", sigma=1.0, seed=5)
+    q, k, v, do = (np.asarray(x, dtype=np.float64) for x in (w.q, w.k, w.v, w.dout))
+    c = 1.0 / np.sqrt(8)
+    np.testing.assert_allclose(unfused.product(q, k, w.offsets, c), unfused.scores(q, k, w.offsets), rtol=1e-14, atol=1e-15)   # x * c vs x / sqrt(D)
+    P = unfused.softmax_rows(unfused.scores(q, k, w.offsets), w.offsets)
+    dP = unfused.product(do, v, w.offsets, 1.0)
+    dS = unfused.softmax_rows_backward(P, dP, w.offsets, c)
+    dV, dQ, dK = unfused.apply_transposed(P, do, w.offsets), unfused.apply(dS, k, w.offsets), unfused.apply_transposed(dS, q, w.offsets)
+    r_dq, r_dk, r_dv, _ = oracle.backward(w.q, w.k, w.v, w.dout, w.offsets)        # the C oracle: another program
+    np.testing.assert_allclose(dQ, r_dq, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(dK, r_dk, rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(dV, r_dv, rtol=1e-10, atol=1e-12)
+    # softmax_rows_backward against autograd of torch.softmax, one block
+    sq = unfused.square_offsets(w.offsets)
+    S = torch.from_numpy(unfused.scores(q, k, w.offsets)[1, sq[3]:sq[4]].reshape(14, 14)).requires_grad_(True)
+    g = torch.from_numpy(dP[1, sq[3]:sq[4]].reshape(14, 14))
+    (torch.softmax(S, dim=1) * g).sum().backward()
+    np.testing.assert_allclose(unfused.softmax_rows_backward(P, dP, w.offsets)[1, sq[3]:sq[4]].reshape(14, 14), S.grad.numpy(),
+                               rtol=1e-11, atol=1e-13)
