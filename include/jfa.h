@@ -142,6 +142,15 @@ int jfa_backward_causal_f32(const float *q, const float *k, const float *v, cons
  *   jfa_unfused_softmax  row softmax of every L_b x L_b block, in place.
  *   jfa_unfused_apply    out = P v per sample and head (v, out bf16 [sum_B, H, D]); P is rounded to bf16 for
  *                        the matrix product, as in the fused kernel.
+ * The paper builds forward and backward for its jagged operators (Section 2.2); the gradients of the three are
+ * products of the same kinds plus the softmax's own backward, on the same array layout:
+ *   jfa_unfused_product           out[h, sq[b] + i L_b + j] = scale * a[s_b + i, h, :] . b[s_b + j, h, :]  (a, b bf16
+ *                                 [sum_B, H, D]); jfa_unfused_scores is the case scale = 1 / sqrt(D), and
+ *                                 dP = product(dout, v, 1).
+ *   jfa_unfused_softmax_backward  dprobs <- scale * P o (dprobs - rowsum(P o dprobs)) row by row, in place (dS from dP;
+ *                                 with scale = 1 / sqrt(D) the two products below need no further scaling).
+ *   jfa_unfused_apply_transposed  out[s_b + j, h, :] = sum_i array[h, sq[b] + i L_b + j] x[s_b + i, h, :]  (x, out bf16):
+ *                                 dV = apply_transposed(P, dout), dK = apply_transposed(dS, q); dQ = jfa_unfused_apply(dS, k).
  * Errors, streams and ownership as for the calls above.
  */
 int jfa_square_offsets(const int64_t *offsets, int64_t B, int64_t *sq_offsets, void *stream);
@@ -151,6 +160,12 @@ int jfa_unfused_softmax(const int64_t *offsets, const int64_t *sq_offsets, int64
                         float *scores, void *stream);
 int jfa_unfused_apply(const float *probs, const void *v, const int64_t *offsets, const int64_t *sq_offsets, int64_t B,
                       int64_t max_len, int H, int D, void *out, void *stream);
+int jfa_unfused_product(const void *a, const void *b, const int64_t *offsets, const int64_t *sq_offsets, int64_t B,
+                        int64_t max_len, int H, int D, float scale, float *out, void *stream);
+int jfa_unfused_softmax_backward(const float *probs, const int64_t *offsets, const int64_t *sq_offsets, int64_t B,
+                                 int64_t max_len, int H, float scale, float *dprobs, void *stream);
+int jfa_unfused_apply_transposed(const float *array, const void *x, const int64_t *offsets, const int64_t *sq_offsets,
+                                 int64_t B, int64_t max_len, int H, int D, void *out, void *stream);
 
 /*
  * Jagged <-> padded-dense conversion (paper Section 2.2: jagged tensors are padded where a dense operator

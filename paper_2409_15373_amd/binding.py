@@ -29,7 +29,8 @@ EXPORTS = (
     "jfa_jagged_to_dense", "jfa_dense_to_jagged", "jfa_jagged_dense_bmm", "jfa_jagged_jagged_bmm",
     "jfa_jagged_softmax", "jfa_jagged_softmax_backward", "jfa_forward_cross", "jfa_forward_cross_f32",
     "jfa_backward_cross", "jfa_backward_cross_f32", "jfa_forward_causal", "jfa_forward_causal_f32",
-    "jfa_backward_causal", "jfa_backward_causal_f32",
+    "jfa_backward_causal", "jfa_backward_causal_f32", "jfa_unfused_product", "jfa_unfused_softmax_backward",
+    "jfa_unfused_apply_transposed",
 )
 
 
@@ -92,6 +93,12 @@ def load() -> ctypes.CDLL:
     lib.jfa_unfused_softmax.argtypes = [vp, vp, i64, i64, i32, vp, vp]
     lib.jfa_unfused_apply.restype = i32
     lib.jfa_unfused_apply.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, vp]
+    lib.jfa_unfused_product.restype = i32
+    lib.jfa_unfused_product.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, ctypes.c_float, vp, vp]
+    lib.jfa_unfused_softmax_backward.restype = i32
+    lib.jfa_unfused_softmax_backward.argtypes = [vp, vp, vp, i64, i64, i32, ctypes.c_float, vp, vp]
+    lib.jfa_unfused_apply_transposed.restype = i32
+    lib.jfa_unfused_apply_transposed.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, vp]
     lib.jfa_jagged_to_dense.restype = i32
     lib.jfa_jagged_to_dense.argtypes = [vp, vp, i64, i64, i64, ctypes.c_uint32, vp, vp]
     lib.jfa_dense_to_jagged.restype = i32
@@ -240,6 +247,30 @@ def jfa_unfused_apply(probs, v, offsets, sq_offsets, max_len: int, out: Optional
     out = torch.empty_like(v) if out is None else out
     _check(load().jfa_unfused_apply(_ptr(probs), _ptr(v), _ptr(offsets), _ptr(sq_offsets), offsets.numel() - 1,
                                     max_len, H, D, _ptr(out), _stream()))
+    return out
+
+
+def jfa_unfused_product(a, b, offsets, sq_offsets, max_len: int, scale: float, out: torch.Tensor):
+    """out fp32 [H, sq[B]] = scale * a b^T per sample and head (the scaled product behind scores and dP)."""
+    _, H, D = a.shape
+    _check(load().jfa_unfused_product(_ptr(a), _ptr(b), _ptr(offsets), _ptr(sq_offsets), offsets.numel() - 1, max_len,
+                                      H, D, scale, _ptr(out), _stream()))
+    return out
+
+
+def jfa_unfused_softmax_backward(probs, offsets, sq_offsets, max_len: int, H: int, scale: float, dprobs: torch.Tensor):
+    """dprobs <- scale * P o (dprobs - rowsum(P o dprobs)), row by row, in place."""
+    _check(load().jfa_unfused_softmax_backward(_ptr(probs), _ptr(offsets), _ptr(sq_offsets), offsets.numel() - 1, max_len,
+                                               H, scale, _ptr(dprobs), _stream()))
+    return dprobs
+
+
+def jfa_unfused_apply_transposed(array, x, offsets, sq_offsets, max_len: int, out: Optional[torch.Tensor] = None):
+    """out [sum_B, H, D] (bf16): out_j = sum_i array[i, j] x_i per sample and head."""
+    _, H, D = x.shape
+    out = torch.empty_like(x) if out is None else out
+    _check(load().jfa_unfused_apply_transposed(_ptr(array), _ptr(x), _ptr(offsets), _ptr(sq_offsets), offsets.numel() - 1,
+                                               max_len, H, D, _ptr(out), _stream()))
     return out
 
 

@@ -430,7 +430,7 @@ int jfa_unfused_scores(const void *q, const void *k, const int64_t *offsets, con
     int st = unfused_begin("jfa_unfused_scores", B, max_len, H, D, ptrs, 5, offsets, s, &w, &sc);
     if (st != JFA_OK || B == 0) return st;
     hipError_t e;
-    { ScopedTimer tm("unfused_scores", s); e = jfa::launch_unfused_scores(q, k, offsets, sq_offsets, (int)B, H, D, sc, scores, w.cus, s); }
+    { ScopedTimer tm("unfused_scores", s); e = jfa::launch_unfused_scores(q, k, offsets, sq_offsets, (int)B, H, D, sc, 1.0f / sqrtf((float)D), scores, w.cus, s); }
     if (e != hipSuccess) return hip_fail("unfused scores kernel", e);
     return JFA_OK;
 }
@@ -446,6 +446,48 @@ int jfa_unfused_softmax(const int64_t *offsets, const int64_t *sq_offsets, int64
     hipError_t e;
     { ScopedTimer tm("unfused_softmax", s); e = jfa::launch_unfused_softmax(offsets, sq_offsets, (int)B, H, sc, scores, w.cus, s); }
     if (e != hipSuccess) return hip_fail("unfused softmax kernel", e);
+    return JFA_OK;
+}
+
+int jfa_unfused_product(const void *a, const void *b, const int64_t *offsets, const int64_t *sq_offsets, int64_t B,
+                        int64_t max_len, int H, int D, float scale, float *out, void *stream) {
+    const void *ptrs[] = {a, b, offsets, sq_offsets, out};
+    hipStream_t s = (hipStream_t)stream;
+    Views w;
+    jfa::Schedule sc;
+    int st = unfused_begin("jfa_unfused_product", B, max_len, H, D, ptrs, 5, offsets, s, &w, &sc);
+    if (st != JFA_OK || B == 0) return st;
+    hipError_t e;
+    { ScopedTimer tm("unfused_product", s); e = jfa::launch_unfused_scores(a, b, offsets, sq_offsets, (int)B, H, D, sc, scale, out, w.cus, s); }
+    if (e != hipSuccess) return hip_fail("unfused product kernel", e);
+    return JFA_OK;
+}
+
+int jfa_unfused_softmax_backward(const float *probs, const int64_t *offsets, const int64_t *sq_offsets, int64_t B,
+                                 int64_t max_len, int H, float scale, float *dprobs, void *stream) {
+    const void *ptrs[] = {probs, offsets, sq_offsets, dprobs};
+    hipStream_t s = (hipStream_t)stream;
+    Views w;
+    jfa::Schedule sc;
+    int st = unfused_begin("jfa_unfused_softmax_backward", B, max_len, H, 128, ptrs, 4, offsets, s, &w, &sc);
+    if (st != JFA_OK || B == 0) return st;
+    hipError_t e;
+    { ScopedTimer tm("unfused_softmax_bwd", s); e = jfa::launch_unfused_softmax_bwd(probs, offsets, sq_offsets, (int)B, H, sc, scale, dprobs, w.cus, s); }
+    if (e != hipSuccess) return hip_fail("unfused softmax backward kernel", e);
+    return JFA_OK;
+}
+
+int jfa_unfused_apply_transposed(const float *array, const void *x, const int64_t *offsets, const int64_t *sq_offsets,
+                                 int64_t B, int64_t max_len, int H, int D, void *out, void *stream) {
+    const void *ptrs[] = {array, x, offsets, sq_offsets, out};
+    hipStream_t s = (hipStream_t)stream;
+    Views w;
+    jfa::Schedule sc;
+    int st = unfused_begin("jfa_unfused_apply_transposed", B, max_len, H, D, ptrs, 5, offsets, s, &w, &sc);
+    if (st != JFA_OK || B == 0) return st;
+    hipError_t e;
+    { ScopedTimer tm("unfused_apply_t", s); e = jfa::launch_unfused_apply_t(array, x, offsets, sq_offsets, (int)B, H, D, sc, out, w.cus, s); }
+    if (e != hipSuccess) return hip_fail("unfused transposed apply kernel", e);
     return JFA_OK;
 }
 

@@ -301,7 +301,11 @@ hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const voi
 // Unfused jagged attention (Table 1): offsets of the jagged square array, then the three operators.
 hipError_t launch_square_offsets(const int64_t *offsets, int B, int64_t *sq, hipStream_t stream);
 hipError_t launch_unfused_scores(const void *q, const void *k, const int64_t *offsets, const int64_t *sq, int B, int H,
-                                 int D, Schedule s, float *scores, int cus, hipStream_t stream);
+                                 int D, Schedule s, float scale, float *scores, int cus, hipStream_t stream);
+hipError_t launch_unfused_softmax_bwd(const float *probs, const int64_t *offsets, const int64_t *sq, int B, int H,
+                                      Schedule s, float scale, float *dprobs, int cus, hipStream_t stream);
+hipError_t launch_unfused_apply_t(const float *X, const void *x, const int64_t *offsets, const int64_t *sq, int B, int H,
+                                  int D, Schedule s, void *out, int cus, hipStream_t stream);
 hipError_t launch_unfused_softmax(const int64_t *offsets, const int64_t *sq, int B, int H, Schedule s, float *scores,
                                   int cus, hipStream_t stream);
 hipError_t launch_unfused_apply(const float *probs, const void *v, const int64_t *offsets, const int64_t *sq, int B,

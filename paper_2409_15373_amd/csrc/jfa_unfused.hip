@@ -57,14 +57,13 @@ __global__ __launch_bounds__(kUfThreads, 2) void unfused_scores_kernel(const __b
                                                                     const __bf16 *__restrict__ k,
                                                                     const int64_t *__restrict__ offsets,
                                                                     const int64_t *__restrict__ sq, int B, int H,
-                                                                    Schedule s, float *__restrict__ scores) {
+                                                                    Schedule s, float scale, float *__restrict__ scores) {
     constexpr int kKSteps = D / 16, kChunks = D / 8, kRowBytes = D * 2 + 16;
     constexpr int kLoads = 64 * kChunks / kUfThreads;   // 16-byte chunks of a K block per thread
     __shared__ __attribute__((aligned(16))) char kt[64 * kRowBytes];
     __shared__ int64_t slot;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, half = lane >> 5;
-    const float scale = 1.0f / sqrtf((float)D);
     const int64_t total = (int64_t)s.tile_start[B] * H;
     const int64_t row_stride = (int64_t)H * D;
     const int64_t S2 = sq[B];
@@ -383,17 +382,195 @@ __global__ __launch_bounds__(kUfThreads) void unfused_apply_kernel(const float *
     }
 }
 
+// ---- backward of the row softmax: dS = scale * P o (dP - rowsum(P o dP)), written over dP ----
+// Same shape as the forward: one wave per row, both rows held in registers as 1024-byte aligned windows (P and dP
+// have the same element index, and both arrays are 16-byte aligned, so one alignment serves both).
+template <int R>
+__device__ inline void softmax_bwd_row_cached(const float *prow, float *grow, int L, float scale, int lane) {
+    const int s = __builtin_amdgcn_readfirstlane((int)((reinterpret_cast<uintptr_t>(grow) >> 2) & 255));
+    float4 p[R], g[R];
+    float dot = 0.0f;
+#pragma unroll
+    for (int u = 0; u < R; ++u) {
+        p[u] = g[u] = float4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (256 * u - s < L) {
+            const int j = 256 * u - s + 4 * lane;
+            if (j >= 0 && j + 3 < L) {
+                p[u] = *reinterpret_cast<const float4 *>(prow + j);
+                g[u] = *reinterpret_cast<const float4 *>(grow + j);
+            } else {
+                if (j >= 0 && j < L) { p[u].x = prow[j]; g[u].x = grow[j]; }
+                if (j + 1 >= 0 && j + 1 < L) { p[u].y = prow[j + 1]; g[u].y = grow[j + 1]; }
+                if (j + 2 >= 0 && j + 2 < L) { p[u].z = prow[j + 2]; g[u].z = grow[j + 2]; }
+                if (j + 3 >= 0 && j + 3 < L) { p[u].w = prow[j + 3]; g[u].w = grow[j + 3]; }
+            }
+        }
+        dot += (p[u].x * g[u].x + p[u].y * g[u].y) + (p[u].z * g[u].z + p[u].w * g[u].w);
+    }
+    for (int d = 32; d >= 1; d >>= 1) dot += __shfl_xor(dot, d, 64);
+#pragma unroll
+    for (int u = 0; u < R; ++u)
+        if (256 * u - s < L) {
+            const int j = 256 * u - s + 4 * lane;
+            const float4 y = float4{scale * p[u].x * (g[u].x - dot), scale * p[u].y * (g[u].y - dot),
+                                    scale * p[u].z * (g[u].z - dot), scale * p[u].w * (g[u].w - dot)};
+            if (j >= 0 && j + 3 < L) *reinterpret_cast<float4 *>(grow + j) = y;
+            else {
+                if (j >= 0 && j < L) grow[j] = y.x;
+                if (j + 1 >= 0 && j + 1 < L) grow[j + 1] = y.y;
+                if (j + 2 >= 0 && j + 2 < L) grow[j + 2] = y.z;
+                if (j + 3 >= 0 && j + 3 < L) grow[j + 3] = y.w;
+            }
+        }
+}
+
+__device__ inline void softmax_bwd_row_streamed(const float *prow, float *grow, int L, float scale, int lane) {
+    float dot = 0.0f;
+    for (int j = lane; j < L; j += 64) dot += prow[j] * grow[j];
+    for (int d = 32; d >= 1; d >>= 1) dot += __shfl_xor(dot, d, 64);
+    for (int j = lane; j < L; j += 64) grow[j] = scale * prow[j] * (grow[j] - dot);
+}
+
+__global__ __launch_bounds__(kUfThreads) void unfused_softmax_bwd_kernel(const float *__restrict__ probs,
+                                                                         const int64_t *__restrict__ offsets,
+                                                                         const int64_t *__restrict__ sq, int B, int H,
+                                                                         Schedule s, float scale, float *dprobs) {
+    __shared__ int64_t slot;
+    const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int64_t total = (int64_t)s.tile_start[B] * H;
+    const int64_t S2 = sq[B];
+    WorkCursor cursor;
+    for (;;) {
+        const int64_t w = fetch_item(s.counter, cursor, total, &slot);
+        if (w < 0) break;
+        const Work t = decode_work(s, offsets, B, H, w);
+        const int L = t.len;
+        const int64_t blk = (int64_t)t.head * S2 + sq[t.sample];
+        const int i0 = t.block * kUfRows + wave * 32;
+        const int i1 = i0 + 32 < L ? i0 + 32 : L;
+        for (int i = i0; i < i1; ++i) {
+            const float *prow = probs + blk + (int64_t)i * L;
+            float *grow = dprobs + blk + (int64_t)i * L;
+            if (L <= 256 * 2 - 255) softmax_bwd_row_cached<2>(prow, grow, L, scale, lane);
+            else if (L <= 256 * 5 - 255) softmax_bwd_row_cached<5>(prow, grow, L, scale, lane);
+            else if (L <= 256 * 17 - 255) softmax_bwd_row_cached<17>(prow, grow, L, scale, lane);
+            else softmax_bwd_row_streamed(prow, grow, L, scale, lane);
+        }
+    }
+}
+
+// ---- transposed apply: out_j = sum_i X[i, j] x_i  (dV = P^T dO, dK = dS^T Q) ----
+// Computed as out^T = x^T X on blocks of 64 rows i.  A wave owns 32 output rows j.  With the slot order of the
+// transposing read that delivers x^T (row i of a 16-row step in slot order 4 half + e, 8 + 4 half + e), the
+// B operand of lane (col, half) is the column j = col of exactly those rows of X: each of its loads covers 32
+// consecutive j of one row (two rows per instruction), straight from memory into operand position.  x goes
+// through LDS as [i][feature], shared by the four waves; the next block is in flight during the products.
+template <int D>
+__global__ __launch_bounds__(kUfThreads) void unfused_apply_t_kernel(const float *__restrict__ X,
+                                                                     const __bf16 *__restrict__ x,
+                                                                     const int64_t *__restrict__ offsets,
+                                                                     const int64_t *__restrict__ sq, int B, int H,
+                                                                     Schedule s, __bf16 *__restrict__ out) {
+    constexpr int kDBlocks = D / 32, kChunks = D / 8;
+    constexpr int kRowBytes = D == 32 ? 64 : D * 2 + 64;
+    constexpr int kLoads = 64 * kChunks / kUfThreads;
+    __shared__ __attribute__((aligned(16))) char xt[64 * kRowBytes];
+    __shared__ int64_t slot;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = lane & 31, half = lane >> 5;
+    const int64_t total = (int64_t)s.tile_start[B] * H;
+    const int64_t row_stride = (int64_t)H * D;
+    const int64_t S2 = sq[B];
+    const int xoff = (half * 4 + ((lane & 15) >> 2)) * kRowBytes + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
+    WorkCursor cursor;
+    for (;;) {
+        const int64_t w = fetch_item(s.counter, cursor, total, &slot);
+        if (w < 0) break;
+        const Work t = decode_work(s, offsets, B, H, w);
+        const int L = t.len;
+        const int j = t.block * kUfRows + wave * 32 + col;   // this lane's output row
+        const bool wave_active = t.block * kUfRows + wave * 32 < L;
+        const bool j_ok = j < L;
+        const float *xcol = X + (int64_t)t.head * S2 + sq[t.sample] + (j_ok ? j : 0);   // X[i, j] = xcol[i * L]
+        const __bf16 *xbase = x + t.row0 * row_stride + (int64_t)t.head * D;
+        f32x16 o[kDBlocks];
+#pragma unroll
+        for (int db = 0; db < kDBlocks; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[db][e] = 0.0f;
+        u32x4 xpre[kLoads];
+        float cpre[32];   // slot e of step ks: row i0 + 16 ks + (e / 4) 8 + 4 half + e % 4
+        auto load_block = [&](int i0) {
+#pragma unroll
+            for (int u = 0; u < kLoads; ++u) {
+                const int c = tid + kUfThreads * u, r = c / kChunks, ch = c % kChunks;
+                const int ir = i0 + r < L ? i0 + r : L - 1;
+                xpre[u] = *reinterpret_cast<const u32x4 *>(xbase + (int64_t)ir * row_stride + ch * 8);
+            }
+            if (wave_active) {
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int i = i0 + 16 * ks + (e >> 2) * 8 + 4 * half + (e & 3);
+                        cpre[8 * ks + e] = (j_ok && i < L) ? xcol[(int64_t)i * L] : 0.0f;
+                    }
+            }
+        };
+        load_block(0);
+        for (int i0 = 0; i0 < L; i0 += 64) {
+            __syncthreads();   // the previous block of x has been consumed
+#pragma unroll
+            for (int u = 0; u < kLoads; ++u) {
+                const int c = tid + kUfThreads * u, r = c / kChunks, ch = c % kChunks;
+                *reinterpret_cast<u32x4 *>(xt + r * kRowBytes + ch * 16) = xpre[u];
+            }
+            bf16x8 cb[4];
+            if (wave_active) {
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) cb[ks][e] = (__bf16)cpre[8 * ks + e];
+            }
+            __syncthreads();
+            if (i0 + 64 < L) load_block(i0 + 64);
+            if (!wave_active) continue;
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {
+                if (i0 + ks * 16 >= L) break;
+#pragma unroll
+                for (int db = 0; db < kDBlocks; ++db) {
+                    const char *p = xt + ks * 16 * kRowBytes + xoff + db * 64;
+                    o[db] = mfma_32x32x16(concat(lds_read_tr16(p), lds_read_tr16(p + 8 * kRowBytes)), cb[ks], o[db]);
+                }
+            }
+        }
+        if (j_ok) {
+            __bf16 *orow = out + (t.row0 + j) * row_stride + (int64_t)t.head * D;
+#pragma unroll
+            for (int db = 0; db < kDBlocks; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x4 v;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) v[e] = (__bf16)o[db][4 * g + e];
+                    *reinterpret_cast<bf16x4 *>(orow + db * 32 + g * 8 + half * 4) = v;
+                }
+        }
+    }
+}
+
 hipError_t launch_square_offsets(const int64_t *offsets, int B, int64_t *sq, hipStream_t stream) {
     hipLaunchKernelGGL(square_offsets_kernel, dim3(1), dim3(1024), 0, stream, offsets, B, sq);
     return hipGetLastError();
 }
 
 hipError_t launch_unfused_scores(const void *q, const void *k, const int64_t *offsets, const int64_t *sq, int B, int H,
-                                 int D, Schedule s, float *scores, int cus, hipStream_t stream) {
+                                 int D, Schedule s, float scale, float *scores, int cus, hipStream_t stream) {
 #define JFA_CASE(DD)                                                                                                \
     case DD:                                                                                                        \
         hipLaunchKernelGGL(unfused_scores_kernel<DD>, dim3(persistent_grid<unfused_scores_kernel<DD>>(kUfThreads, cus)), \
-                           dim3(kUfThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, offsets, sq, B, H, s, scores); \
+                           dim3(kUfThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, offsets, sq, B, H, s, scale, scores); \
         break;
     switch (D) {
         JFA_CASE(32) JFA_CASE(64) JFA_CASE(128)
@@ -416,6 +593,28 @@ hipError_t launch_unfused_apply(const float *probs, const void *v, const int64_t
     case DD:                                                                                                       \
         hipLaunchKernelGGL(unfused_apply_kernel<DD>, dim3(persistent_grid<unfused_apply_kernel<DD>>(kUfThreads, cus)), \
                            dim3(kUfThreads), 0, stream, probs, (const __bf16 *)v, offsets, sq, B, H, s, (__bf16 *)out); \
+        break;
+    switch (D) {
+        JFA_CASE(32) JFA_CASE(64) JFA_CASE(128)
+        default: return hipErrorInvalidValue;
+    }
+#undef JFA_CASE
+    return hipGetLastError();
+}
+
+hipError_t launch_unfused_softmax_bwd(const float *probs, const int64_t *offsets, const int64_t *sq, int B, int H,
+                                      Schedule s, float scale, float *dprobs, int cus, hipStream_t stream) {
+    hipLaunchKernelGGL(unfused_softmax_bwd_kernel, dim3(persistent_grid<unfused_softmax_bwd_kernel>(kUfThreads, cus)),
+                       dim3(kUfThreads), 0, stream, probs, offsets, sq, B, H, s, scale, dprobs);
+    return hipGetLastError();
+}
+
+hipError_t launch_unfused_apply_t(const float *X, const void *x, const int64_t *offsets, const int64_t *sq, int B, int H,
+                                  int D, Schedule s, void *out, int cus, hipStream_t stream) {
+#define JFA_CASE(DD)                                                                                                   \
+    case DD:                                                                                                           \
+        hipLaunchKernelGGL(unfused_apply_t_kernel<DD>, dim3(persistent_grid<unfused_apply_t_kernel<DD>>(kUfThreads, cus)), \
+                           dim3(kUfThreads), 0, stream, X, (const __bf16 *)x, offsets, sq, B, H, s, (__bf16 *)out);     \
         break;
     switch (D) {
         JFA_CASE(32) JFA_CASE(64) JFA_CASE(128)

@@ -1,5 +1,5 @@
 #!/usr/bin/env python3
-"""Fused jagged flash attention versus the unfused jagged attention, forward, on the same GPU.
+"""Fused jagged flash attention versus the unfused jagged attention, forward and backward, on the same GPU.
 
     python -m paper_2409_15373_amd.unfused_compare [--workloads c2_geom_bf16,c3_zipf_bf16,...] [--reps N]
 
@@ -10,7 +10,9 @@ jfa_unfused_softmax -> jfa_unfused_apply).  For each workload it reports microse
 the three operators' own durations (HIP events inside the library) with the rate at which each moves the
 score array (4 bytes per score: written once by scores, read and written by softmax, read by apply), and the
 extra device memory either side needs beyond q, k, v and out (Section 3's memory claim): the fp32 score array
-for the unfused path, the fp32 log-sum-exp rows for the fused one.
+for the unfused path, the fp32 log-sum-exp rows for the fused one.  The backward is compared the same way:
+jfa_backward against product (dP), apply_transposed (dV), softmax_backward (dS), apply (dQ), apply_transposed (dK),
+which need a second array of that size.
 Inputs are random normals of the workload's scale drawn on the device.  Prints one JSON line.
 """
 import argparse
@@ -43,7 +45,7 @@ def main():
     from .synthetic import CONFIGS, lengths_for, offsets_from_lengths
     binding.load()
     assert torch.cuda.is_available(), "needs the GPU"
-    result = {"comparison": "fused jagged flash attention vs unfused jagged attention (scores, softmax, apply), forward",
+    result = {"comparison": "fused jagged flash attention vs unfused jagged attention (scores, softmax, apply and their backward operators)",
               "dtype": "bf16", "data": "synthetic", "workloads": {}}
     for name in args.workloads.split(","):
         c = CONFIGS[name]
@@ -69,8 +71,28 @@ def main():
             binding.jfa_unfused_softmax(off, sq, max_len, H, scores)
             binding.jfa_unfused_apply(scores, v, off, sq, max_len, out=out_u)
 
+        dout = mk(1.0)
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+        dq_u, dk_u, dv_u = torch.empty_like(q), torch.empty_like(q), torch.empty_like(q)
+        stats = torch.empty(2, H, n, device="cuda")
+        dscores = torch.empty_like(scores)
+        inv_sqrt_d = 1.0 / float(np.sqrt(D))
+
+        def fused_bwd():
+            binding.jfa_backward(q, k, v, out, dout, lse, off, max_len, dq=dq, dk=dk, dv=dv, delta=stats)
+
+        def unfused_bwd():   # `scores` holds the probabilities of the last unfused forward
+            binding.jfa_unfused_product(dout, v, off, sq, max_len, 1.0, dscores)
+            binding.jfa_unfused_apply_transposed(scores, dout, off, sq, max_len, out=dv_u)
+            binding.jfa_unfused_softmax_backward(scores, off, sq, max_len, H, inv_sqrt_d, dscores)
+            binding.jfa_unfused_apply(dscores, k, off, sq, max_len, out=dq_u)
+            binding.jfa_unfused_apply_transposed(dscores, q, off, sq, max_len, out=dk_u)
+
         t_f = _time(fused, args.reps)
         t_u = _time(unfused, args.reps)
+        t_fb = _time(fused_bwd, args.reps)
+        t_ub = _time(unfused_bwd, args.reps)
+        diff_b = max((a.float() - b.float()).abs().max().item() for a, b in ((dq, dq_u), (dk, dk_u), (dv, dv_u)))
         binding.jfa_timing_enable(True)
         binding.jfa_timing_read()
         for _ in range(args.reps):
@@ -88,15 +110,18 @@ def main():
         result["workloads"][name] = {
             "B": c["B"], "H": H, "D": D, "max_len": max_len, "rows": n, "score_pairs_per_head": pairs,
             "fused_us": round(t_f, 1), "unfused_us": round(t_u, 1), "speedup": round(t_u / t_f, 2),
+            "fused_bwd_us": round(t_fb, 1), "unfused_bwd_us": round(t_ub, 1), "speedup_bwd": round(t_ub / t_fb, 2),
+            "max_abs_difference_of_gradients": round(diff_b, 5),
             "operators": ops,
             "fused_extra_bytes": 4 * H * n, "unfused_extra_bytes": score_bytes,
             "qkvo_bytes": 4 * n * H * D * 2,
             "memory_saving": round(1.0 - (4 * n * H * D * 2 + 4 * H * n) / (4 * n * H * D * 2 + score_bytes), 3),
             "max_abs_difference_of_outputs": round(diff, 5),
         }
-        print(f"[unfused_compare] {name}: fused {t_f:.1f} us, unfused {t_u:.1f} us ({t_u / t_f:.2f}x), "
-              f"score array {score_bytes / 1e9:.2f} GB", file=sys.stderr, flush=True)
-        del scores, q, k, v, out, out_u, lse
+        print(f"[unfused_compare] {name}: forward fused {t_f:.1f} us, unfused {t_u:.1f} us ({t_u / t_f:.2f}x); backward "
+              f"fused {t_fb:.1f} us, unfused {t_ub:.1f} us ({t_ub / t_fb:.2f}x); score array {score_bytes / 1e9:.2f} GB",
+              file=sys.stderr, flush=True)
+        del scores, dscores, q, k, v, out, out_u, lse, dout, dq, dk, dv, dq_u, dk_u, dv_u
         torch.cuda.empty_cache()
     print(json.dumps(result))
 

@@ -117,3 +117,64 @@ def test_unfused_full_size_on_sampled_blocks():
         assert np.abs(p_gpu - p_ref).max() <= 2e-6, f"softmax of sample {b} head {h}"
         o_ref = unfused.apply(p_gpu, one(w.v, b, h), np.array([0, L]))
         gate_bf16(f"apply of sample {b} head {h}", f64(out[w.offsets[b]:w.offsets[b + 1], h:h + 1]), o_ref)
+
+
+@pytest.mark.parametrize("D,H,lengths", [(128, 2, [200, 1, 0, 77, 130, 33]), (64, 2, [5, 64, 129, 300]), (32, 1, [70, 2])])
+def test_unfused_backward_operators_match_the_oracle(D, H, lengths):
+    """dP = product(dout, v, 1); dS = softmax_backward(P, dP, 1/sqrt(D)) in place; dV = apply_transposed(P, dout);
+    dQ = apply(dS, k); dK = apply_transposed(dS, q): each against the oracle on the arrays the GPU really had."""
+    from paper_2409_15373_amd import binding
+    w = make_custom("unfused", lengths, H, D, "bf16", sigma=1.0, seed=13)
+    d = to_device(w, names=("q", "k", "v", "dout"), pad_rows=2)
+    sq = binding.jfa_square_offsets(d["offsets"])
+    sq_ref = unfused.square_offsets(w.offsets); S2 = int(sq_ref[-1]); n = w.sum_B
+    probs = torch.full((H * S2 + 5,), 777.0, dtype=torch.float32, device="cuda")
+    binding.jfa_unfused_scores(d["q"], d["k"], d["offsets"], sq, w.max_len, probs)
+    binding.jfa_unfused_softmax(d["offsets"], sq, w.max_len, H, probs)
+    dp = torch.full((H * S2 + 5,), 555.0, dtype=torch.float32, device="cuda")
+    binding.jfa_unfused_product(d["dout"], d["v"], d["offsets"], sq, w.max_len, 1.0, dp)
+    torch.cuda.synchronize()
+    P = f64(probs[:H * S2]).reshape(H, S2)
+    dP = f64(dp[:H * S2]).reshape(H, S2)
+    ref = unfused.product(w.dout, w.v, w.offsets, 1.0)
+    assert (np.abs(dP - ref) / np.maximum(1.0, np.abs(ref))).max() <= 1e-4
+    c = 1.0 / np.sqrt(D)
+    binding.jfa_unfused_softmax_backward(probs, d["offsets"], sq, w.max_len, H, c, dp)
+    torch.cuda.synchronize()
+    assert (dp[H * S2:] == 555.0).all() and (probs[H * S2:] == 777.0).all(), "elements past the arrays were written"
+    dS = f64(dp[:H * S2]).reshape(H, S2)
+    ref = unfused.softmax_rows_backward(P, dP, w.offsets, c)
+    assert np.abs(dS - ref).max() <= 1e-5 * max(1.0, np.abs(ref).max())
+    outs = {}
+    for name, arr, x in (("dv", probs, "dout"), ("dk", dp, "q")):
+        o = torch.full_like(d["q"], 333.0)
+        binding.jfa_unfused_apply_transposed(arr, d[x], d["offsets"], sq, w.max_len, out=o)
+        torch.cuda.synchronize()
+        assert (o[n:] == 333.0).all(), "guard rows were written"
+        outs[name] = f64(o[:n])
+    dq = binding.jfa_unfused_apply(dp, d["k"], d["offsets"], sq, w.max_len)
+    torch.cuda.synchronize()
+    gate_bf16("dV", outs["dv"], unfused.apply_transposed(P, w.dout, w.offsets), abs_tol=2e-2 * max(1.0, np.abs(outs["dv"]).max() / 4))
+    gate_bf16("dK", outs["dk"], unfused.apply_transposed(dS, w.q, w.offsets))
+    gate_bf16("dQ", f64(dq[:n]), unfused.apply(dS, w.k, w.offsets))
+
+
+def test_unfused_backward_chain_matches_the_fused_backward(oracle):
+    from paper_2409_15373_amd import binding
+    w = make_custom("unfused", [257, 64, 1, 500, 0, 40], 2, 128, "bf16", sigma=1.0, seed=14)
+    d = to_device(w, names=("q", "k", "v", "dout"))
+    H, D = w.H, w.D
+    sq = binding.jfa_square_offsets(d["offsets"])
+    S2 = int(unfused.square_offsets(w.offsets)[-1])
+    probs = torch.empty(H * S2, dtype=torch.float32, device="cuda"); dp = torch.empty_like(probs)
+    binding.jfa_unfused_scores(d["q"], d["k"], d["offsets"], sq, 512, probs)
+    binding.jfa_unfused_softmax(d["offsets"], sq, 512, H, probs)
+    binding.jfa_unfused_product(d["dout"], d["v"], d["offsets"], sq, 512, 1.0, dp)
+    dv = binding.jfa_unfused_apply_transposed(probs, d["dout"], d["offsets"], sq, 512)
+    binding.jfa_unfused_softmax_backward(probs, d["offsets"], sq, 512, H, 1.0 / np.sqrt(D), dp)
+    dq = binding.jfa_unfused_apply(dp, d["k"], d["offsets"], sq, 512)
+    dk = binding.jfa_unfused_apply_transposed(dp, d["q"], d["offsets"], sq, 512)
+    torch.cuda.synchronize()
+    r_dq, r_dk, r_dv, _ = oracle.backward(w.q, w.k, w.v, w.dout, w.offsets)
+    for name, g, r in (("dq", dq, r_dq), ("dk", dk, r_dk), ("dv", dv, r_dv)):
+        gate_bf16(name, f64(g), r, abs_tol=2e-2 * max(1.0, float(np.abs(r).max()) / 4))

@@ -87,6 +87,11 @@ def test_unfused_conversion_and_feature_operator_argument_errors(lib):
     assert lib.jfa_unfused_scores(None, None, None, None, 0, 8, 1, 64, None, None) == OK
     assert lib.jfa_unfused_softmax(None, None, 1, 8, 0, None, None) == BAD                  # H = 0
     assert lib.jfa_unfused_apply(None, None, None, None, -2, 8, 1, 64, None, None) == BAD
+    assert lib.jfa_unfused_product(None, None, None, None, 1, 8, 1, 64, 1.0, None, None) == BAD
+    assert lib.jfa_unfused_product(None, None, None, None, 1, 8, 1, 50, 1.0, None, None) == UNS
+    assert lib.jfa_unfused_softmax_backward(None, None, None, 1, 8, 2, 1.0, None, None) == BAD
+    assert lib.jfa_unfused_softmax_backward(None, None, None, 0, 8, 2, 1.0, None, None) == OK
+    assert lib.jfa_unfused_apply_transposed(16, 16, 16, 16, 1, 8, 1, 64, 8, None) == BAD     # out misaligned
     # conversions: row_bytes must be a positive multiple of 16; null and misaligned tensors are refused
     assert lib.jfa_jagged_to_dense(16, 16, 2, 8, 24, 0, 16, None) == UNS
     assert "multiple of 16" in binding.jfa_last_error()
