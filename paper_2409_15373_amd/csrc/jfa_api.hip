@@ -285,15 +285,17 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
         if (e != hipSuccess) return hip_fail("fp32 backward kernels", e);
         return JFA_OK;
     }
-    { ScopedTimer tm("delta", s); e = jfa::launch_delta(out, dout, lse, offsets, (int)B, H, D, true, delta, w.cus, s); }
-    if (e != hipSuccess) return hip_fail("delta kernel", e);
+    if (!dma) {   // the direct-to-LDS dQ kernel computes the row statistics itself
+        { ScopedTimer tm("delta", s); e = jfa::launch_delta(out, dout, lse, offsets, (int)B, H, D, true, delta, w.cus, s); }
+        if (e != hipSuccess) return hip_fail("delta kernel", e);
+    }
     if (dma) {
         static const char *const names[3] = {"dq_bf16_dma", "dk_bf16_dma", "dv_bf16_dma"};
         void *const grads[3] = {dq, dk, dv};
         for (int mode = 0; mode < 3; ++mode) {
             const int which = mode == 0 ? 0 : kv;
             jfa::Schedule sc{w.order[which], w.tile_start[which], w.counters + mode * jfa::kXcds};
-            { ScopedTimer tm(names[mode], s); e = jfa::launch_bwd_bf16_dma(mode, q, k, v, dout, lse, delta, mode == 0 ? offsets : offsets_k, mode == 0 ? offsets_kv : offsets_q_other, causal, (int)B, H, D, sc, grads[mode], w.cus, s); }
+            { ScopedTimer tm(names[mode], s); e = jfa::launch_bwd_bf16_dma(mode, q, k, v, out, dout, lse, delta, mode == 0 ? offsets : offsets_k, mode == 0 ? offsets_kv : offsets_q_other, causal, (int)B, H, D, sc, grads[mode], w.cus, s); }
             if (e != hipSuccess) return hip_fail(names[mode], e);
         }
         return JFA_OK;

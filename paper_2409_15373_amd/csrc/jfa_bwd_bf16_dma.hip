@@ -59,7 +59,8 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                                                                      const __bf16 *__restrict__ v,
                                                                      const __bf16 *__restrict__ dout,
                                                                      const float *__restrict__ lse,
-                                                                     const float *__restrict__ delta,
+                                                                     const __bf16 *__restrict__ out_fwd,   // dQ only; see below
+                                                                     float *delta,
                                                                      const int64_t *__restrict__ offsets,
                                                                      const int64_t *__restrict__ offsets_other, int B, int H,
                                                                      Schedule s, __bf16 *__restrict__ grad) {
@@ -131,6 +132,10 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                 __bf16 *grow = grad + (t.row0 + i) * row_stride + (int64_t)t.head * D + (lane >> 5) * (D / 2);
 #pragma unroll
                 for (int e = 0; e < D / 2; e += 8) *reinterpret_cast<u32x4 *>(grow + e) = u32x4{0, 0, 0, 0};
+                if (!kRowStats && out_fwd != nullptr && lane < 32) {   // out = 0 there: delta = 0; lse = -inf
+                    delta[(int64_t)t.head * sum_B + t.row0 + i] = 0.0f;
+                    delta[(int64_t)(H + t.head) * sum_B + t.row0 + i] = INFINITY;
+                }
             }
             continue;
         }
@@ -197,12 +202,6 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                 for (int e = 0; e < 4; ++e) w[e] ^= 0x80008000u;
                 yreg[ks] = __builtin_bit_cast(bf16x8, w);
             }
-        }
-        if (!kRowStats) {   // written and read by the same lane: no barrier needed
-            const float nl = lse2_rows[ic], nd = -delta_rows[ic];
-            float4 *mine = lane_init + wave * 128 + lane;                               // consecutive lanes, consecutive
-            mine[0] = make_float4(nl, nl, nl, nl);                                      // 16-byte slots: no bank conflicts
-            mine[64] = make_float4(nd, nd, nd, nd);
         }
         f32x16 acc[kDBlocks];
 #pragma unroll
@@ -352,6 +351,36 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             asm volatile("" : "+v"(xreg[ks]));   // stationary-row loads complete here
             if (kSecond) asm volatile("" : "+v"(yreg[ks]));
         }
+        if (!kRowStats) {
+            // This lane's query's statistics: minus the base-2 lse and minus delta = rowsum(dO o O).  With out_fwd given,
+            // this kernel is the first of the backward and computes them itself from the rows it holds (each lane of
+            // a pair has half of the row), leaving both planes of the statistics buffer for the dK and dV kernels;
+            // otherwise an earlier kernel has filled the buffer.
+            float nl, nd;
+            if (out_fwd != nullptr) {
+                const int64_t off = (t.row0 + ic) * row_stride + (int64_t)t.head * D + 8 * half;
+                float dot = 0.0f;
+#pragma unroll
+                for (int ks = 0; ks < kKSteps; ++ks) {
+                    const bf16x8 o = *reinterpret_cast<const bf16x8 *>(out_fwd + off + 16 * ks);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) dot = fmaf((float)o[e], (float)yreg[ks][e], dot);
+                }
+                dot = pair_sum(dot);
+                nl = -lse[(int64_t)t.head * sum_B + t.row0 + ic] * 1.4426950408889634f;
+                nd = -dot;
+                if (i < Ls && half == 0) {
+                    delta[(int64_t)t.head * sum_B + t.row0 + i] = dot;
+                    delta[(int64_t)(H + t.head) * sum_B + t.row0 + i] = nl;
+                }
+            } else {
+                nl = lse2_rows[ic];
+                nd = -delta_rows[ic];
+            }
+            float4 *mine = lane_init + wave * 128 + lane;   // consecutive lanes, consecutive 16-byte slots: no bank
+            mine[0] = make_float4(nl, nl, nl, nl);          // conflicts; written and read by the same lane: no barrier
+            mine[64] = make_float4(nd, nd, nd, nd);
+        }
         // The softmax scale and the change to base-2 exponentials go into the stationary operand of the score
         // product once per tile (x * log2(e) / sqrt(D), rounded to bf16 again): scores then only need v_exp_f32.
 #pragma unroll
@@ -421,14 +450,14 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
 }
 
 template <int MODE>
-static hipError_t launch_mode(const void *q, const void *k, const void *v, const void *dout, const float *lse,
-                              const float *delta, const int64_t *offsets, const int64_t *offsets_other, bool causal, int B,
+static hipError_t launch_mode(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
+                              float *delta, const int64_t *offsets, const int64_t *offsets_other, bool causal, int B,
                               int H, Schedule s, void *grad, int cus, hipStream_t stream) {
     if (causal && offsets_other) return hipErrorInvalidValue;
 #define JFA_LAUNCH(CROSS, CAUSAL)                                                                                           \
     hipLaunchKernelGGL((bwd_bf16_dma_kernel<MODE, CROSS, CAUSAL>), dim3(persistent_grid<bwd_bf16_dma_kernel<MODE, CROSS, CAUSAL>>(kBdThreads, cus)), \
                        dim3(kBdThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,                \
-                       (const __bf16 *)dout, lse, delta, offsets, offsets_other, B, H, s, (__bf16 *)grad)
+                       (const __bf16 *)dout, lse, (const __bf16 *)out, delta, offsets, offsets_other, B, H, s, (__bf16 *)grad)
     if (offsets_other) JFA_LAUNCH(true, false);
     else if (causal) JFA_LAUNCH(false, true);
     else JFA_LAUNCH(false, false);
@@ -436,15 +465,15 @@ static hipError_t launch_mode(const void *q, const void *k, const void *v, const
     return hipGetLastError();
 }
 
-hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const void *v, const void *dout,
-                               const float *lse, const float *delta, const int64_t *offsets,
+hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const void *v, const void *out, const void *dout,
+                               const float *lse, float *delta, const int64_t *offsets,
                                const int64_t *offsets_other, bool causal, int B, int H, int D, Schedule s, void *grad,
                                int cus, hipStream_t stream) {
     if (D != kBdD) return hipErrorInvalidValue;
     switch (mode) {
-        case kModeDQ: return launch_mode<kModeDQ>(q, k, v, dout, lse, delta, offsets, offsets_other, causal, B, H, s, grad, cus, stream);
-        case kModeDK: return launch_mode<kModeDK>(q, k, v, dout, lse, delta, offsets, offsets_other, causal, B, H, s, grad, cus, stream);
-        case kModeDV: return launch_mode<kModeDV>(q, k, v, dout, lse, delta, offsets, offsets_other, causal, B, H, s, grad, cus, stream);
+        case kModeDQ: return launch_mode<kModeDQ>(q, k, v, out, dout, lse, delta, offsets, offsets_other, causal, B, H, s, grad, cus, stream);
+        case kModeDK: return launch_mode<kModeDK>(q, k, v, nullptr, dout, lse, delta, offsets, offsets_other, causal, B, H, s, grad, cus, stream);
+        case kModeDV: return launch_mode<kModeDV>(q, k, v, nullptr, dout, lse, delta, offsets, offsets_other, causal, B, H, s, grad, cus, stream);
         default: return hipErrorInvalidValue;
     }
 }
