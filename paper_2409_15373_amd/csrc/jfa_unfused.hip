@@ -3,12 +3,15 @@
 //   scores   jagged x jagged product with a jagged square output:  S[h, sq[b] + i L_b + j] = q_i . k_j / sqrt(D)
 //   softmax  row softmax over each sample's L_b x L_b block of that array (in place)
 //   apply    (jagged square array) x jagged product:                out_i = sum_j P[h, sq[b] + i L_b + j] v_j
+// and the operators their gradients need (Section 2.2 builds forward and backward): the same product with a free
+// scale (dP = dO V^T), the softmax's backward, and the transposed apply (dV = P^T dO, dK = dS^T Q).
 // sq = [0, cumsum(L_b^2)] is the offsets array of the jagged square array (square_offsets_kernel).  The score
 // array is fp32 [H, sq[B]]; q, k, v, out are bf16 [sum_B, H, D] as everywhere else.
 //
-// These are deliberately plain kernels on the same building blocks as the fused path (one wave = 32 queries,
-// transposed score tile on v_mfma_f32_32x32x16_bf16, transposing LDS reads for V): what they measure is the
-// cost of moving sum L_b^2 scores through HBM three times, which is the point of the comparison.
+// All of them are bound by HBM: what they measure is the cost of moving sum L_b^2 scores through memory several
+// times, which is the point of the comparison.  They share the fused path's building blocks (one wave = 32 rows,
+// v_mfma_f32_32x32x16_bf16, transposing LDS reads) but are organised around the score array: a key index sits on
+// the lane axis wherever the array is touched, and stores cover whole 128-byte lines.
 #include "jfa_common.h"
 #include "jfa_mfma.h"
 
@@ -47,17 +50,17 @@ __global__ __launch_bounds__(1024) void square_offsets_kernel(const int64_t *__r
 // All three operators keep a key index on the lane axis wherever they touch the score array: one wave-wide access
 // covers 64 (or 2 x 32) consecutive keys of a row, so every load and store of the array is coalesced.
 
-// ---- scores: S = Q K^T / sqrt(D) ----
+// ---- scores: S = scale * Q K^T (scale = 1 / sqrt(D) for the scores, 1 for dP = dO V^T) ----
 // A workgroup takes 128 queries of one (sample, head); wave w holds queries 32 w .. 32 w + 31 as the A operand
 // in registers for the whole item.  K streams through LDS in blocks of 64 keys shared by the four waves (rows padded
 // by 16 bytes: the 16-byte operand reads of consecutive key rows fall into different banks); the block after the
 // current one is already on its way into registers while the current one is multiplied.
 template <int D>
 __global__ __launch_bounds__(kUfThreads, 2) void unfused_scores_kernel(const __bf16 *__restrict__ q,
-                                                                    const __bf16 *__restrict__ k,
-                                                                    const int64_t *__restrict__ offsets,
-                                                                    const int64_t *__restrict__ sq, int B, int H,
-                                                                    Schedule s, float scale, float *__restrict__ scores) {
+                                                                       const __bf16 *__restrict__ k,
+                                                                       const int64_t *__restrict__ offsets,
+                                                                       const int64_t *__restrict__ sq, int B, int H,
+                                                                       Schedule s, float scale, float *__restrict__ scores) {
     constexpr int kKSteps = D / 16, kChunks = D / 8, kRowBytes = D * 2 + 16;
     constexpr int kLoads = 64 * kChunks / kUfThreads;   // 16-byte chunks of a K block per thread
     __shared__ __attribute__((aligned(16))) char kt[64 * kRowBytes];
