@@ -115,20 +115,27 @@ struct Work {
     int olen;
 };
 
-// Largest p in [0, B) with tile_start[p] * H <= w, for w < tile_start[B] * H.
-__device__ inline int find_position(const int32_t *tile_start, int B, int H, int64_t w) {
+// Largest p in [0, B) with tile_start[p] * H <= w, found by one wave: 64 probes per round instead of one.
+__device__ inline int find_position_wave(const int32_t *tile_start, int B, int H, int64_t w) {
+    const int lane = threadIdx.x & 63;
     int lo = 0, hi = B;  // invariant: tile_start[lo]*H <= w < tile_start[hi]*H
     while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if ((int64_t)tile_start[mid] * H <= w) lo = mid; else hi = mid;
+        const int step = (hi - lo + 63) / 64;
+        const int idx = lo + (lane + 1) * step;
+        const bool ok = idx < hi && (int64_t)tile_start[idx] * H <= w;   // true for a prefix of the lanes
+        const int cnt = __popcll(__builtin_amdgcn_ballot_w64(ok));
+        lo += cnt * step;
+        hi = hi < lo + step ? hi : lo + step;
     }
     return lo;
 }
 
+// Work item w -> (sample, head, row block).  Called by whole waves (each wave searches for itself, 64 probes per
+// round: two or three dependent loads instead of log2(B)).
 __device__ inline Work decode_work(const Schedule &s, const int64_t *offsets, int B, int H, int64_t w,
                                    const int64_t *offsets_other = nullptr) {
     Work t;
-    const int p = find_position(s.tile_start, B, H, w);
+    const int p = find_position_wave(s.tile_start, B, H, w);   // every lane of the calling wave must be active
     const int t0 = s.tile_start[p];
     const int n = s.tile_start[p + 1] - t0;
     const int r = (int)(w - (int64_t)t0 * H);
@@ -167,21 +174,6 @@ struct WorkSlot {
     int row0_lo, row0_hi;
     int olen, orow0_lo, orow0_hi;   // the other side's rows (cross attention only)
 };
-
-// Largest p in [0, B) with tile_start[p] * H <= w, found by one wave: 64 probes per round instead of one.
-__device__ inline int find_position_wave(const int32_t *tile_start, int B, int H, int64_t w) {
-    const int lane = threadIdx.x & 63;
-    int lo = 0, hi = B;  // invariant: tile_start[lo]*H <= w < tile_start[hi]*H
-    while (hi - lo > 1) {
-        const int step = (hi - lo + 63) / 64;
-        const int idx = lo + (lane + 1) * step;
-        const bool ok = idx < hi && (int64_t)tile_start[idx] * H <= w;   // true for a prefix of the lanes
-        const int cnt = __popcll(__builtin_amdgcn_ballot_w64(ok));
-        lo += cnt * step;
-        hi = hi < lo + step ? hi : lo + step;
-    }
-    return lo;
-}
 
 // Claim the next work item and decode it into `slot`.  Called by every lane of ONE wave (the claim itself is
 // made by its lane 0, whose registers hold `cur`); meant to be issued right after a tile's first loads so
