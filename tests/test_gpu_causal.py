@@ -78,3 +78,26 @@ def test_causal_first_row_returns_v_and_later_rows_ignore_the_future():
         assert torch.equal(out[s].view(torch.int16), d["v"][s].view(torch.int16))
     assert torch.equal(out[:100].view(torch.int16), out2[:100].view(torch.int16)) and torch.equal(lse[:, :100], lse2[:, :100])
     assert not torch.equal(out[100:150].view(torch.int16), out2[100:150].view(torch.int16))
+
+
+def test_causal_stale_reference_maximum_takes_the_conservative_pass():
+    """Direct-to-LDS forward: the first 40 keys score 0 and the later ones ~724, so the fixed reference maximum (first
+    32 keys) is far too low for every query past row 40: the tile is redone maximum-first, with the causal mask."""
+    from paper_2409_15373_amd import binding
+    from paper_2409_15373_amd.synthetic import round_to_bf16_bits
+    lengths = [300, 500, 40]
+    w = make_custom("stale", lengths, 1, 128, dtype="bf16", seed=12, dout=False, max_len=512)
+    q = np.full_like(w.q, 8.0)
+    k = np.zeros_like(w.k)
+    for b, L in enumerate(lengths):
+        s0 = int(w.offsets[b])
+        k[s0 + 40: s0 + L] = 8.0
+    w.q, w.k = q, k
+    w.bits["q"], w.bits["k"] = round_to_bf16_bits(q), round_to_bf16_bits(k)
+    d = to_device(w, names=("q", "k", "v"))
+    out, lse = binding.jfa_forward(d["q"], d["k"], d["v"], d["offsets"], 512, causal=True)
+    torch.cuda.synchronize()
+    r_out, r_lse = causal.forward(w.q, w.k, w.v, w.offsets)
+    assert np.isfinite(f64(out)).all() and np.isfinite(f64(lse)).all()
+    gate_bf16("out", f64(out), r_out)
+    gate_bf16("lse", f64(lse), r_lse, abs_tol=2e-2 * max(1.0, np.abs(r_lse).max() / 4))

@@ -124,3 +124,27 @@ def test_cross_with_equal_offsets_is_self_attention_bit_for_bit(max_len):
     torch.cuda.synchronize()
     for a, b in zip(gs[:3], gx[:3]):
         assert torch.equal(a[:n].view(torch.int16), b[:n].view(torch.int16))
+
+
+def test_cross_stale_reference_maximum_takes_the_conservative_pass():
+    """Direct-to-LDS forward with separate lengths: the first 40 keys of a sample score 0 and the later ones ~724, far
+    above the fixed reference maximum of the first 32 keys: the tile is redone maximum-first."""
+    from paper_2409_15373_amd import binding
+    Lq, Lk = [300, 70, 10], [500, 300, 40]
+    host, dev, oq, ok = make(Lq, Lk, 1, 128, "bf16", 9)
+    q = np.full_like(host["q"], 8.0)
+    k = np.zeros_like(host["k"])
+    for b in range(3):
+        k[ok[b] + 40: ok[b + 1]] = 8.0
+    guard = torch.full((GUARD, 1, 128), float("nan"), dtype=torch.bfloat16)
+    qd = torch.cat([torch.from_numpy(round_to_bf16_bits(q).view(np.int16)).view(torch.bfloat16), guard]).cuda()
+    kd = torch.cat([torch.from_numpy(round_to_bf16_bits(k).view(np.int16)).view(torch.bfloat16), guard]).cuda()
+    nq = int(oq[-1])
+    lse = torch.empty((1, nq), dtype=torch.float32, device="cuda")
+    out, _ = binding.jfa_forward_cross(qd, kd, dev["v"], torch.from_numpy(oq).cuda(), torch.from_numpy(ok).cuda(), 512, 512, lse=lse)
+    torch.cuda.synchronize()
+    out = out[:nq]
+    r_out, r_lse = cross.forward(q, k, host["v"], oq, ok)
+    assert np.isfinite(f64(out)).all() and np.isfinite(f64(lse)).all()
+    gate_bf16("out", f64(out), r_out)
+    gate_bf16("lse", f64(lse), r_lse, abs_tol=2e-2 * max(1.0, np.abs(r_lse).max() / 4))
