@@ -86,6 +86,23 @@ __device__ inline int64_t next_work(int32_t *counters, WorkCursor &cur, int64_t 
     }
 }
 
+// The same claim in two parts, for kernels that hide the atomic's latency behind a tile's work: claim_issue() sends the
+// home queue's atomic add and returns its result without using it (-1: this claim takes no such atomic -- small
+// problem, first item, or home queue already empty); claim_finish() turns it into a work id, going on to the other
+// queues as next_work() does.  Both are called by the same single thread.
+__device__ inline int claim_issue(int32_t *counters, const WorkCursor &cur, int64_t total) {
+    if (total <= 4 * (int64_t)gridDim.x || cur.first || cur.home_done) return -1;
+    return atomicAdd(&counters[blockIdx.x % kXcds], 1);
+}
+__device__ inline int64_t claim_finish(int32_t *counters, WorkCursor &cur, int64_t total, int ticket) {
+    if (ticket >= 0) {
+        const int64_t id = work_id(blockIdx.x % kXcds, gridDim.x / kXcds + ticket);
+        if (id < total) return id;
+        cur.home_done = true;
+    }
+    return next_work(counters, cur, total);
+}
+
 // The work id is the same for every lane; saying so lets the tile parameters derived from it live in scalar
 // registers and be fetched with scalar loads.
 __device__ inline int64_t uniform64(int64_t x) {
@@ -175,6 +192,9 @@ struct WorkSlot {
     int olen, orow0_lo, orow0_hi;   // the other side's rows (cross attention only)
 };
 
+__device__ inline void decode_into_slot(WorkSlot *slot, const Schedule &s, const int64_t *offsets, int B, int H, int64_t w,
+                                        const int64_t *offsets_other);
+
 // Claim the next work item and decode it into `slot`.  Called by every lane of ONE wave (the claim itself is
 // made by its lane 0, whose registers hold `cur`); meant to be issued right after a tile's first loads so
 // that its latency chain (atomic, search, offsets) overlaps with theirs.
@@ -183,7 +203,13 @@ __device__ inline void claim_and_decode(WorkSlot *slot, const Schedule &s, const
     const int lane = threadIdx.x & 63;
     int64_t w = -1;
     if (lane == 0) w = next_work(s.counter, cur, total);
-    w = uniform64(w);
+    decode_into_slot(slot, s, offsets, B, H, uniform64(w), offsets_other);
+}
+
+// Decode work id w (the same in every lane; < 0: nothing left) into `slot`.  Called by every lane of one wave.
+__device__ inline void decode_into_slot(WorkSlot *slot, const Schedule &s, const int64_t *offsets, int B, int H, int64_t w,
+                                        const int64_t *offsets_other) {
+    const int lane = threadIdx.x & 63;
     if (w < 0) {
         if (lane == 0) slot->valid = 0;
         return;

@@ -26,6 +26,7 @@ constexpr int kDmaBN = 64;            // keys per LDS stage
 constexpr int kDmaD = 128;
 constexpr int kDmaTile = kDmaBN * kDmaD * 2;   // bytes of one K or V stage in LDS
 constexpr int kDmaOpsPerStage = 2 * (kDmaBN / 4) / kDmaWaves;   // DMA instructions per wave per stage (K and V)
+constexpr int kDmaTabCap = 1024;      // samples whose schedule entries a workgroup keeps in LDS
 
 template <int N> using IntC = std::integral_constant<int, N>;
 
@@ -61,8 +62,13 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
     __shared__ __attribute__((aligned(1024))) char V0[kDmaTile];
     __shared__ __attribute__((aligned(1024))) char V1[kDmaTile];
     __shared__ __attribute__((aligned(1024))) char V2[kDmaTile];
-    __shared__ WorkSlot slot;   // the NEXT work item, claimed and decoded while the current one starts up
+    __shared__ WorkSlot slot;   // the NEXT work item, decoded by wave 0 at the end of the current one's stages
     __shared__ int restart;   // set by a wave whose reference maximum went stale beyond repair
+    // The schedule, copied into LDS once per workgroup when it fits (position p of the sorted order: first tile, sample,
+    // rows): decoding a claimed work id then costs a few LDS reads instead of a chain of dependent global loads.
+    __shared__ int32_t tab_start[kDmaTabCap + 1];
+    __shared__ int32_t tab_sample[kDmaTabCap], tab_len[kDmaTabCap], tab_row0[kDmaTabCap][2];
+    __shared__ int32_t tab_olen[CROSS ? kDmaTabCap : 1], tab_orow0[CROSS ? kDmaTabCap : 1][2];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, half = lane >> 5;
@@ -101,22 +107,109 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
     const int dma_row0 = 8 * wave + (lane >> 4);
     const int pc = lane & 15;
 
+    // byte offsets of this lane's DMA chunks inside a full stage (K and V differ in the swizzle)
+    uint32_t koffs[2], voffs[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int r = dma_row0 + 4 * u;
+        koffs[u] = 2u * (uint32_t)(r * (int)row_stride + ((pc ^ (r & 15)) << 3));
+        voffs[u] = 2u * (uint32_t)(r * (int)row_stride + ((pc ^ ((r & 3) << 2)) << 3));
+    }
+    // The keys a tile streams: first rows of K and V, number of keys of the sample, number of 64-key stages.
+    struct Stream {
+        const __bf16 *kbase, *vbase;
+        int L, n_stages;
+    };
+    auto stream_of = [&](const Work &w) {
+        Stream st;
+        st.L = CROSS ? w.olen : w.len;
+        const int64_t krow0 = CROSS ? w.orow0 : w.row0;
+        const int w_tile0 = w.block * kDmaBlockRows;
+        const int Lc = CAUSAL && w_tile0 + kDmaBlockRows < st.L ? w_tile0 + kDmaBlockRows : st.L;   // keys the tile needs
+        st.n_stages = (Lc + kDmaBN - 1) / kDmaBN;
+        st.kbase = k + krow0 * row_stride + (int64_t)w.head * D;
+        st.vbase = v + krow0 * row_stride + (int64_t)w.head * D;
+        return st;
+    };
+    bf16x8 qreg[kKSteps];
+    auto load_q = [&](const Work &w) {   // the lane's query row (rows past the end of the sample repeat its last row)
+        const int iw = w.block * kDmaBlockRows + wave * 32 + col;
+        const __bf16 *qrow = q + (w.row0 + (iw < w.len ? iw : w.len - 1)) * row_stride + (int64_t)w.head * D + 8 * half;
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * ks);
+    };
+    // Work id -> slot, by wave 0: from the LDS copy of the schedule when there is one.
+    const bool tabled = B <= kDmaTabCap;
+    auto decode_next = [&](int64_t w) {
+        if (!tabled) {
+            decode_into_slot(&slot, s, offsets, B, H, w, CROSS ? offsets_kv : nullptr);
+            return;
+        }
+        if (w < 0) {
+            if (lane == 0) slot.valid = 0;
+            return;
+        }
+        int lo = 0, hi = B;   // invariant: tab_start[lo] * H <= w < tab_start[hi] * H
+        while (hi - lo > 1) {
+            const int step = (hi - lo + 63) / 64;
+            const int idx = lo + (lane + 1) * step;
+            const bool ok = idx < hi && (int64_t)tab_start[idx] * H <= w;   // true for a prefix of the lanes
+            const int cnt = __popcll(__builtin_amdgcn_ballot_w64(ok));
+            lo += cnt * step;
+            hi = hi < lo + step ? hi : lo + step;
+        }
+        if (lane == 0) {
+            const int t0 = tab_start[lo];
+            const int n = tab_start[lo + 1] - t0;
+            const int r = (int)(w - (int64_t)t0 * H);
+            slot.valid = 1;
+            slot.sample = tab_sample[lo];
+            slot.head = r / n;
+            slot.block = r - (r / n) * n;
+            slot.len = tab_len[lo];
+            slot.row0_lo = tab_row0[lo][0];
+            slot.row0_hi = tab_row0[lo][1];
+            if (CROSS) {
+                slot.olen = tab_olen[lo];
+                slot.orow0_lo = tab_orow0[lo][0];
+                slot.orow0_hi = tab_orow0[lo][1];
+            }
+        }
+    };
+
     WorkCursor cursor;
     if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_kv : nullptr);
-    for (;;) {
-        __syncthreads();   // the slot is written; the previous tile is finished
-        Work t;
-        if (!load_work<CROSS>(&slot, t)) break;
-        __syncthreads();   // every wave has read the slot before wave 0 refills it
+    if (tabled) {
+        for (int p = tid; p <= B; p += kDmaThreads) tab_start[p] = s.tile_start[p];
+        for (int p = tid; p < B; p += kDmaThreads) {
+            const int sample = s.order[p];
+            const int64_t r0 = offsets[sample];
+            tab_sample[p] = sample;
+            tab_len[p] = (int)(offsets[sample + 1] - r0);
+            tab_row0[p][0] = (int)(uint32_t)r0;
+            tab_row0[p][1] = (int)(uint32_t)((uint64_t)r0 >> 32);
+            if (CROSS) {
+                const int64_t o0 = offsets_kv[sample];
+                tab_olen[p] = (int)(offsets_kv[sample + 1] - o0);
+                tab_orow0[p][0] = (int)(uint32_t)o0;
+                tab_orow0[p][1] = (int)(uint32_t)((uint64_t)o0 >> 32);
+            }
+        }
+    }
+    __syncthreads();   // the slot and the tables are written
+    Work t;
+    bool have = load_work<CROSS>(&slot, t);
+    bool pre = false;   // the query rows and the first two stages of t are already on their way
+    while (have) {
+        const Stream cur = stream_of(t);
         const int Lq = t.len;                      // queries of the sample
-        const int L = CROSS ? t.olen : t.len;      // keys of the sample
-        const int64_t krow0 = CROSS ? t.orow0 : t.row0;
+        const int L = cur.L;                       // keys of the sample
         const int q_tile0 = t.block * kDmaBlockRows;   // first query of the tile
-        const int Lc = CAUSAL && q_tile0 + kDmaBlockRows < L ? q_tile0 + kDmaBlockRows : L;   // keys this tile needs
-        const int n_stages = (Lc + kDmaBN - 1) / kDmaBN;
-        const __bf16 *kbase = k + krow0 * row_stride + (int64_t)t.head * D;
-        const __bf16 *vbase = v + krow0 * row_stride + (int64_t)t.head * D;
+        const int n_stages = cur.n_stages;
+        const __bf16 *const kbase = cur.kbase;
+        const __bf16 *const vbase = cur.vbase;
         if (CROSS && L == 0) {   // no keys: an empty softmax, out = 0 and lse = -inf
+            __syncthreads();   // every wave has read the slot
             if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, offsets_kv);
             const int i = t.block * kDmaBlockRows + wave * 32 + (lane & 31);
             if (i < Lq) {
@@ -125,18 +218,14 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
                 for (int e = 0; e < D / 2; e += 8) *reinterpret_cast<u32x4 *>(orow + e) = u32x4{0, 0, 0, 0};
                 if (lane < 32) lse[(int64_t)t.head * sum_B + t.row0 + i] = -INFINITY;
             }
+            __syncthreads();   // the slot is written
+            have = load_work<CROSS>(&slot, t);
+            pre = false;
             continue;
         }
 
-        // byte offsets of this lane's DMA chunks inside a full stage (K and V differ in the swizzle)
-        uint32_t koffs[2], voffs[2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int r = dma_row0 + 4 * u;
-            koffs[u] = 2u * (uint32_t)(r * (int)row_stride + ((pc ^ (r & 15)) << 3));
-            voffs[u] = 2u * (uint32_t)(r * (int)row_stride + ((pc ^ ((r & 3) << 2)) << 3));
-        }
-        auto issue = [&](const __bf16 *base, char *tile, int stage, bool is_k) {
+        auto issue_from = [&](const Stream &st, const __bf16 *base, char *tile, int stage, bool is_k) {
+            const int L = st.L;
             const int j0 = stage * kDmaBN;
             const __bf16 *sbase = base + (int64_t)j0 * row_stride;
             if (j0 + kDmaBN <= L) {
@@ -152,16 +241,11 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
                 }
             }
         };
+        auto issue = [&](const __bf16 *base, char *tile, int stage, bool is_k) { issue_from(cur, base, tile, stage, is_k); };
 
         const int i = t.block * kDmaBlockRows + wave * 32 + col;   // this lane's query
         const int iq = i < Lq ? i : Lq - 1;
         const bool wave_active = t.block * kDmaBlockRows + wave * 32 < Lq;
-        bf16x8 qreg[kKSteps];
-        {
-            const __bf16 *qrow = q + (t.row0 + iq) * row_stride + (int64_t)t.head * D + 8 * half;
-#pragma unroll
-            for (int ks = 0; ks < kKSteps; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * ks);
-        }
 
         f32x16 o[kDBlocks];
 #pragma unroll
@@ -313,10 +397,11 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             asm volatile("" ::: "memory");
         };
 
-        if (tid == 0) restart = 0;
-        issue_stage(IntC<0>{}, 0);
-        if (n_stages > 1) issue_stage(IntC<1>{}, 1);
-        if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_kv : nullptr);   // overlaps with the loads in flight
+        if (!pre) {   // first tile of the workgroup: nothing was sent ahead
+            load_q(t);
+            issue_stage(IntC<0>{}, 0);
+            if (n_stages > 1) issue_stage(IntC<1>{}, 1);
+        }
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qreg[ks]));   // Q loads complete here
         // The softmax scale and the change to base-2 exponentials go into Q once per tile (q * log2(e) / sqrt(D),
@@ -325,8 +410,17 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         for (int ks = 0; ks < kKSteps; ++ks)
 #pragma unroll
             for (int e = 0; e < 8; ++e) qreg[ks][e] = (__bf16)((float)qreg[ks][e] * c);
+        // Stage 0 has landed once at most one stage's loads are outstanding: what this wave sent after it is stage 1
+        // and, when the tile was sent ahead, the previous tile's output stores.
         if (n_stages > 1) __builtin_amdgcn_s_waitcnt(0x0070 | kDmaOpsPerStage); else __builtin_amdgcn_s_waitcnt(0x0070);
         __syncthreads();
+        // The claim of the next work item: its atomic travels while the stages run; nobody looks at `restart` between
+        // the previous tile's check and this barrier.
+        int ticket = -1;
+        if (tid == 0) {
+            restart = 0;
+            ticket = claim_issue(s.counter, cursor, total);
+        }
         if (wave_active) {   // reference maximum: the first 32 keys
             f32x16 s0;
             scores(K0, 0, s0);
@@ -355,14 +449,18 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
                 else run_stage(IntC<2>{}, IntC<1>{}, j);
             }
         }
+        if (wave == 0) {   // the next work item, decoded into the slot (a few LDS reads when the schedule is in LDS)
+            int64_t w = -1;
+            if (lane == 0) w = claim_finish(s.counter, cursor, total, ticket);
+            decode_next(uniform64(w));
+        }
         // a row sum this large (or not finite) means the fixed reference was too far below the true maximum
         if (wave_active && __builtin_amdgcn_ballot_w64(!(lsum < 0x1p62f)) != 0 && lane == 0) restart = 1;
-        __syncthreads();
+        __syncthreads();   // the slot and `restart` are written
         const bool again = restart != 0;
 
         // ---- pass 2 (never on data of one scale): the whole tile again, maximum first, two buffers ----
         if (again) {
-            __syncthreads();   // every wave has seen `restart` before the next tile clears it
             issue(kbase, K0, 0, true);
             issue(vbase, V0, 0, false);
             __builtin_amdgcn_s_waitcnt(0x0070);
@@ -384,41 +482,66 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             }
         }
 
-        // ---- epilogue: normalise; transpose the wave's 32 x 128 output block through LDS so that it leaves as
-        // whole 256-byte rows (16 bytes per lane, four rows per store instruction) instead of 8-byte pieces of 32
-        // different rows per instruction; store the log-sum-exp ----
-        // The stage buffers are idle here (every wave is past the last stage's barrier and no DMA is in flight);
-        // wave w uses 8 KB of them: row r of its block at r * 256, 16-byte chunk ch at (ch ^ (r & 15)) << 4.
+        // ---- the next tile: its query rows and first two stages start now and travel during the epilogue ----
+        Work nt;
+        const bool have_next = load_work<CROSS>(&slot, nt);
+        bool pre_next = false;
+        if (have_next) {
+            const Stream ns = stream_of(nt);
+            if (!CROSS || ns.L > 0) {
+                load_q(nt);
+                issue_from(ns, ns.kbase, K0, 0, true);
+                issue_from(ns, ns.vbase, V0, 0, false);
+                if (ns.n_stages > 1) {
+                    issue_from(ns, ns.kbase, K1, 1, true);
+                    issue_from(ns, ns.vbase, V1, 1, false);
+                }
+                pre_next = true;
+            }
+        }
+
+        // ---- epilogue: normalise; transpose the wave's 32 x 128 output block through LDS, 64 features at a time, so
+        // that it leaves as whole 128-byte pieces of rows (16 bytes per lane, eight rows per store instruction) instead
+        // of 8-byte pieces of 32 different rows per instruction; store the log-sum-exp ----
+        // The third stage buffer is idle here (every wave is past the last stage's barrier, and the next tile's third
+        // stage is only sent after that tile's first barrier); wave w uses 4 KB of it: row r of its block at r * 128,
+        // 16-byte chunk ch at (ch ^ (r & 7)) << 4.
         const float l_total = pair_sum(lsum);
         {
-            char *const region = (wave < 2 ? K0 : (wave < 4 ? K1 : (wave < 6 ? K2 : V0))) + (wave & 1) * 8192;
+            char *const region = (wave < 4 ? K2 : V2) + (wave & 3) * 4096;
             const float inv = 1.0f / l_total;
             int lane_e = lane;   // every address below derives from this copy, which the compiler cannot see
             asm volatile("" : "+v"(lane_e));   // through: otherwise they are computed at tile start and spilled
             const int col_e = lane_e & 31, half_e = lane_e >> 5;
-            const int wbase = col_e * 256 + ((half_e * 8) ^ ((col_e & 15) << 4));
-#pragma unroll
-            for (int db = 0; db < kDBlocks; ++db)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    bf16x4 x;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) x[e] = (__bf16)(o[db][4 * g + e] * inv);
-                    *reinterpret_cast<bf16x4 *>(region + (wbase ^ (db * 64 + g * 16))) = x;
-                }
+            const int wbase = col_e * 128 + ((half_e * 8) ^ ((col_e & 7) << 4));
             const int q0 = t.block * kDmaBlockRows + wave * 32;   // first query of this wave
             __bf16 *const obase = out + (t.row0 + q0) * row_stride + (int64_t)t.head * D;
-            const uint32_t lane_off = 2u * (uint32_t)((lane_e >> 4) * (int)row_stride + (lane_e & 15) * 8);
+            const uint32_t lane_off = 2u * (uint32_t)((lane_e >> 3) * (int)row_stride + (lane_e & 7) * 8);
 #pragma unroll
-            for (int it = 0; it < 8; ++it) {
-                const int r = it * 4 + (lane_e >> 4);
-                const u32x4 rowpiece = *reinterpret_cast<const u32x4 *>(region + r * 256 + (((lane_e & 15) ^ (r & 15)) << 4));
-                char *dst = reinterpret_cast<char *>(obase + (int64_t)it * 4 * row_stride) + lane_off;   // scalar base + 32-bit lane offset
-                if (q0 + r < Lq) *reinterpret_cast<u32x4 *>(dst) = rowpiece;
+            for (int f = 0; f < 2; ++f) {   // features 64 f .. 64 f + 63
+#pragma unroll
+                for (int dl = 0; dl < 2; ++dl)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        bf16x4 x;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) x[e] = (__bf16)(o[2 * f + dl][4 * g + e] * inv);
+                        *reinterpret_cast<bf16x4 *>(region + (wbase ^ (dl * 64 + g * 16))) = x;
+                    }
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int r = it * 8 + (lane_e >> 3);
+                    const u32x4 rowpiece = *reinterpret_cast<const u32x4 *>(region + r * 128 + (((lane_e & 7) ^ (r & 7)) << 4));
+                    char *dst = reinterpret_cast<char *>(obase + (int64_t)it * 8 * row_stride + 64 * f) + lane_off;   // scalar base + 32-bit lane offset
+                    if (q0 + r < Lq) *reinterpret_cast<u32x4 *>(dst) = rowpiece;
+                }
             }
         }
         if (i < Lq && half == 0)
             lse[(int64_t)t.head * sum_B + t.row0 + i] = (m + fast_log2(l_total)) * 0.6931471805599453f;
+        t = nt;
+        have = have_next;
+        pre = pre_next;
     }
 }
 
