@@ -85,7 +85,8 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
     // and dP accumulators of every block start from these (four 16-byte LDS reads each, no VALU work, no registers
     // held across the stage): P = exp2(acc) and dS = P * acc then cost one exponential and one multiply.
     __shared__ float4 lane_init[MODE == kModeDQ ? kBdThreads * 2 : 1];
-    __shared__ WorkSlot slot;   // the NEXT work item, claimed and decoded while the current one starts up
+    __shared__ WorkSlot slot;   // the NEXT work item, decoded by wave 0 at the end of the current one's stages
+    __shared__ LdsSchedule<CROSS> tab;   // the schedule, copied once per workgroup when it fits
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, half = lane >> 5;
@@ -109,23 +110,101 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             for (int db = 0; db < kDBlocks; ++db)
                 taddr[h2][db] = (r + 8 * h2) * 256 + (((db * 4 + chunk_in_group) ^ swz(r + 8 * h2)) << 4) + byte_in_chunk;
     }
+    // What streams past a tile: first rows of the two streamed tensors and of the streamed rows' statistics, number of
+    // streamed rows of the sample, first stage and number of stages (causal tiles need only a part of the sample).
+    struct Stream {
+        const __bf16 *abase, *bbase;
+        const float *delta_rows, *lse2_rows;   // plane 0 of the statistics buffer: delta; plane 1: -lse * log2(e)
+        int L, Lc, js, n_stages;
+    };
+    auto stream_of = [&](const Work &w) {
+        Stream st;
+        st.L = CROSS ? w.olen : w.len;
+        const int64_t srow0 = CROSS ? w.orow0 : w.row0;
+        const int w_tile0 = w.block * kDmaBlockRows;   // first stationary row of the tile
+        // causal: the streamed rows a tile needs are keys 0 .. (tile's last query) for dQ, queries (tile's first key) .. L - 1 for dK, dV
+        st.Lc = CAUSAL && !kRowStats && w_tile0 + kDmaBlockRows < st.L ? w_tile0 + kDmaBlockRows : st.L;
+        st.js = CAUSAL && kRowStats ? w_tile0 / kBdBN : 0;
+        st.n_stages = (st.Lc + kBdBN - 1) / kBdBN;
+        const int64_t head_off = srow0 * row_stride + (int64_t)w.head * D;
+        st.abase = (MODE == kModeDQ ? k : q) + head_off;
+        st.bbase = (MODE == kModeDQ ? v : dout) + head_off;
+        const int64_t qrow0 = kRowStats ? srow0 : w.row0;   // first query row of the sample
+        st.delta_rows = delta + (int64_t)w.head * sum_B + qrow0;
+        st.lse2_rows = delta + (int64_t)(H + w.head) * sum_B + qrow0;
+        return st;
+    };
+    // The per-lane byte offsets of the two DMA chunks of a stage are rebuilt from the thread id at every
+    // issue (a handful of VALU operations per stage) instead of living in registers across the stage: values
+    // used once per stage are the first the register allocator spills, and a reload from scratch memory
+    // would wait on the vector-memory counter, i.e. on the very loads that are meant to stay in flight.
+    auto issue_from = [&](const Stream &st, const __bf16 *base, char *tile, int stage) {
+        const int L = st.L;
+        const int j0 = stage * kBdBN;
+        const __bf16 *sbase = base + (int64_t)j0 * row_stride;
+        int t_opaque = tid;
+        asm volatile("" : "+v"(t_opaque));
+        const int dma_row0 = 8 * wave + ((t_opaque >> 4) & 3);
+        const int pc = t_opaque & 15;
+        if (j0 + kBdBN <= L) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int r = dma_row0 + 4 * u;
+                bd_dma16(sbase, 2u * (uint32_t)(r * (int)row_stride + ((pc ^ swz(r)) << 3)), tile + (8 * wave + 4 * u) * 256);
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int r = dma_row0 + 4 * u;
+                const int jr = j0 + r < L ? r : L - 1 - j0;   // rows past the end repeat the last row (masked later)
+                bd_dma16(sbase, 2u * (uint32_t)(jr * (int)row_stride + ((pc ^ swz(r)) << 3)), tile + (8 * wave + 4 * u) * 256);
+            }
+        }
+    };
+    auto issue_stats_from = [&](const Stream &st, char *stats, int stage) {   // wave 0 only: lse and delta of the 64 streamed rows
+        const int j0 = stage * kBdBN;
+        const uint32_t j = 4u * (uint32_t)(j0 + lane < st.L ? j0 + lane : st.L - 1);
+        bd_dma4(st.lse2_rows, j, stats);
+        if (kSecond) bd_dma4(st.delta_rows, j, stats + 256);
+    };
+    auto issue_stage_from = [&](const Stream &st, auto BUF, int j) {
+        constexpr int Bf = decltype(BUF)::value;
+        issue_from(st, st.abase, Bf == 0 ? A0 : (Bf == 1 ? A1 : A2), j);
+        issue_from(st, st.bbase, Bf == 0 ? B0 : (Bf == 1 ? B1 : B2), j);
+        if (kRowStats && wave == 0) issue_stats_from(st, Bf == 0 ? S0 : (Bf == 1 ? S1 : S2), j);
+    };
+    // ---- stationary rows: this lane's row as B operands (rows past the end of the sample repeat its last row) ----
+    bf16x8 xreg[kKSteps], yreg[kKSteps];   // dQ: Q, dO rows   dK: K, V rows   dV: K rows
+    auto load_stationary = [&](const Work &w) {
+        const int iw = w.block * kDmaBlockRows + wave * 32 + col;
+        const int64_t off = (w.row0 + (iw < w.len ? iw : w.len - 1)) * row_stride + (int64_t)w.head * D + 8 * half;
+        const __bf16 *xsrc = MODE == kModeDQ ? q : k;
+        const __bf16 *ysrc = MODE == kModeDQ ? dout : v;
+#pragma unroll
+        for (int ks = 0; ks < kKSteps; ++ks) {
+            xreg[ks] = *reinterpret_cast<const bf16x8 *>(xsrc + off + 16 * ks);
+            if (kSecond) yreg[ks] = *reinterpret_cast<const bf16x8 *>(ysrc + off + 16 * ks);
+        }
+    };
+    const bool tabled = B <= kTabCap;
+
     WorkCursor cursor;
     if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_other : nullptr);
-    for (;;) {
-        __syncthreads();   // the slot is written; the previous tile is finished
-        Work t;
-        if (!load_work<CROSS>(&slot, t)) break;
-        __syncthreads();   // every wave has read the slot before wave 0 refills it
+    if (tabled) tab.fill(s, offsets, offsets_other, B);
+    __syncthreads();   // the slot and the tables are written
+    Work t;
+    bool have = load_work<CROSS>(&slot, t);
+    bool pre = false;   // the stationary rows and the first two stages of t are already on their way
+    while (have) {
+        const Stream cur = stream_of(t);
         const int Ls = t.len;                      // stationary rows of the sample
-        const int L = CROSS ? t.olen : t.len;      // streamed rows of the sample
-        const int64_t srow0 = CROSS ? t.orow0 : t.row0;
+        const int L = cur.L;                       // streamed rows of the sample
         const int tile0 = t.block * kDmaBlockRows;   // first stationary row of the tile
-        // causal: the streamed rows a tile needs are keys 0 .. (tile's last query) for dQ, queries (tile's first key) .. L - 1 for dK, dV
-        const int Lc = CAUSAL && !kRowStats && tile0 + kDmaBlockRows < L ? tile0 + kDmaBlockRows : L;
-        const int js = CAUSAL && kRowStats ? tile0 / kBdBN : 0;   // first stage of the stream
-        const int n_stages = (Lc + kBdBN - 1) / kBdBN;
-        const int64_t head_off = srow0 * row_stride + (int64_t)t.head * D;
+        const int Lc = cur.Lc;
+        const int js = cur.js;                     // first stage of the stream
+        const int n_stages = cur.n_stages;
         if (CROSS && L == 0) {   // nothing streams past these rows: their gradient is zero
+            __syncthreads();   // every wave has read the slot
             if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, offsets_other);
             const int i = t.block * kDmaBlockRows + wave * 32 + (lane & 31);
             if (i < Ls) {
@@ -137,71 +216,21 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                     delta[(int64_t)(H + t.head) * sum_B + t.row0 + i] = INFINITY;
                 }
             }
+            __syncthreads();   // the slot is written
+            have = load_work<CROSS>(&slot, t);
+            pre = false;
             continue;
         }
-        const __bf16 *abase = (MODE == kModeDQ ? k : q) + head_off;
-        const __bf16 *bbase = (MODE == kModeDQ ? v : dout) + head_off;
-        // plane 0 of the statistics buffer: delta; plane 1: -lse * log2(e), written by the delta kernel
-        const int64_t qrow0 = kRowStats ? srow0 : t.row0;   // first query row of the sample
-        const float *delta_rows = delta + (int64_t)t.head * sum_B + qrow0;
-        const float *lse2_rows = delta + (int64_t)(H + t.head) * sum_B + qrow0;
+        const float *const delta_rows = cur.delta_rows;
+        const float *const lse2_rows = cur.lse2_rows;
 
-        // The per-lane byte offsets of the two DMA chunks of a stage are rebuilt from the thread id at every
-        // issue (a handful of VALU operations per stage) instead of living in registers across the stage: values
-        // used once per stage are the first the register allocator spills, and a reload from scratch memory
-        // would wait on the vector-memory counter, i.e. on the very loads that are meant to stay in flight.
-        auto issue = [&](const __bf16 *base, char *tile, int stage) {
-            const int j0 = stage * kBdBN;
-            const __bf16 *sbase = base + (int64_t)j0 * row_stride;
-            int t_opaque = tid;
-            asm volatile("" : "+v"(t_opaque));
-            const int dma_row0 = 8 * wave + ((t_opaque >> 4) & 3);
-            const int pc = t_opaque & 15;
-            if (j0 + kBdBN <= L) {
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const int r = dma_row0 + 4 * u;
-                    bd_dma16(sbase, 2u * (uint32_t)(r * (int)row_stride + ((pc ^ swz(r)) << 3)), tile + (8 * wave + 4 * u) * 256);
-                }
-            } else {
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const int r = dma_row0 + 4 * u;
-                    const int jr = j0 + r < L ? r : L - 1 - j0;   // rows past the end repeat the last row (masked later)
-                    bd_dma16(sbase, 2u * (uint32_t)(jr * (int)row_stride + ((pc ^ swz(r)) << 3)), tile + (8 * wave + 4 * u) * 256);
-                }
-            }
-        };
-        auto issue_stats = [&](char *stats, int stage) {   // wave 0 only: lse and delta of the 64 streamed rows
-            const int j0 = stage * kBdBN;
-            const uint32_t j = 4u * (uint32_t)(j0 + lane < L ? j0 + lane : L - 1);
-            bd_dma4(lse2_rows, j, stats);
-            if (kSecond) bd_dma4(delta_rows, j, stats + 256);
-        };
-
-        // ---- stationary rows: this lane's row as B operands ----
         const int i = t.block * kDmaBlockRows + wave * 32 + col;
         const int ic = i < Ls ? i : Ls - 1;
         const bool wave_active = t.block * kDmaBlockRows + wave * 32 < Ls;
-        bf16x8 xreg[kKSteps], yreg[kKSteps];   // dQ: Q, dO rows   dK: K, V rows   dV: K rows
-        {
-            const int64_t off = (t.row0 + ic) * row_stride + (int64_t)t.head * D + 8 * half;
-            const __bf16 *xsrc = MODE == kModeDQ ? q : k;
-            const __bf16 *ysrc = MODE == kModeDQ ? dout : v;
-#pragma unroll
-            for (int ks = 0; ks < kKSteps; ++ks) {
-                xreg[ks] = *reinterpret_cast<const bf16x8 *>(xsrc + off + 16 * ks);
-                if (kSecond) yreg[ks] = *reinterpret_cast<const bf16x8 *>(ysrc + off + 16 * ks);
-            }
-        }
-        if (MODE == kModeDK) {   // V enters negated: the dP accumulator starts at delta and ends as delta - dP
-#pragma unroll
-            for (int ks = 0; ks < kKSteps; ++ks) {
-                u32x4 w = __builtin_bit_cast(u32x4, yreg[ks]);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] ^= 0x80008000u;
-                yreg[ks] = __builtin_bit_cast(bf16x8, w);
-            }
+        if (!pre) {   // first tile of the workgroup: nothing was sent ahead
+            load_stationary(t);
+            issue_stage_from(cur, IntB<0>{}, js);
+            if (n_stages - js > 1) issue_stage_from(cur, IntB<1>{}, js + 1);
         }
         f32x16 acc[kDBlocks];
 #pragma unroll
@@ -310,12 +339,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                 for (int db = 0; db < kDBlocks; ++db) acc[db] = mfma_32x32x16(top[db], pb, acc[db]);
             }
         };
-        auto issue_stage = [&](auto BUF, int j) {
-            constexpr int Bf = decltype(BUF)::value;
-            issue(abase, Bf == 0 ? A0 : (Bf == 1 ? A1 : A2), j);
-            issue(bbase, Bf == 0 ? B0 : (Bf == 1 ? B1 : B2), j);
-            if (kRowStats && wave == 0) issue_stats(Bf == 0 ? S0 : (Bf == 1 ? S1 : S2), j);
-        };
+        auto issue_stage = [&](auto BUF, int j) { issue_stage_from(cur, BUF, j); };
         // DMA operations per wave per stage: 4 tile chunks, plus the row statistics on wave 0
         auto wait_one_stage_outstanding = [&]() {
             if (kRowStats && wave == 0) {
@@ -343,13 +367,19 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             asm volatile("" ::: "memory");
         };
 
-        issue_stage(IntB<0>{}, js);
-        if (n_stages - js > 1) issue_stage(IntB<1>{}, js + 1);
-        if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_other : nullptr);   // overlaps with the loads in flight
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) {
             asm volatile("" : "+v"(xreg[ks]));   // stationary-row loads complete here
             if (kSecond) asm volatile("" : "+v"(yreg[ks]));
+        }
+        if (MODE == kModeDK) {   // V enters negated: the dP accumulator starts at delta and ends as delta - dP
+#pragma unroll
+            for (int ks = 0; ks < kKSteps; ++ks) {
+                u32x4 w = __builtin_bit_cast(u32x4, yreg[ks]);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] ^= 0x80008000u;
+                yreg[ks] = __builtin_bit_cast(bf16x8, w);
+            }
         }
         if (!kRowStats) {
             // This lane's query's statistics: minus the base-2 lse and minus delta = rowsum(dO o O).  With out_fwd given,
@@ -387,8 +417,12 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         for (int ks = 0; ks < kKSteps; ++ks)
 #pragma unroll
             for (int e = 0; e < 8; ++e) xreg[ks][e] = (__bf16)((float)xreg[ks][e] * c);
+        // The first stage has landed once at most one stage's loads are outstanding: what this wave sent after it is
+        // the second stage and, when the tile was sent ahead, the previous tile's gradient stores.
         if (n_stages - js > 1) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);
         __syncthreads();
+        int ticket = -1;   // the claim of the next work item: its atomic travels while the stages run
+        if (tid == 0) ticket = claim_issue(s.counter, cursor, total);
         if (CAUSAL) {   // stage j lives in buffer (j - js) % 3; which stages mask depends on the side of the diagonal
             for (int j = js; j < n_stages; ++j) {
                 const bool masking = kRowStats ? (j < js + kDmaBlockRows / kBdBN || (j + 1) * kBdBN > L)
@@ -416,36 +450,66 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             }
         }
 
-        // ---- epilogue: scale, transpose the wave's 32 x 128 gradient block through LDS (the stage buffers are
-        // idle: every wave is past the last stage's barrier, no DMA in flight) and store whole 256-byte rows,
-        // four per store instruction.  Row r of the block sits at r * 256, 16-byte chunk ch at (ch ^ (r & 15)) << 4.
+        if (wave == 0) {   // the next work item, decoded into the slot (a few LDS reads when the schedule is in LDS)
+            int64_t w = -1;
+            if (lane == 0) w = claim_finish(s.counter, cursor, total, ticket);
+            w = uniform64(w);
+            if (tabled) tab.decode(&slot, B, H, w);
+            else decode_into_slot(&slot, s, offsets, B, H, w, CROSS ? offsets_other : nullptr);
+        }
+        __syncthreads();   // the slot is written
+
+        // ---- the next tile: its stationary rows and first two stages start now and travel during the epilogue ----
+        Work nt;
+        const bool have_next = load_work<CROSS>(&slot, nt);
+        bool pre_next = false;
+        if (have_next) {
+            const Stream ns = stream_of(nt);
+            if (!CROSS || ns.L > 0) {
+                load_stationary(nt);
+                issue_stage_from(ns, IntB<0>{}, ns.js);
+                if (ns.n_stages - ns.js > 1) issue_stage_from(ns, IntB<1>{}, ns.js + 1);
+                pre_next = true;
+            }
+        }
+
+        // ---- epilogue: scale, transpose the wave's 32 x 128 gradient block through LDS, 64 features at a time, and store
+        // whole 128-byte pieces of rows, eight rows per store instruction.  The third pair of stage buffers is idle (every
+        // wave is past the last stage's barrier, and the next tile's third stage is only sent after that tile's first
+        // barrier); wave w uses 4 KB of it: row r of its block at r * 128, 16-byte chunk ch at (ch ^ (r & 7)) << 4.
         {
-            char *const region = (wave < 2 ? A0 : (wave < 4 ? A1 : (wave < 6 ? A2 : B0))) + (wave & 1) * 8192;
+            char *const region = (wave < 4 ? A2 : B2) + (wave & 3) * 4096;
             const float out_scale = MODE == kModeDV ? 1.0f : (MODE == kModeDK ? -scale : scale);
             int lane_e = lane;   // every address below derives from this copy, which the compiler cannot see
             asm volatile("" : "+v"(lane_e));   // through: otherwise they are computed at tile start and spilled
             const int col_e = lane_e & 31, half_e = lane_e >> 5;
-            const int wbase = col_e * 256 + ((half_e * 8) ^ ((col_e & 15) << 4));
-#pragma unroll
-            for (int db = 0; db < kDBlocks; ++db)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    bf16x4 x;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) x[e] = (__bf16)(acc[db][4 * g + e] * out_scale);
-                    *reinterpret_cast<bf16x4 *>(region + (wbase ^ (db * 64 + g * 16))) = x;
-                }
+            const int wbase = col_e * 128 + ((half_e * 8) ^ ((col_e & 7) << 4));
             const int r0 = t.block * kDmaBlockRows + wave * 32;   // first stationary row of this wave
             __bf16 *const gbase = grad + (t.row0 + r0) * row_stride + (int64_t)t.head * D;
-            const uint32_t lane_off = 2u * (uint32_t)((lane_e >> 4) * (int)row_stride + (lane_e & 15) * 8);
+            const uint32_t lane_off = 2u * (uint32_t)((lane_e >> 3) * (int)row_stride + (lane_e & 7) * 8);
 #pragma unroll
-            for (int it = 0; it < 8; ++it) {
-                const int r = it * 4 + (lane_e >> 4);
-                const u32x4 rowpiece = *reinterpret_cast<const u32x4 *>(region + r * 256 + (((lane_e & 15) ^ (r & 15)) << 4));
-                char *dst = reinterpret_cast<char *>(gbase + (int64_t)it * 4 * row_stride) + lane_off;
-                if (r0 + r < Ls) *reinterpret_cast<u32x4 *>(dst) = rowpiece;
+            for (int f = 0; f < 2; ++f) {   // features 64 f .. 64 f + 63
+#pragma unroll
+                for (int dl = 0; dl < 2; ++dl)
+#pragma unroll
+                    for (int g = 0; g < 4; ++g) {
+                        bf16x4 x;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) x[e] = (__bf16)(acc[2 * f + dl][4 * g + e] * out_scale);
+                        *reinterpret_cast<bf16x4 *>(region + (wbase ^ (dl * 64 + g * 16))) = x;
+                    }
+#pragma unroll
+                for (int it = 0; it < 4; ++it) {
+                    const int r = it * 8 + (lane_e >> 3);
+                    const u32x4 rowpiece = *reinterpret_cast<const u32x4 *>(region + r * 128 + (((lane_e & 7) ^ (r & 7)) << 4));
+                    char *dst = reinterpret_cast<char *>(gbase + (int64_t)it * 8 * row_stride + 64 * f) + lane_off;
+                    if (r0 + r < Ls) *reinterpret_cast<u32x4 *>(dst) = rowpiece;
+                }
             }
         }
+        t = nt;
+        have = have_next;
+        pre = pre_next;
     }
 }
 

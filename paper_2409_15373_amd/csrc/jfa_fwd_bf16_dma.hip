@@ -26,7 +26,6 @@ constexpr int kDmaBN = 64;            // keys per LDS stage
 constexpr int kDmaD = 128;
 constexpr int kDmaTile = kDmaBN * kDmaD * 2;   // bytes of one K or V stage in LDS
 constexpr int kDmaOpsPerStage = 2 * (kDmaBN / 4) / kDmaWaves;   // DMA instructions per wave per stage (K and V)
-constexpr int kDmaTabCap = 1024;      // samples whose schedule entries a workgroup keeps in LDS
 
 template <int N> using IntC = std::integral_constant<int, N>;
 
@@ -64,11 +63,7 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
     __shared__ __attribute__((aligned(1024))) char V2[kDmaTile];
     __shared__ WorkSlot slot;   // the NEXT work item, decoded by wave 0 at the end of the current one's stages
     __shared__ int restart;   // set by a wave whose reference maximum went stale beyond repair
-    // The schedule, copied into LDS once per workgroup when it fits (position p of the sorted order: first tile, sample,
-    // rows): decoding a claimed work id then costs a few LDS reads instead of a chain of dependent global loads.
-    __shared__ int32_t tab_start[kDmaTabCap + 1];
-    __shared__ int32_t tab_sample[kDmaTabCap], tab_len[kDmaTabCap], tab_row0[kDmaTabCap][2];
-    __shared__ int32_t tab_olen[CROSS ? kDmaTabCap : 1], tab_orow0[CROSS ? kDmaTabCap : 1][2];
+    __shared__ LdsSchedule<CROSS> tab;   // the schedule, copied once per workgroup when it fits
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, half = lane >> 5;
@@ -139,63 +134,15 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         for (int ks = 0; ks < kKSteps; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * ks);
     };
     // Work id -> slot, by wave 0: from the LDS copy of the schedule when there is one.
-    const bool tabled = B <= kDmaTabCap;
+    const bool tabled = B <= kTabCap;
     auto decode_next = [&](int64_t w) {
-        if (!tabled) {
-            decode_into_slot(&slot, s, offsets, B, H, w, CROSS ? offsets_kv : nullptr);
-            return;
-        }
-        if (w < 0) {
-            if (lane == 0) slot.valid = 0;
-            return;
-        }
-        int lo = 0, hi = B;   // invariant: tab_start[lo] * H <= w < tab_start[hi] * H
-        while (hi - lo > 1) {
-            const int step = (hi - lo + 63) / 64;
-            const int idx = lo + (lane + 1) * step;
-            const bool ok = idx < hi && (int64_t)tab_start[idx] * H <= w;   // true for a prefix of the lanes
-            const int cnt = __popcll(__builtin_amdgcn_ballot_w64(ok));
-            lo += cnt * step;
-            hi = hi < lo + step ? hi : lo + step;
-        }
-        if (lane == 0) {
-            const int t0 = tab_start[lo];
-            const int n = tab_start[lo + 1] - t0;
-            const int r = (int)(w - (int64_t)t0 * H);
-            slot.valid = 1;
-            slot.sample = tab_sample[lo];
-            slot.head = r / n;
-            slot.block = r - (r / n) * n;
-            slot.len = tab_len[lo];
-            slot.row0_lo = tab_row0[lo][0];
-            slot.row0_hi = tab_row0[lo][1];
-            if (CROSS) {
-                slot.olen = tab_olen[lo];
-                slot.orow0_lo = tab_orow0[lo][0];
-                slot.orow0_hi = tab_orow0[lo][1];
-            }
-        }
+        if (tabled) tab.decode(&slot, B, H, w);
+        else decode_into_slot(&slot, s, offsets, B, H, w, CROSS ? offsets_kv : nullptr);
     };
 
     WorkCursor cursor;
     if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_kv : nullptr);
-    if (tabled) {
-        for (int p = tid; p <= B; p += kDmaThreads) tab_start[p] = s.tile_start[p];
-        for (int p = tid; p < B; p += kDmaThreads) {
-            const int sample = s.order[p];
-            const int64_t r0 = offsets[sample];
-            tab_sample[p] = sample;
-            tab_len[p] = (int)(offsets[sample + 1] - r0);
-            tab_row0[p][0] = (int)(uint32_t)r0;
-            tab_row0[p][1] = (int)(uint32_t)((uint64_t)r0 >> 32);
-            if (CROSS) {
-                const int64_t o0 = offsets_kv[sample];
-                tab_olen[p] = (int)(offsets_kv[sample + 1] - o0);
-                tab_orow0[p][0] = (int)(uint32_t)o0;
-                tab_orow0[p][1] = (int)(uint32_t)((uint64_t)o0 >> 32);
-            }
-        }
-    }
+    if (tabled) tab.fill(s, offsets, offsets_kv, B);
     __syncthreads();   // the slot and the tables are written
     Work t;
     bool have = load_work<CROSS>(&slot, t);
