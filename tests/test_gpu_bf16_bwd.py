@@ -90,3 +90,40 @@ def test_backward_is_deterministic():
     b = gpu_forward_backward(w)
     for x, y in zip(a, b):
         assert torch.equal(x, y)
+
+
+@pytest.mark.parametrize("is_causal", [False, True])
+def test_more_samples_than_the_lds_schedule_holds(oracle, is_causal):
+    """The direct-to-LDS kernels keep the schedule of up to 1024 samples in LDS and decode claimed work ids from global
+    memory beyond that: 1300 short samples (some empty) and three long ones, with enough work items for dynamic claims."""
+    from oracle import causal
+    from paper_2409_15373_amd import binding
+    rng = np.random.default_rng(31)
+    lengths = rng.integers(0, 49, size=1300)
+    lengths[[7, 650, 1299]] = [300, 520, 257]
+    w = make_custom("many", lengths, 2, 128, dtype="bf16", seed=32, max_len=600)
+    d = to_device(w, pad_rows=2)
+    n = w.sum_B
+    out = torch.full_like(d["q"], 777.0)
+    lse = torch.full((w.H, n), 777.0, dtype=torch.float32, device="cuda")
+    binding.jfa_forward(d["q"], d["k"], d["v"], d["offsets"], 600, out=out, lse=lse, causal=is_causal)
+    g = {x: torch.full_like(d["q"], 777.0) for x in ("dq", "dk", "dv")}
+    delta = torch.full((2, w.H, n), 777.0, dtype=torch.float32, device="cuda")
+    binding.jfa_backward(d["q"], d["k"], d["v"], out, d["dout"], lse, d["offsets"], 600,
+                         dq=g["dq"], dk=g["dk"], dv=g["dv"], delta=delta, causal=is_causal)
+    torch.cuda.synchronize()
+    assert (out[n:] == 777.0).all() and all((t[n:] == 777.0).all() for t in g.values()), "guard rows were written"
+    if is_causal:
+        r_out, r_lse = causal.forward(w.q, w.k, w.v, w.offsets)
+        rdq, rdk, rdv, _ = causal.backward(w.q, w.k, w.v, w.dout, w.offsets)
+    else:
+        r_out, r_lse = oracle.forward(w.q, w.k, w.v, w.offsets)
+        rdq, rdk, rdv, _ = oracle.backward(w.q, w.k, w.v, w.dout, w.offsets)
+    # gradients of short, peaked samples reach several units: the absolute gate follows the tensor's scale (bf16 rounding
+    # of a value x alone is |x| / 512), the relative gate is unchanged
+    scaled = lambda r: 2e-2 * max(1.0, float(np.abs(r).max()) / 2)
+    gate_bf16("out", f64(out[:n]), r_out)
+    gate_bf16("lse", f64(lse), r_lse)
+    gate_bf16("dq", f64(g["dq"][:n]), rdq, abs_tol=scaled(rdq))
+    gate_bf16("dk", f64(g["dk"][:n]), rdk, abs_tol=scaled(rdk))
+    gate_bf16("dv", f64(g["dv"][:n]), rdv, abs_tol=scaled(rdv))
