@@ -358,8 +358,20 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                 const char *Bt = Bf == 0 ? B0 : (Bf == 1 ? B1 : B2);
                 const char *St = Bf == 0 ? S0 : (Bf == 1 ? S1 : S2);
                 const int j0 = j * kBdBN;
-                run_block(RAGGED, At, Bt, St, 0, j0);
-                if (!ragged || j0 + 32 < Lc) run_block(RAGGED, At, Bt, St, 1, j0);
+                if (CAUSAL && ragged) {
+                    // A masking stage of a causal tile, seen by one wave: its 32 stationary rows against each block of 32
+                    // streamed rows.  Blocks wholly on the far side of the diagonal contribute nothing.
+                    const int mine = (tile0 + wave * 32) / 32;
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb) {
+                        const int theirs = j0 / 32 + mb;
+                        if (theirs * 32 >= Lc) continue;
+                        if (kRowStats ? theirs >= mine : theirs <= mine) run_block(RAGGED, At, Bt, St, mb, j0);
+                    }
+                } else {
+                    run_block(RAGGED, At, Bt, St, 0, j0);
+                    if (!ragged || j0 + 32 < Lc) run_block(RAGGED, At, Bt, St, 1, j0);
+                }
             }
             asm volatile("" ::: "memory");
             if (ahead) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);

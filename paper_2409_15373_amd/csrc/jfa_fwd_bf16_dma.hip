@@ -336,7 +336,15 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             constexpr int Bf = decltype(BUF)::value;
             const bool ahead = j + 2 < n_stages;
             if (ahead) issue_stage(IntC<(Bf + 2) % 3>{}, j + 2);
-            if (wave_active) pipelined(BUF, RAGGED, j);
+            if (CAUSAL && decltype(RAGGED)::value != 0) {
+                // A masking stage of a causal tile, seen by one wave: its 32 queries lie inside one 64-key stage.  Earlier
+                // stages hold only keys below all of them (no mask, and all inside the sample), later ones only keys above.
+                const int j_diagonal = (q_tile0 + wave * 32) / kDmaBN;
+                if (wave_active && j < j_diagonal) pipelined(BUF, IntC<0>{}, j);
+                else if (wave_active && j == j_diagonal) pipelined(BUF, IntC<1>{}, j);
+            } else if (wave_active) {
+                pipelined(BUF, RAGGED, j);
+            }
             asm volatile("" ::: "memory");
             if (ahead) __builtin_amdgcn_s_waitcnt(0x0070 | kDmaOpsPerStage);   // vmcnt(ops of one stage) lgkmcnt(0)
             else __builtin_amdgcn_s_waitcnt(0x0070);                           // vmcnt(0) lgkmcnt(0)
