@@ -435,14 +435,49 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         __syncthreads();
         int ticket = -1;   // the claim of the next work item: its atomic travels while the stages run
         if (tid == 0) ticket = claim_issue(s.counter, cursor, total);
-        if (CAUSAL) {   // stage j lives in buffer (j - js) % 3; which stages mask depends on the side of the diagonal
-            for (int j = js; j < n_stages; ++j) {
-                const bool masking = kRowStats ? (j < js + kDmaBlockRows / kBdBN || (j + 1) * kBdBN > L)
-                                               : (j + 1) * kBdBN > (tile0 + 1 < L ? tile0 + 1 : L);
-                const int r = (j - js) % 3;
-                if (r == 0) { if (masking) run_stage(IntB<0>{}, IntB<1>{}, j); else run_stage(IntB<0>{}, IntB<0>{}, j); }
-                else if (r == 1) { if (masking) run_stage(IntB<1>{}, IntB<1>{}, j); else run_stage(IntB<1>{}, IntB<0>{}, j); }
-                else { if (masking) run_stage(IntB<2>{}, IntB<1>{}, j); else run_stage(IntB<2>{}, IntB<0>{}, j); }
+        if (CAUSAL && !kRowStats) {
+            // dQ: keys 0 .. tile0 lie below every query of the tile (full stages, as without the mask); the stages that
+            // reach past the tile's first query follow in the masking form
+            const int n_full = (tile0 + 1 < L ? tile0 + 1 : L) / kBdBN;
+            int j = 0;
+            for (; j + 3 <= n_full; j += 3) {
+                run_stage(IntB<0>{}, IntB<0>{}, j);
+                run_stage(IntB<1>{}, IntB<0>{}, j + 1);
+                run_stage(IntB<2>{}, IntB<0>{}, j + 2);
+            }
+            if (j < n_full) { run_stage(IntB<0>{}, IntB<0>{}, j); ++j; }
+            if (j < n_full) { run_stage(IntB<1>{}, IntB<0>{}, j); ++j; }
+            for (; j < n_stages; ++j) {
+                const int r = j % 3;
+                if (r == 0) run_stage(IntB<0>{}, IntB<1>{}, j);
+                else if (r == 1) run_stage(IntB<1>{}, IntB<1>{}, j);
+                else run_stage(IntB<2>{}, IntB<1>{}, j);
+            }
+        } else if (CAUSAL) {
+            // dK, dV: the stream of queries starts at the tile's first key; stage j lives in buffer (j - js) % 3.  Its first
+            // four stages cross the diagonal (buffers 0, 1, 2, 0) and mask, full stages follow from buffer 1 on, and the
+            // sample's ragged last stage masks again: one copy of the masking stages serves both ends.
+            const int diagonal_end = js + kDmaBlockRows / kBdBN < n_stages ? js + kDmaBlockRows / kBdBN : n_stages;
+            const int n_full = L / kBdBN;
+            int j = js;
+#pragma nounroll
+            for (int part = 0; part < 2; ++part) {
+                const int masking_end = part == 0 ? diagonal_end : n_stages;
+                for (; j < masking_end; ++j) {
+                    const int r = (j - js) % 3;
+                    if (r == 0) run_stage(IntB<0>{}, IntB<1>{}, j);
+                    else if (r == 1) run_stage(IntB<1>{}, IntB<1>{}, j);
+                    else run_stage(IntB<2>{}, IntB<1>{}, j);
+                }
+                if (part == 0) {
+                    for (; j + 3 <= n_full; j += 3) {
+                        run_stage(IntB<1>{}, IntB<0>{}, j);
+                        run_stage(IntB<2>{}, IntB<0>{}, j + 1);
+                        run_stage(IntB<0>{}, IntB<0>{}, j + 2);
+                    }
+                    if (j < n_full) { run_stage(IntB<1>{}, IntB<0>{}, j); ++j; }
+                    if (j < n_full) { run_stage(IntB<2>{}, IntB<0>{}, j); ++j; }
+                }
             }
         } else {
             const int n_full = L / kBdBN;   // stages with all 64 streamed rows valid; a ragged one may follow
