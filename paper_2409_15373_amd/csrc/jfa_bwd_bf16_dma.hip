@@ -85,8 +85,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
     // and dP accumulators of every block start from these (four 16-byte LDS reads each, no VALU work, no registers
     // held across the stage): P = exp2(acc) and dS = P * acc then cost one exponential and one multiply.
     __shared__ float4 lane_init[MODE == kModeDQ ? kBdThreads * 2 : 1];
-    __shared__ WorkSlot slot;   // the NEXT work item, decoded by wave 0 at the end of the current one's stages
-    __shared__ LdsSchedule<CROSS> tab;   // the schedule, copied once per workgroup when it fits
+    __shared__ WorkSlot slot;   // the NEXT work item, claimed and decoded while the current one starts up
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, half = lane >> 5;
@@ -186,16 +185,14 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             if (kSecond) yreg[ks] = *reinterpret_cast<const bf16x8 *>(ysrc + off + 16 * ks);
         }
     };
-    const bool tabled = B <= kTabCap;
 
     WorkCursor cursor;
     if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_other : nullptr);
-    if (tabled) tab.fill(s, offsets, offsets_other, B);
-    __syncthreads();   // the slot and the tables are written
+    __syncthreads();   // the slot is written
     Work t;
     bool have = load_work<CROSS>(&slot, t);
-    bool pre = false;   // the stationary rows and the first two stages of t are already on their way
     while (have) {
+        __syncthreads();   // every wave has read the slot before wave 0 refills it
         const Stream cur = stream_of(t);
         const int Ls = t.len;                      // stationary rows of the sample
         const int L = cur.L;                       // streamed rows of the sample
@@ -204,7 +201,6 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         const int js = cur.js;                     // first stage of the stream
         const int n_stages = cur.n_stages;
         if (CROSS && L == 0) {   // nothing streams past these rows: their gradient is zero
-            __syncthreads();   // every wave has read the slot
             if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, offsets_other);
             const int i = t.block * kDmaBlockRows + wave * 32 + (lane & 31);
             if (i < Ls) {
@@ -218,7 +214,6 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             }
             __syncthreads();   // the slot is written
             have = load_work<CROSS>(&slot, t);
-            pre = false;
             continue;
         }
         const float *const delta_rows = cur.delta_rows;
@@ -227,11 +222,10 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         const int i = t.block * kDmaBlockRows + wave * 32 + col;
         const int ic = i < Ls ? i : Ls - 1;
         const bool wave_active = t.block * kDmaBlockRows + wave * 32 < Ls;
-        if (!pre) {   // first tile of the workgroup: nothing was sent ahead
-            load_stationary(t);
-            issue_stage_from(cur, IntB<0>{}, js);
-            if (n_stages - js > 1) issue_stage_from(cur, IntB<1>{}, js + 1);
-        }
+        load_stationary(t);
+        issue_stage_from(cur, IntB<0>{}, js);
+        if (n_stages - js > 1) issue_stage_from(cur, IntB<1>{}, js + 1);
+        if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_other : nullptr);   // overlaps with the loads in flight
         f32x16 acc[kDBlocks];
 #pragma unroll
         for (int db = 0; db < kDBlocks; ++db)
@@ -430,11 +424,9 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
 #pragma unroll
             for (int e = 0; e < 8; ++e) xreg[ks][e] = (__bf16)((float)xreg[ks][e] * c);
         // The first stage has landed once at most one stage's loads are outstanding: what this wave sent after it is
-        // the second stage and, when the tile was sent ahead, the previous tile's gradient stores.
+        // the second stage (and, on wave 0, the loads of the claim, which it has waited for itself).
         if (n_stages - js > 1) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);
         __syncthreads();
-        int ticket = -1;   // the claim of the next work item: its atomic travels while the stages run
-        if (tid == 0) ticket = claim_issue(s.counter, cursor, total);
         if (CAUSAL && !kRowStats) {
             // dQ: keys 0 .. tile0 lie below every query of the tile (full stages, as without the mask); the stages that
             // reach past the tile's first query follow in the masking form
@@ -497,33 +489,13 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             }
         }
 
-        if (wave == 0) {   // the next work item, decoded into the slot (a few LDS reads when the schedule is in LDS)
-            int64_t w = -1;
-            if (lane == 0) w = claim_finish(s.counter, cursor, total, ticket);
-            w = uniform64(w);
-            if (tabled) tab.decode(&slot, B, H, w);
-            else decode_into_slot(&slot, s, offsets, B, H, w, CROSS ? offsets_other : nullptr);
-        }
-        __syncthreads();   // the slot is written
-
-        // ---- the next tile: its stationary rows and first two stages start now and travel during the epilogue ----
-        Work nt;
+        Work nt;   // the next work item: wave 0 parked it in the slot before this tile's first barrier
         const bool have_next = load_work<CROSS>(&slot, nt);
-        bool pre_next = false;
-        if (have_next) {
-            const Stream ns = stream_of(nt);
-            if (!CROSS || ns.L > 0) {
-                load_stationary(nt);
-                issue_stage_from(ns, IntB<0>{}, ns.js);
-                if (ns.n_stages - ns.js > 1) issue_stage_from(ns, IntB<1>{}, ns.js + 1);
-                pre_next = true;
-            }
-        }
 
         // ---- epilogue: scale, transpose the wave's 32 x 128 gradient block through LDS, 64 features at a time, and store
-        // whole 128-byte pieces of rows, eight rows per store instruction.  The third pair of stage buffers is idle (every
-        // wave is past the last stage's barrier, and the next tile's third stage is only sent after that tile's first
-        // barrier); wave w uses 4 KB of it: row r of its block at r * 128, 16-byte chunk ch at (ch ^ (r & 7)) << 4.
+        // whole 128-byte pieces of rows, eight rows per store instruction.  The stage buffers are idle (every wave is past
+        // the last stage's barrier, no DMA is in flight, and the next tile's loads start behind the barrier at the top of
+        // the loop); wave w uses 4 KB of the third pair: row r of its block at r * 128, 16-byte chunk ch at (ch ^ (r & 7)) << 4.
         {
             char *const region = (wave < 4 ? A2 : B2) + (wave & 3) * 4096;
             const float out_scale = MODE == kModeDV ? 1.0f : (MODE == kModeDK ? -scale : scale);
@@ -556,7 +528,6 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         }
         t = nt;
         have = have_next;
-        pre = pre_next;
     }
 }
 

@@ -97,23 +97,6 @@ __device__ inline int64_t next_work(int32_t *counters, WorkCursor &cur, int64_t 
     }
 }
 
-// The same claim in two parts, for kernels that hide the atomic's latency behind a tile's work: claim_issue() sends the
-// home queue's atomic add and returns its result without using it (-1: this claim takes no such atomic -- small
-// problem, first item, or home queue already empty); claim_finish() turns it into a work id, going on to the other
-// queues as next_work() does.  Both are called by the same single thread.
-__device__ inline int claim_issue(int32_t *counters, WorkCursor &cur, int64_t total) {
-    if (total <= 4 * (int64_t)cursor_grid(cur) || cur.first || cur.home_done) return -1;
-    return atomicAdd(&counters[blockIdx.x % kXcds], 1);
-}
-__device__ inline int64_t claim_finish(int32_t *counters, WorkCursor &cur, int64_t total, int ticket) {
-    if (ticket >= 0) {
-        const int64_t id = work_id(blockIdx.x % kXcds, cursor_grid(cur) / kXcds + ticket);
-        if (id < total) return id;
-        cur.home_done = true;
-    }
-    return next_work(counters, cur, total);
-}
-
 // The work id is the same for every lane; saying so lets the tile parameters derived from it live in scalar
 // registers and be fetched with scalar loads.
 __device__ inline int64_t uniform64(int64_t x) {
@@ -203,9 +186,6 @@ struct WorkSlot {
     int olen, orow0_lo, orow0_hi;   // the other side's rows (cross attention only)
 };
 
-__device__ inline void decode_into_slot(WorkSlot *slot, const Schedule &s, const int64_t *offsets, int B, int H, int64_t w,
-                                        const int64_t *offsets_other);
-
 // Claim the next work item and decode it into `slot`.  Called by every lane of ONE wave (the claim itself is
 // made by its lane 0, whose registers hold `cur`); meant to be issued right after a tile's first loads so
 // that its latency chain (atomic, search, offsets) overlaps with theirs.
@@ -214,13 +194,7 @@ __device__ inline void claim_and_decode(WorkSlot *slot, const Schedule &s, const
     const int lane = threadIdx.x & 63;
     int64_t w = -1;
     if (lane == 0) w = next_work(s.counter, cur, total);
-    decode_into_slot(slot, s, offsets, B, H, uniform64(w), offsets_other);
-}
-
-// Decode work id w (the same in every lane; < 0: nothing left) into `slot`.  Called by every lane of one wave.
-__device__ inline void decode_into_slot(WorkSlot *slot, const Schedule &s, const int64_t *offsets, int B, int H, int64_t w,
-                                        const int64_t *offsets_other) {
-    const int lane = threadIdx.x & 63;
+    w = uniform64(w);
     if (w < 0) {
         if (lane == 0) slot->valid = 0;
         return;
@@ -251,71 +225,6 @@ __device__ inline void decode_into_slot(WorkSlot *slot, const Schedule &s, const
         slot->row0_hi = (int)(uint32_t)((uint64_t)row0 >> 32);
     }
 }
-
-// A workgroup's LDS copy of a schedule of at most kTabCap samples (position p of the sorted order: first tile,
-// sample, rows): decoding a claimed work id then costs a few LDS reads instead of a chain of dependent global loads.
-// Declare it __shared__; CROSS adds the other side's rows.
-constexpr int kTabCap = 1024;
-template <bool CROSS>
-struct LdsSchedule {
-    int32_t start[kTabCap + 1];
-    int32_t sample[kTabCap], len[kTabCap], row0[kTabCap][2];
-    int32_t olen[CROSS ? kTabCap : 1], orow0[CROSS ? kTabCap : 1][2];
-
-    // Called by every thread of the workgroup, B <= kTabCap; a barrier must follow before decode().
-    __device__ void fill(const Schedule &s, const int64_t *offsets, const int64_t *offsets_other, int B) {
-        for (int p = threadIdx.x; p <= B; p += blockDim.x) start[p] = s.tile_start[p];
-        for (int p = threadIdx.x; p < B; p += blockDim.x) {
-            const int b = s.order[p];
-            const int64_t r0 = offsets[b];
-            sample[p] = b;
-            len[p] = (int)(offsets[b + 1] - r0);
-            row0[p][0] = (int)(uint32_t)r0;
-            row0[p][1] = (int)(uint32_t)((uint64_t)r0 >> 32);
-            if (CROSS) {
-                const int64_t o0 = offsets_other[b];
-                olen[p] = (int)(offsets_other[b + 1] - o0);
-                orow0[p][0] = (int)(uint32_t)o0;
-                orow0[p][1] = (int)(uint32_t)((uint64_t)o0 >> 32);
-            }
-        }
-    }
-
-    // Work id w (the same in every lane; < 0: nothing left) -> slot.  Called by every lane of one wave.
-    __device__ void decode(WorkSlot *slot, int B, int H, int64_t w) const {
-        const int lane = threadIdx.x & 63;
-        if (w < 0) {
-            if (lane == 0) slot->valid = 0;
-            return;
-        }
-        int lo = 0, hi = B;   // invariant: start[lo] * H <= w < start[hi] * H
-        while (hi - lo > 1) {
-            const int step = (hi - lo + 63) / 64;
-            const int idx = lo + (lane + 1) * step;
-            const bool ok = idx < hi && (int64_t)start[idx] * H <= w;   // true for a prefix of the lanes
-            const int cnt = __popcll(__builtin_amdgcn_ballot_w64(ok));
-            lo += cnt * step;
-            hi = hi < lo + step ? hi : lo + step;
-        }
-        if (lane == 0) {
-            const int t0 = start[lo];
-            const int n = start[lo + 1] - t0;
-            const int r = (int)(w - (int64_t)t0 * H);
-            slot->valid = 1;
-            slot->sample = sample[lo];
-            slot->head = r / n;
-            slot->block = r - (r / n) * n;
-            slot->len = len[lo];
-            slot->row0_lo = row0[lo][0];
-            slot->row0_hi = row0[lo][1];
-            if (CROSS) {
-                slot->olen = olen[lo];
-                slot->orow0_lo = orow0[lo][0];
-                slot->orow0_hi = orow0[lo][1];
-            }
-        }
-    }
-};
 
 // Read the parked work item into scalar registers; returns false when nothing is left.  CROSS: the slot also holds
 // the other side's rows.

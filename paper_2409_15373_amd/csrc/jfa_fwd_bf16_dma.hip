@@ -61,9 +61,8 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
     __shared__ __attribute__((aligned(1024))) char V0[kDmaTile];
     __shared__ __attribute__((aligned(1024))) char V1[kDmaTile];
     __shared__ __attribute__((aligned(1024))) char V2[kDmaTile];
-    __shared__ WorkSlot slot;   // the NEXT work item, decoded by wave 0 at the end of the current one's stages
+    __shared__ WorkSlot slot;   // the NEXT work item, claimed and decoded while the current one starts up
     __shared__ int restart;   // set by a wave whose reference maximum went stale beyond repair
-    __shared__ LdsSchedule<CROSS> tab;   // the schedule, copied once per workgroup when it fits
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, half = lane >> 5;
@@ -133,21 +132,13 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * ks);
     };
-    // Work id -> slot, by wave 0: from the LDS copy of the schedule when there is one.
-    const bool tabled = B <= kTabCap;
-    auto decode_next = [&](int64_t w) {
-        if (tabled) tab.decode(&slot, B, H, w);
-        else decode_into_slot(&slot, s, offsets, B, H, w, CROSS ? offsets_kv : nullptr);
-    };
-
     WorkCursor cursor;
     if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_kv : nullptr);
-    if (tabled) tab.fill(s, offsets, offsets_kv, B);
-    __syncthreads();   // the slot and the tables are written
+    __syncthreads();   // the slot is written
     Work t;
     bool have = load_work<CROSS>(&slot, t);
-    bool pre = false;   // the query rows and the first two stages of t are already on their way
     while (have) {
+        __syncthreads();   // every wave has read the slot before wave 0 refills it
         const Stream cur = stream_of(t);
         const int Lq = t.len;                      // queries of the sample
         const int L = cur.L;                       // keys of the sample
@@ -156,7 +147,6 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         const __bf16 *const kbase = cur.kbase;
         const __bf16 *const vbase = cur.vbase;
         if (CROSS && L == 0) {   // no keys: an empty softmax, out = 0 and lse = -inf
-            __syncthreads();   // every wave has read the slot
             if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, offsets_kv);
             const int i = t.block * kDmaBlockRows + wave * 32 + (lane & 31);
             if (i < Lq) {
@@ -167,7 +157,6 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             }
             __syncthreads();   // the slot is written
             have = load_work<CROSS>(&slot, t);
-            pre = false;
             continue;
         }
 
@@ -352,11 +341,10 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             asm volatile("" ::: "memory");
         };
 
-        if (!pre) {   // first tile of the workgroup: nothing was sent ahead
-            load_q(t);
-            issue_stage(IntC<0>{}, 0);
-            if (n_stages > 1) issue_stage(IntC<1>{}, 1);
-        }
+        load_q(t);
+        issue_stage(IntC<0>{}, 0);
+        if (n_stages > 1) issue_stage(IntC<1>{}, 1);
+        if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_kv : nullptr);   // overlaps with the loads in flight
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qreg[ks]));   // Q loads complete here
         // The softmax scale and the change to base-2 exponentials go into Q once per tile (q * log2(e) / sqrt(D),
@@ -366,16 +354,10 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
 #pragma unroll
             for (int e = 0; e < 8; ++e) qreg[ks][e] = (__bf16)((float)qreg[ks][e] * c);
         // Stage 0 has landed once at most one stage's loads are outstanding: what this wave sent after it is stage 1
-        // and, when the tile was sent ahead, the previous tile's output stores.
+        // (and, on wave 0, the loads of the claim, which it has waited for itself).
         if (n_stages > 1) __builtin_amdgcn_s_waitcnt(0x0070 | kDmaOpsPerStage); else __builtin_amdgcn_s_waitcnt(0x0070);
         __syncthreads();
-        // The claim of the next work item: its atomic travels while the stages run; nobody looks at `restart` between
-        // the previous tile's check and this barrier.
-        int ticket = -1;
-        if (tid == 0) {
-            restart = 0;
-            ticket = claim_issue(s.counter, cursor, total);
-        }
+        if (tid == 0) restart = 0;   // nobody looks at it between the previous tile's check and this barrier
         if (wave_active) {   // reference maximum: the first 32 keys
             f32x16 s0;
             scores(K0, 0, s0);
@@ -404,14 +386,9 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
                 else run_stage(IntC<2>{}, IntC<1>{}, j);
             }
         }
-        if (wave == 0) {   // the next work item, decoded into the slot (a few LDS reads when the schedule is in LDS)
-            int64_t w = -1;
-            if (lane == 0) w = claim_finish(s.counter, cursor, total, ticket);
-            decode_next(uniform64(w));
-        }
         // a row sum this large (or not finite) means the fixed reference was too far below the true maximum
         if (wave_active && __builtin_amdgcn_ballot_w64(!(lsum < 0x1p62f)) != 0 && lane == 0) restart = 1;
-        __syncthreads();   // the slot and `restart` are written
+        __syncthreads();   // `restart` is written
         const bool again = restart != 0;
 
         // ---- pass 2 (never on data of one scale): the whole tile again, maximum first, two buffers ----
@@ -437,29 +414,14 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             }
         }
 
-        // ---- the next tile: its query rows and first two stages start now and travel during the epilogue ----
-        Work nt;
+        Work nt;   // the next work item: wave 0 parked it in the slot before this tile's first barrier
         const bool have_next = load_work<CROSS>(&slot, nt);
-        bool pre_next = false;
-        if (have_next) {
-            const Stream ns = stream_of(nt);
-            if (!CROSS || ns.L > 0) {
-                load_q(nt);
-                issue_from(ns, ns.kbase, K0, 0, true);
-                issue_from(ns, ns.vbase, V0, 0, false);
-                if (ns.n_stages > 1) {
-                    issue_from(ns, ns.kbase, K1, 1, true);
-                    issue_from(ns, ns.vbase, V1, 1, false);
-                }
-                pre_next = true;
-            }
-        }
 
         // ---- epilogue: normalise; transpose the wave's 32 x 128 output block through LDS, 64 features at a time, so
         // that it leaves as whole 128-byte pieces of rows (16 bytes per lane, eight rows per store instruction) instead
         // of 8-byte pieces of 32 different rows per instruction; store the log-sum-exp ----
-        // The third stage buffer is idle here (every wave is past the last stage's barrier, and the next tile's third
-        // stage is only sent after that tile's first barrier); wave w uses 4 KB of it: row r of its block at r * 128,
+        // The stage buffers are idle here (every wave is past the last stage's barrier and no DMA is in flight, and the
+        // next tile's loads start behind the barrier at the top of the loop); wave w uses 4 KB of the third one: row r of its block at r * 128,
         // 16-byte chunk ch at (ch ^ (r & 7)) << 4.
         const float l_total = pair_sum(lsum);
         {
@@ -496,7 +458,6 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             lse[(int64_t)t.head * sum_B + t.row0 + i] = (m + fast_log2(l_total)) * 0.6931471805599453f;
         t = nt;
         have = have_next;
-        pre = pre_next;
     }
 }
 

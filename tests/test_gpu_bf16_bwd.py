@@ -93,9 +93,9 @@ def test_backward_is_deterministic():
 
 
 @pytest.mark.parametrize("is_causal", [False, True])
-def test_more_samples_than_the_lds_schedule_holds(oracle, is_causal):
-    """The direct-to-LDS kernels keep the schedule of up to 1024 samples in LDS and decode claimed work ids from global
-    memory beyond that: 1300 short samples (some empty) and three long ones, with enough work items for dynamic claims."""
+def test_many_short_samples_with_dynamic_claims(oracle, is_causal):
+    """The direct-to-LDS kernels on a batch of 1300 short samples (some empty) and three long ones: several work items per
+    workgroup, so that items are claimed dynamically and decoded by the two-level search of the schedule."""
     from oracle import causal
     from paper_2409_15373_amd import binding
     rng = np.random.default_rng(31)
