@@ -86,6 +86,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
     // held across the stage): P = exp2(acc) and dS = P * acc then cost one exponential and one multiply.
     __shared__ float4 lane_init[MODE == kModeDQ ? kBdThreads * 2 : 1];
     __shared__ WorkSlot slot;   // the NEXT work item, claimed and decoded while the current one starts up
+    __shared__ LdsSchedule<CROSS> tab;   // the schedule, copied once per workgroup when it fits
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, half = lane >> 5;
@@ -186,9 +187,22 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         }
     };
 
+    // The claim of the next item runs while a tile's first loads travel, and the tile cannot start before it is done:
+    // with the schedule in LDS it is one atomic and a few LDS reads instead of five dependent trips to memory.
+    const bool tabled = B <= kTabCap;
     WorkCursor cursor;
+    auto claim_next = [&]() {   // wave 0, every lane
+        if (!tabled) {
+            claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_other : nullptr);
+            return;
+        }
+        int64_t w = -1;
+        if (lane == 0) w = next_work(s.counter, cursor, total);
+        tab.decode(&slot, B, H, uniform64(w));
+    };
     if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_other : nullptr);
-    __syncthreads();   // the slot is written
+    if (tabled) tab.fill(s, offsets, offsets_other, B);
+    __syncthreads();   // the slot and the tables are written
     Work t;
     bool have = load_work<CROSS>(&slot, t);
     while (have) {
@@ -201,7 +215,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         const int js = cur.js;                     // first stage of the stream
         const int n_stages = cur.n_stages;
         if (CROSS && L == 0) {   // nothing streams past these rows: their gradient is zero
-            if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, offsets_other);
+            if (wave == 0) claim_next();
             const int i = t.block * kDmaBlockRows + wave * 32 + (lane & 31);
             if (i < Ls) {
                 __bf16 *grow = grad + (t.row0 + i) * row_stride + (int64_t)t.head * D + (lane >> 5) * (D / 2);
@@ -225,7 +239,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         load_stationary(t);
         issue_stage_from(cur, IntB<0>{}, js);
         if (n_stages - js > 1) issue_stage_from(cur, IntB<1>{}, js + 1);
-        if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_other : nullptr);   // overlaps with the loads in flight
+        if (wave == 0) claim_next();   // overlaps with the loads in flight
         f32x16 acc[kDBlocks];
 #pragma unroll
         for (int db = 0; db < kDBlocks; ++db)

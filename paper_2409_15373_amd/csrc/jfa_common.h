@@ -226,6 +226,71 @@ __device__ inline void claim_and_decode(WorkSlot *slot, const Schedule &s, const
     }
 }
 
+// A workgroup's LDS copy of a schedule of at most kTabCap samples (position p of the sorted order: first tile,
+// sample, rows): decoding a claimed work id then costs a few LDS reads instead of a chain of dependent global loads.
+// Declare it __shared__; CROSS adds the other side's rows.
+constexpr int kTabCap = 1024;
+template <bool CROSS>
+struct LdsSchedule {
+    int32_t start[kTabCap + 1];
+    int32_t sample[kTabCap], len[kTabCap], row0[kTabCap][2];
+    int32_t olen[CROSS ? kTabCap : 1], orow0[CROSS ? kTabCap : 1][2];
+
+    // Called by every thread of the workgroup, B <= kTabCap; a barrier must follow before decode().
+    __device__ void fill(const Schedule &s, const int64_t *offsets, const int64_t *offsets_other, int B) {
+        for (int p = threadIdx.x; p <= B; p += blockDim.x) start[p] = s.tile_start[p];
+        for (int p = threadIdx.x; p < B; p += blockDim.x) {
+            const int b = s.order[p];
+            const int64_t r0 = offsets[b];
+            sample[p] = b;
+            len[p] = (int)(offsets[b + 1] - r0);
+            row0[p][0] = (int)(uint32_t)r0;
+            row0[p][1] = (int)(uint32_t)((uint64_t)r0 >> 32);
+            if (CROSS) {
+                const int64_t o0 = offsets_other[b];
+                olen[p] = (int)(offsets_other[b + 1] - o0);
+                orow0[p][0] = (int)(uint32_t)o0;
+                orow0[p][1] = (int)(uint32_t)((uint64_t)o0 >> 32);
+            }
+        }
+    }
+
+    // Work id w (the same in every lane; < 0: nothing left) -> slot.  Called by every lane of one wave.
+    __device__ void decode(WorkSlot *slot, int B, int H, int64_t w) const {
+        const int lane = threadIdx.x & 63;
+        if (w < 0) {
+            if (lane == 0) slot->valid = 0;
+            return;
+        }
+        int lo = 0, hi = B;   // invariant: start[lo] * H <= w < start[hi] * H
+        while (hi - lo > 1) {
+            const int step = (hi - lo + 63) / 64;
+            const int idx = lo + (lane + 1) * step;
+            const bool ok = idx < hi && (int64_t)start[idx] * H <= w;   // true for a prefix of the lanes
+            const int cnt = __popcll(__builtin_amdgcn_ballot_w64(ok));
+            lo += cnt * step;
+            hi = hi < lo + step ? hi : lo + step;
+        }
+        if (lane == 0) {
+            const int t0 = start[lo];
+            const int n = start[lo + 1] - t0;
+            const int r = (int)(w - (int64_t)t0 * H);
+            slot->valid = 1;
+            slot->sample = sample[lo];
+            slot->head = r / n;
+            slot->block = r - (r / n) * n;
+            slot->len = len[lo];
+            slot->row0_lo = row0[lo][0];
+            slot->row0_hi = row0[lo][1];
+            if (CROSS) {
+                slot->olen = olen[lo];
+                slot->orow0_lo = orow0[lo][0];
+                slot->orow0_hi = orow0[lo][1];
+            }
+        }
+    }
+};
+
 // Read the parked work item into scalar registers; returns false when nothing is left.  CROSS: the slot also holds
 // the other side's rows.
 template <bool CROSS = false>

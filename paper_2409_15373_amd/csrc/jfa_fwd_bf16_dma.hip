@@ -62,6 +62,7 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
     __shared__ __attribute__((aligned(1024))) char V1[kDmaTile];
     __shared__ __attribute__((aligned(1024))) char V2[kDmaTile];
     __shared__ WorkSlot slot;   // the NEXT work item, claimed and decoded while the current one starts up
+    __shared__ LdsSchedule<CROSS> tab;   // the schedule, copied once per workgroup when it fits
     __shared__ int restart;   // set by a wave whose reference maximum went stale beyond repair
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -132,9 +133,22 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) qreg[ks] = *reinterpret_cast<const bf16x8 *>(qrow + 16 * ks);
     };
+    // The claim of the next item runs while a tile's first loads travel, and the tile cannot start before it is done:
+    // with the schedule in LDS it is one atomic and a few LDS reads instead of five dependent trips to memory.
+    const bool tabled = B <= kTabCap;
     WorkCursor cursor;
+    auto claim_next = [&]() {   // wave 0, every lane
+        if (!tabled) {
+            claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_kv : nullptr);
+            return;
+        }
+        int64_t w = -1;
+        if (lane == 0) w = next_work(s.counter, cursor, total);
+        tab.decode(&slot, B, H, uniform64(w));
+    };
     if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_kv : nullptr);
-    __syncthreads();   // the slot is written
+    if (tabled) tab.fill(s, offsets, offsets_kv, B);
+    __syncthreads();   // the slot and the tables are written
     Work t;
     bool have = load_work<CROSS>(&slot, t);
     while (have) {
@@ -147,7 +161,7 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         const __bf16 *const kbase = cur.kbase;
         const __bf16 *const vbase = cur.vbase;
         if (CROSS && L == 0) {   // no keys: an empty softmax, out = 0 and lse = -inf
-            if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, offsets_kv);
+            if (wave == 0) claim_next();
             const int i = t.block * kDmaBlockRows + wave * 32 + (lane & 31);
             if (i < Lq) {
                 __bf16 *orow = out + (t.row0 + i) * row_stride + (int64_t)t.head * D + (lane >> 5) * (D / 2);
@@ -344,7 +358,7 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         load_q(t);
         issue_stage(IntC<0>{}, 0);
         if (n_stages > 1) issue_stage(IntC<1>{}, 1);
-        if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_kv : nullptr);   // overlaps with the loads in flight
+        if (wave == 0) claim_next();   // overlaps with the loads in flight
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qreg[ks]));   // Q loads complete here
         // The softmax scale and the change to base-2 exponentials go into Q once per tile (q * log2(e) / sqrt(D),
