@@ -64,8 +64,11 @@ def test_bf16_backward_length_one(oracle):
     assert np.abs(f64(dq)).max() <= 1e-2 and np.abs(f64(dk)).max() <= 1e-2     # dS = P (dP - delta) ~ 0
 
 
-def test_config5_backward_on_sampled_pairs(oracle):
-    w = make_workload("c5_uniform_bf16")
+@pytest.mark.parametrize("name", ["c5_uniform_bf16", "c4_bimodal_bf16"])
+def test_full_size_backward_on_sampled_pairs(oracle, name):
+    """The configuration with gradients and the benchmarked one, as the benchmark runs them (same inputs, same launch
+    shapes); whole (sample, head) pairs -- longest, shortest, median and random ones -- against the oracle."""
+    w = make_workload(name, with_dout=True)
     dq, dk, dv, delta = gpu_forward_backward(w)
     for t in (dq, dk, dv):
         assert torch.isfinite(t.float()).all()
