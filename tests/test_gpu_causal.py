@@ -101,3 +101,30 @@ def test_causal_stale_reference_maximum_takes_the_conservative_pass():
     assert np.isfinite(f64(out)).all() and np.isfinite(f64(lse)).all()
     gate_bf16("out", f64(out), r_out)
     gate_bf16("lse", f64(lse), r_lse, abs_tol=2e-2 * max(1.0, np.abs(r_lse).max() / 4))
+
+
+def test_causal_full_size_on_sampled_pairs():
+    """The benchmarked configuration's inputs through the causal entry points (what variants_bench times); whole
+    (sample, head) pairs -- longest, shortest, median and random ones -- against the oracle run on each pair alone."""
+    from paper_2409_15373_amd import binding
+    from paper_2409_15373_amd.synthetic import make_workload
+    w = make_workload("c4_bimodal_bf16", with_dout=True)
+    d = to_device(w)
+    out, lse = binding.jfa_forward(d["q"], d["k"], d["v"], d["offsets"], w.max_len, causal=True)
+    dq, dk, dv, _ = binding.jfa_backward(d["q"], d["k"], d["v"], out, d["dout"], lse, d["offsets"], w.max_len, causal=True)
+    torch.cuda.synchronize()
+    order = np.argsort(w.lengths)
+    rng = np.random.default_rng(6)
+    picks = [(int(order[-1]), 0), (int(order[0]), w.H - 1), (int(order[len(order) // 2]), 1)]
+    picks += [(int(rng.integers(0, w.B)), int(rng.integers(0, w.H))) for _ in range(5)]
+    for b, h in picks:
+        s, e = int(w.offsets[b]), int(w.offsets[b + 1])
+        one = lambda x: np.ascontiguousarray(x[s:e, h:h + 1])
+        off1 = np.array([0, e - s], dtype=np.int64)
+        r_out, r_lse = causal.forward(one(w.q), one(w.k), one(w.v), off1)
+        r_dq, r_dk, r_dv, _ = causal.backward(one(w.q), one(w.k), one(w.v), one(w.dout), off1)
+        tag = f"sample {b} (length {e - s}) head {h}: "
+        gate_bf16(tag + "out", f64(out[s:e, h:h + 1]), r_out)
+        gate_bf16(tag + "lse", f64(lse[h:h + 1, s:e]), r_lse)
+        for name, g, r in (("dq", dq, r_dq), ("dk", dk, r_dk), ("dv", dv, r_dv)):
+            gate_bf16(tag + name, f64(g[s:e, h:h + 1]), r, abs_tol=2e-2 * max(1.0, float(np.abs(r).max()) / 2))

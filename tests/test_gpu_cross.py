@@ -148,3 +148,39 @@ def test_cross_stale_reference_maximum_takes_the_conservative_pass():
     assert np.isfinite(f64(out)).all() and np.isfinite(f64(lse)).all()
     gate_bf16("out", f64(out), r_out)
     gate_bf16("lse", f64(lse), r_lse, abs_tol=2e-2 * max(1.0, np.abs(r_lse).max() / 4))
+
+
+def test_cross_full_size_on_sampled_pairs():
+    """Keys with the benchmarked configuration's lengths, queries with those lengths shuffled across samples (the
+    "shuffled" workload of variants_bench, B = 512, H = 8, D = 128); whole (sample, head) pairs against the oracle."""
+    from paper_2409_15373_amd import binding
+    from paper_2409_15373_amd.synthetic import CONFIGS, lengths_for
+    c = CONFIGS["c4_bimodal_bf16"]
+    Lk = lengths_for(c["lengths"], c["B"], c["max_len"], np.random.Generator(np.random.PCG64(c["seed"])))
+    Lq = np.random.default_rng(7).permutation(Lk)
+    H, D = c["H"], c["D"]
+    host, dev, oq, ok = make(Lq, Lk, H, D, "bf16", 8)
+    oqd, okd = torch.from_numpy(oq).cuda(), torch.from_numpy(ok).cuda()
+    nq, nk = int(oq[-1]), int(ok[-1])
+    lse = torch.empty((H, nq), dtype=torch.float32, device="cuda")
+    out, _ = binding.jfa_forward_cross(dev["q"], dev["k"], dev["v"], oqd, okd, c["max_len"], c["max_len"], lse=lse)
+    stats = torch.empty((2, H, nq), dtype=torch.float32, device="cuda")
+    dq, dk, dv, _ = binding.jfa_backward_cross(dev["q"], dev["k"], dev["v"], out, dev["dout"], lse, oqd, okd, c["max_len"],
+                                               c["max_len"], delta=stats)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(9)
+    picks = [(int(np.argmax(Lq * Lk)), 0), (int(np.argmax(Lk)), H - 1), (int(np.argmax(Lq)), 1)]
+    picks += [(int(rng.integers(0, len(Lq))), int(rng.integers(0, H))) for _ in range(5)]
+    for b, h in picks:
+        qs, qe, ks, ke = int(oq[b]), int(oq[b + 1]), int(ok[b]), int(ok[b + 1])
+        oneq = lambda x: np.ascontiguousarray(x[qs:qe, h:h + 1])
+        onek = lambda x: np.ascontiguousarray(x[ks:ke, h:h + 1])
+        o1q, o1k = np.array([0, qe - qs], dtype=np.int64), np.array([0, ke - ks], dtype=np.int64)
+        r_out, r_lse = cross.forward(oneq(host["q"]), onek(host["k"]), onek(host["v"]), o1q, o1k)
+        r_dq, r_dk, r_dv, _ = cross.backward(oneq(host["q"]), onek(host["k"]), onek(host["v"]), oneq(host["dout"]), o1q, o1k)
+        tag = f"sample {b} ({qe - qs} queries, {ke - ks} keys) head {h}: "
+        gate_bf16(tag + "out", f64(out[qs:qe, h:h + 1]), r_out)
+        gate_bf16(tag + "lse", f64(lse[h:h + 1, qs:qe]), r_lse)
+        gate_bf16(tag + "dq", f64(dq[qs:qe, h:h + 1]), r_dq, abs_tol=2e-2 * max(1.0, float(np.abs(r_dq).max()) / 2))
+        gate_bf16(tag + "dk", f64(dk[ks:ke, h:h + 1]), r_dk, abs_tol=2e-2 * max(1.0, float(np.abs(r_dk).max()) / 2))
+        gate_bf16(tag + "dv", f64(dv[ks:ke, h:h + 1]), r_dv, abs_tol=2e-2 * max(1.0, float(np.abs(r_dv).max()) / 2))
