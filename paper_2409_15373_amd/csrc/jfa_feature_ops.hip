@@ -36,11 +36,19 @@ __device__ inline bf16x8 tr_operand(const char *tile, int off, int step, int blo
 // samples of different lengths; an offsets-sorted order would cost a scheduler launch that takes longer than it saves).
 __global__ void reset_counter_kernel(int32_t *counter) { if (threadIdx.x == 0) *counter = 0; }
 
-__device__ inline int claim_sample(int32_t *counter, int n_claimed, int *slot) {
+// Samples are claimed kClaimGroup consecutive ones at a time (`group` holds the current group between calls).  With
+// 64-byte rows a sample is a few kilobytes and a claim per sample costs more than moving it: two per claim took the
+// operators at D = T = 32 from 2.6 - 3.8 to 2.9 - 5.3 TB/s; with longer rows pairs only unbalance the workgroups (2 - 4 %
+// slower at 128- and 256-byte rows), so those claim one at a time.
+template <int kClaimGroup>
+__device__ inline int claim_sample(int32_t *counter, int n_claimed, int *slot, int &group) {
     __syncthreads();
-    if (threadIdx.x == 0) *slot = n_claimed == 0 ? (int)blockIdx.x : (int)gridDim.x + atomicAdd(counter, 1);
-    __syncthreads();
-    return __builtin_amdgcn_readfirstlane(*slot);
+    if (n_claimed % kClaimGroup == 0) {
+        if (threadIdx.x == 0) *slot = n_claimed == 0 ? (int)blockIdx.x : (int)gridDim.x + atomicAdd(counter, 1);
+        __syncthreads();
+        group = __builtin_amdgcn_readfirstlane(*slot);
+    }
+    return group * kClaimGroup + n_claimed % kClaimGroup;
 }
 
 // ---- jagged_dense_bmm: out^T = w_b^T x^T, one sample per workgroup step, 128 rows at a time ----
@@ -63,8 +71,9 @@ __global__ __launch_bounds__(kFoThreads) void jagged_dense_bmm_kernel(const __bf
     const int col = lane & 31, half = lane >> 5;
     const int woff = tr_lane_offset(lane, kWRow);
     char *mine = xt + wave * kRegion;
+    int group = 0;
     for (int n_claimed = 0;; ++n_claimed) {
-        const int p = claim_sample(counter, n_claimed, &slot);   // also: the previous sample's LDS tiles are free
+        const int p = claim_sample<(D + T <= 64 ? 2 : 1)>(counter, n_claimed, &slot, group);   // also: the previous sample's LDS tiles are free
         if (p >= B) break;
         const int b = p;
         const int64_t row0 = offsets[b];
@@ -150,8 +159,9 @@ __global__ __launch_bounds__(kFoThreads) void jagged_jagged_bmm_kernel(const __b
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, half = lane >> 5;
     const int xoff = tr_lane_offset(lane, kXRow), yoff = tr_lane_offset(lane, kYRow);
+    int group = 0;
     for (int n_claimed = 0;; ++n_claimed) {
-        const int p = claim_sample(counter, n_claimed, &slot);   // also: the previous sample's LDS tiles are free
+        const int p = claim_sample<(D + T <= 64 ? 2 : 1)>(counter, n_claimed, &slot, group);   // also: the previous sample's LDS tiles are free
         if (p >= B) break;
         const int b = p;
         const int64_t row0 = offsets[b];
@@ -246,8 +256,9 @@ __global__ __launch_bounds__(kFoThreads) void jagged_softmax_kernel(const __bf16
     __shared__ int slot;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int cg = tid % kGroups, rl = tid / kGroups;
+    int group = 0;
     for (int n_claimed = 0;; ++n_claimed) {
-        const int p = claim_sample(counter, n_claimed, &slot);   // also: the previous sample's statistics have been read
+        const int p = claim_sample<(D <= 32 ? 2 : 1)>(counter, n_claimed, &slot, group);   // also: the previous sample's statistics have been read
         if (p >= B) break;
         const int b = p;
         const int64_t row0 = offsets[b];
