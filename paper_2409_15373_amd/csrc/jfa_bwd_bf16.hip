@@ -193,7 +193,7 @@ __global__ __launch_bounds__(kBwdThreads, 2) void dq_bf16_kernel(const __bf16 *_
 // delta, are the rows of offsets_q.  CAUSAL: key j is seen by queries j .. L - 1: the stream starts at the stage that
 // holds the tile's first key, and streamed rows below the lane's key get P = 0.
 template <int D, bool CROSS, bool CAUSAL>
-__global__ __launch_bounds__(kBwdThreads, 1) void dkv_bf16_kernel(const __bf16 *__restrict__ q,
+__global__ __launch_bounds__(kBwdThreads, D <= 64 ? 2 : 1) void dkv_bf16_kernel(const __bf16 *__restrict__ q,
                                                                   const __bf16 *__restrict__ k,
                                                                   const __bf16 *__restrict__ v,
                                                                   const __bf16 *__restrict__ dout,
