@@ -285,10 +285,6 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
         if (e != hipSuccess) return hip_fail("fp32 backward kernels", e);
         return JFA_OK;
     }
-    if (!dma) {   // the direct-to-LDS dQ kernel computes the row statistics itself
-        { ScopedTimer tm("delta", s); e = jfa::launch_delta(out, dout, lse, offsets, (int)B, H, D, true, delta, w.cus, s); }
-        if (e != hipSuccess) return hip_fail("delta kernel", e);
-    }
     if (dma) {
         static const char *const names[3] = {"dq_bf16_dma", "dk_bf16_dma", "dv_bf16_dma"};
         void *const grads[3] = {dq, dk, dv};
@@ -302,10 +298,11 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
     }
     jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
     jfa::Schedule s_dkv{w.order[kv], w.tile_start[kv], w.counters + jfa::kXcds};
+    // the dQ kernel goes first: it computes delta = rowsum(dO o O) for its own rows and leaves it for the dK / dV kernel
+    { ScopedTimer tm("dq_bf16", s); e = jfa::launch_dq_bf16(q, k, v, out, dout, lse, delta, offsets, offsets_kv, causal, (int)B, H, D, s_dq, dq, w.cus, s); }
+    if (e != hipSuccess) return hip_fail("bf16 dQ kernel", e);
     { ScopedTimer tm("dkv_bf16", s); e = jfa::launch_dkv_bf16(q, k, v, dout, lse, delta, offsets_k, offsets_q_other, causal, (int)B, H, D, s_dkv, dk, dv, w.cus, s); }
     if (e != hipSuccess) return hip_fail("bf16 dK/dV kernel", e);
-    { ScopedTimer tm("dq_bf16", s); e = jfa::launch_dq_bf16(q, k, v, dout, lse, delta, offsets, offsets_kv, causal, (int)B, H, D, s_dq, dq, w.cus, s); }
-    if (e != hipSuccess) return hip_fail("bf16 dQ kernel", e);
     return JFA_OK;
 }
 

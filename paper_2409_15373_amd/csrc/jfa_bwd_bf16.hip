@@ -82,7 +82,8 @@ __global__ __launch_bounds__(kBwdThreads, 2) void dq_bf16_kernel(const __bf16 *_
                                                                  const __bf16 *__restrict__ v,
                                                                  const __bf16 *__restrict__ dout,
                                                                  const float *__restrict__ lse,
-                                                                 const float *__restrict__ delta,
+                                                                 const __bf16 *__restrict__ out_fwd,   // see delta
+                                                                 float *delta,
                                                                  const int64_t *__restrict__ offsets,
                                                                  const int64_t *__restrict__ offsets_kv, int B, int H,
                                                                  Schedule s, __bf16 *__restrict__ dq) {
@@ -125,7 +126,24 @@ __global__ __launch_bounds__(kBwdThreads, 2) void dq_bf16_kernel(const __bf16 *_
             }
         }
         const float lse2 = lse[(int64_t)t.head * sum_B + t.row0 + iq] * 1.4426950408889634f;
-        const float delta_i = delta[(int64_t)t.head * sum_B + t.row0 + iq];
+        // delta = rowsum(dO o O) of this lane's query.  With out_fwd given this kernel is the first of the backward and
+        // computes it from the dO row it holds (each lane of a pair has half of the row), leaving it in `delta` for the
+        // dK / dV kernel; otherwise an earlier kernel has filled `delta`.
+        float delta_i;
+        if (out_fwd != nullptr) {
+            const int64_t off = (t.row0 + iq) * row_stride + (int64_t)t.head * D + 8 * half;
+            float dot = 0.0f;
+#pragma unroll
+            for (int ks = 0; ks < kKSteps; ++ks) {
+                const bf16x8 o = *reinterpret_cast<const bf16x8 *>(out_fwd + off + 16 * ks);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dot = fmaf((float)o[e], (float)doreg[ks][e], dot);
+            }
+            delta_i = pair_sum(dot);
+            if (i < Lq && half == 0) delta[(int64_t)t.head * sum_B + t.row0 + i] = delta_i;
+        } else {
+            delta_i = delta[(int64_t)t.head * sum_B + t.row0 + iq];
+        }
 
         f32x16 acc[kDBlocks];
 #pragma unroll
@@ -345,14 +363,14 @@ hipError_t launch_dkv_bf16(const void *q, const void *k, const void *v, const vo
     return hipGetLastError();
 }
 
-hipError_t launch_dq_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
-                          const float *delta, const int64_t *offsets, const int64_t *offsets_kv, bool causal, int B, int H,
+hipError_t launch_dq_bf16(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
+                          float *delta, const int64_t *offsets, const int64_t *offsets_kv, bool causal, int B, int H,
                           int D, Schedule s, void *dq, int cus, hipStream_t stream) {
     if (causal && offsets_kv) return hipErrorInvalidValue;
 #define JFA_LAUNCH(DD, CROSS, CAUSAL)                                                                            \
     hipLaunchKernelGGL((dq_bf16_kernel<DD, CROSS, CAUSAL>), dim3(persistent_grid<dq_bf16_kernel<DD, CROSS, CAUSAL>>(kBwdThreads, cus)), \
                        dim3(kBwdThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, lse, \
-                       delta, offsets, offsets_kv, B, H, s, (__bf16 *)dq)
+                       (const __bf16 *)out, delta, offsets, offsets_kv, B, H, s, (__bf16 *)dq)
 #define JFA_CASE(DD)                                                                                             \
     case DD:                                                                                                     \
         if (offsets_kv) JFA_LAUNCH(DD, true, false);                                                             \

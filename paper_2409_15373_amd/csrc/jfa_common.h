@@ -351,8 +351,10 @@ hipError_t launch_fwd_bf16(const void *q, const void *k, const void *v, const in
 hipError_t launch_dkv_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
                            const float *delta, const int64_t *offsets, const int64_t *offsets_q, bool causal, int B, int H,
                            int D, Schedule s, void *dk, void *dv, int cus, hipStream_t stream);
-hipError_t launch_dq_bf16(const void *q, const void *k, const void *v, const void *dout, const float *lse,
-                          const float *delta, const int64_t *offsets, const int64_t *offsets_kv, bool causal, int B, int H,
+// out != nullptr: the kernel computes delta = rowsum(dO o O) itself and stores it in `delta` (launch it before the
+// dK / dV kernel); out == nullptr: `delta` has been filled before.
+hipError_t launch_dq_bf16(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
+                          float *delta, const int64_t *offsets, const int64_t *offsets_kv, bool causal, int B, int H,
                           int D, Schedule s, void *dq, int cus, hipStream_t stream);
 
 // bf16 attention, direct-to-LDS kernels (D = 128, long samples; work items are blocks of kDmaBlockRows rows)
