@@ -84,21 +84,32 @@ __global__ __launch_bounds__(kFoThreads) void jagged_dense_bmm_kernel(const __bf
             for (int c = tid; c < D * (T / 8); c += kFoThreads)
                 *reinterpret_cast<u32x4 *>(wt + (c / (T / 8)) * kWRow + (c % (T / 8)) * 16) = wsrc[c];
         }
+        // A block of x is rows * D * 2 contiguous bytes; rows past the sample's end become zeros.  The next block is
+        // fetched into registers while the current one is multiplied.
+        constexpr int kChunks = kFoRows * (D / 8) / kFoThreads;   // 16-byte chunks of a block per thread
+        u32x4 xv[kChunks];
+        auto fetch = [&](int r0) {
+            const int rows = L - r0 < kFoRows ? L - r0 : kFoRows;
+            const u32x4 *src = reinterpret_cast<const u32x4 *>(x + (row0 + r0) * D);
+#pragma unroll
+            for (int u = 0; u < kChunks; ++u) {
+                const int c = tid + kFoThreads * u;
+                xv[u] = u32x4{0, 0, 0, 0};
+                if (c / (D / 8) < rows) xv[u] = src[c];
+            }
+        };
+        fetch(0);
         for (int r0 = 0; r0 < L; r0 += kFoRows) {
             if (r0) __syncthreads();   // every wave is done with the previous block's region
             const int rows = L - r0 < kFoRows ? L - r0 : kFoRows;
-            {   // the block of x is rows * D * 2 contiguous bytes; rows past the sample's end become zeros
-                const u32x4 *src = reinterpret_cast<const u32x4 *>(x + (row0 + r0) * D);
 #pragma unroll
-                for (int u = 0; u < kFoRows * (D / 8) / kFoThreads; ++u) {
-                    const int c = tid + kFoThreads * u, r = c / (D / 8), ch = c % (D / 8);
-                    u32x4 v = {0, 0, 0, 0};
-                    if (r < rows) v = src[c];
-                    char *dst = xt + (r >> 5) * kRegion + (r & 31) * kXRow + ch * 16;
-                    *reinterpret_cast<u32x2 *>(dst) = u32x2{v[0], v[1]};
-                    *reinterpret_cast<u32x2 *>(dst + 8) = u32x2{v[2], v[3]};
-                }
+            for (int u = 0; u < kChunks; ++u) {
+                const int c = tid + kFoThreads * u, r = c / (D / 8), ch = c % (D / 8);
+                char *dst = xt + (r >> 5) * kRegion + (r & 31) * kXRow + ch * 16;
+                *reinterpret_cast<u32x2 *>(dst) = u32x2{xv[u][0], xv[u][1]};
+                *reinterpret_cast<u32x2 *>(dst + 8) = u32x2{xv[u][2], xv[u][3]};
             }
+            if (r0 + kFoRows < L) fetch(r0 + kFoRows);
             __syncthreads();
             if (wave * 32 >= rows) continue;
             f32x16 acc[kTBlocks];
