@@ -469,7 +469,7 @@ __global__ __launch_bounds__(kUfThreads) void unfused_softmax_bwd_kernel(const f
 // consecutive j of one row (two rows per instruction), straight from memory into operand position.  x goes
 // through LDS as [i][feature], shared by the four waves; the next block is in flight during the products.
 template <int D>
-__global__ __launch_bounds__(kUfThreads) void unfused_apply_t_kernel(const float *__restrict__ X,
+__global__ __launch_bounds__(kUfThreads, 2) void unfused_apply_t_kernel(const float *__restrict__ X,
                                                                      const __bf16 *__restrict__ x,
                                                                      const int64_t *__restrict__ offsets,
                                                                      const int64_t *__restrict__ sq, int B, int H,
