@@ -12,7 +12,8 @@
   P7  closed forms: equal keys or zero queries give the mean of V and lse = S + ln L
   P8  shift invariance and gradient identities
   P9  central finite differences of sum(out * dO)
-  P10 large scores stay finite
+  P10 large scores stay finite; a row whose scores are all far below zero keeps its softmax (the maximum is
+      subtracted before the exponentials, not zero)
   P11 rows past offsets[B] are never read
 """
 import numpy as np
@@ -254,6 +255,36 @@ def test_p10_large_scores_are_stable(oracle):
     np.testing.assert_allclose(lse, ref_lse, rtol=1e-12)
     dq, dk, dv, _ = oracle.backward(q, w.k, w.v, w.dout, w.offsets)
     assert all(np.isfinite(g).all() for g in (dq, dk, dv))
+
+
+def test_p10b_rows_with_only_very_negative_scores(oracle):
+    """Every score of every row lies below -800 (queries are positive multiples of one direction, keys negative
+    multiples of it): exp(score) underflows to zero in fp64, so the softmax only exists if the row maximum is
+    subtracted first.  Expected values from scipy's logsumexp / softmax on the same fp64 scores."""
+    from scipy.special import logsumexp, softmax
+    rng = np.random.default_rng(41)
+    lengths, H, D = [7, 1, 4], 2, 8
+    off = offsets_from_lengths(np.asarray(lengths))
+    n = int(off[-1])
+    u = rng.standard_normal((H, D)).astype(np.float32)
+    a = rng.uniform(20.0, 30.0, size=(n, H, 1)).astype(np.float32)
+    b = rng.uniform(20.0, 30.0, size=(n, H, 1)).astype(np.float32)
+    q = (a * u[None]).astype(np.float32)
+    k = (-b * u[None]).astype(np.float32)
+    v = rng.standard_normal((n, H, D)).astype(np.float32)
+    dout = rng.standard_normal((n, H, D)).astype(np.float32)
+    out, lse = oracle.forward(q, k, v, off)
+    dq, dk, dv, _ = oracle.backward(q, k, v, dout, off)
+    assert all(np.isfinite(x).all() for x in (out, lse, dq, dk, dv))
+    for bidx, L in enumerate(lengths):
+        s = int(off[bidx])
+        for h in range(H):
+            S = q[s:s + L, h].astype(np.float64) @ k[s:s + L, h].astype(np.float64).T / np.sqrt(D)
+            assert S.max() < -800.0
+            np.testing.assert_allclose(lse[h, s:s + L], logsumexp(S, axis=1), rtol=1e-13)
+            P = softmax(S, axis=1)
+            np.testing.assert_allclose(out[s:s + L, h], P @ v[s:s + L, h].astype(np.float64), rtol=1e-10, atol=1e-12)
+            np.testing.assert_allclose(dv[s:s + L, h], P.T @ dout[s:s + L, h].astype(np.float64), rtol=1e-10, atol=1e-12)
 
 
 def test_p11_rows_past_the_last_offset_are_ignored(oracle):
