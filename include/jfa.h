@@ -71,9 +71,9 @@ int jfa_forward_f32(const float *q, const float *k, const float *v, const int64_
  * Backward, bf16 (Section 2.2 states that every jagged operator has a backward).
  * Inputs: q, k, v as in the forward; out and lse as produced by jfa_forward; dout bf16 [sum_B, H, D].
  * Outputs: dq, dk, dv bf16 [sum_B, H, D]; delta fp32 [2, H, sum_B], a caller-provided buffer that the call
- * fills and then reads: plane 0 is rowsum(dout * out) (an output), plane 1 is -lse * log2(e), minus the log-sum-exp
- * in the base-2 scale in which the kernels take exponentials (scratch).  These two planes are the only
- * sum_B-sized scratch of the backward.
+ * fills and then reads: plane 0 is rowsum(dout * out) (an output), plane 1 is -lse * sqrt(D), minus the log-sum-exp
+ * in units of the unscaled dot product q.k, the value the kernels' score accumulators start from (scratch).  These two
+ * planes are the only sum_B-sized scratch of the backward.
  */
 int jfa_backward(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
                  const int64_t *offsets, int64_t B, int64_t max_len, int H, int D, void *dq, void *dk, void *dv,

@@ -13,7 +13,7 @@ from typing import Optional, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.environ.get("JFA_LIB") or os.path.join(_HERE, "libjfa.so")   # JFA_LIB: load another build of the same ABI
+LIB_PATH = os.path.join(_HERE, "libjfa.so")
 _lib = None
 
 JFA_OK = 0

@@ -132,18 +132,10 @@ void drop_timed() {
     g_timed.clear();
 }
 
-// Forward variant: the direct-to-LDS kernel for long samples at D = 128, the register-staged one otherwise;
-// JFA_FWD_VARIANT=dma / narrow forces one of them where both apply (for side-by-side measurements).
+// Forward variant: the direct-to-LDS kernel for long samples at D = 128, the register-staged one otherwise.
 enum FwdVariant { kNarrow = 0, kDma = 2 };
 FwdVariant forward_variant(int64_t max_len, int D, int H) {
-    static const int forced = [] {
-        const char *v = getenv("JFA_FWD_VARIANT");
-        if (v && !strcmp(v, "dma")) return (int)kDma;
-        if (v && !strcmp(v, "narrow")) return (int)kNarrow;
-        return -1;
-    }();
     if (D != 128 || (int64_t)H * D > (1 << 20)) return kNarrow;   // the direct-to-LDS kernels keep 32-bit row offsets
-    if (forced >= 0) return (FwdVariant)forced;
     return max_len > 256 ? kDma : kNarrow;   // 256-query tiles only pay off when samples can be long
 }
 

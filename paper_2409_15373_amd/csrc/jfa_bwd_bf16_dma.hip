@@ -81,9 +81,10 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
     __shared__ __attribute__((aligned(256))) char S0[512];   // per stage: lse[64], delta[64] of the streamed rows
     __shared__ __attribute__((aligned(256))) char S1[512];
     __shared__ __attribute__((aligned(256))) char S2[512];
-    // dQ only: per lane, four copies each of minus the base-2 lse and minus delta of the lane's query.  The score
-    // and dP accumulators of every block start from these (four 16-byte LDS reads each, no VALU work, no registers
-    // held across the stage): P = exp2(acc) and dS = P * acc then cost one exponential and one multiply.
+    // dQ only: per lane, four copies each of minus lse * sqrt(D) (the log-sum-exp in units of the raw dot product) and
+    // minus delta of the lane's query.  The score and dP accumulators of every block start from these (four 16-byte
+    // LDS reads each, no VALU work, no registers held across the stage): P = exp2(c * acc) with c = log2(e) / sqrt(D)
+    // applied in fp32, and dS = P * acc.
     __shared__ float4 lane_init[MODE == kModeDQ ? kBdThreads * 2 : 1];
     __shared__ WorkSlot slot;   // the NEXT work item, claimed and decoded while the current one starts up
     __shared__ LdsSchedule<CROSS> tab;   // the schedule, copied once per workgroup when it fits
@@ -114,7 +115,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
     // streamed rows of the sample, first stage and number of stages (causal tiles need only a part of the sample).
     struct Stream {
         const __bf16 *abase, *bbase;
-        const float *delta_rows, *lse2_rows;   // plane 0 of the statistics buffer: delta; plane 1: -lse * log2(e)
+        const float *delta_rows, *lse2_rows;   // plane 0 of the statistics buffer: delta; plane 1: -lse * sqrt(D)
         int L, Lc, js, n_stages;
     };
     auto stream_of = [&](const Work &w) {
@@ -273,7 +274,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             f32x16 sc, dp;
 #pragma unroll
             for (int e = 0; e < 16; ++e) { sc[e] = 0.0f; dp[e] = 0.0f; }
-            if (kRowStats) {   // score accumulator starts at minus the streamed rows' base-2 lse: P = exp2(acc), no FMA
+            if (kRowStats) {   // the dot products start at minus the streamed rows' lse * sqrt(D): P = exp2(c * acc)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     const float4 l4 = *reinterpret_cast<const float4 *>(St + (mb * 32 + g * 8 + half * 4) * 4);
@@ -323,7 +324,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             for (int g = 0; g < 4; ++g) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    float p = fast_exp2(sc[4 * g + e]);
+                    float p = fast_exp2(sc[4 * g + e] * c);   // the scale is applied in fp32: operands stay exact
                     const int r = j0 + mb * 32 + g * 8 + half * 4 + e;   // this register's streamed row
                     if (ragged && (r >= (CAUSAL && !kRowStats && ic + 1 < L ? ic + 1 : L) || (CAUSAL && kRowStats && r < ic)))
                         p = 0.0f;   // past the sample's end, or on the wrong side of the diagonal
@@ -402,7 +403,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             }
         }
         if (!kRowStats) {
-            // This lane's query's statistics: minus the base-2 lse and minus delta = rowsum(dO o O).  With out_fwd given,
+            // This lane's query's statistics: minus lse * sqrt(D) and minus delta = rowsum(dO o O).  With out_fwd given,
             // this kernel is the first of the backward and computes them itself from the rows it holds (each lane of
             // a pair has half of the row), leaving both planes of the statistics buffer for the dK and dV kernels;
             // otherwise an earlier kernel has filled the buffer.
@@ -417,7 +418,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                     for (int e = 0; e < 8; ++e) dot = fmaf((float)o[e], (float)yreg[ks][e], dot);
                 }
                 dot = pair_sum(dot);
-                nl = -lse[(int64_t)t.head * sum_B + t.row0 + ic] * 1.4426950408889634f;
+                nl = -lse[(int64_t)t.head * sum_B + t.row0 + ic] * sqrtf((float)D);
                 nd = -dot;
                 if (i < Ls && half == 0) {
                     delta[(int64_t)t.head * sum_B + t.row0 + i] = dot;
@@ -431,12 +432,6 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             mine[0] = make_float4(nl, nl, nl, nl);          // conflicts; written and read by the same lane: no barrier
             mine[64] = make_float4(nd, nd, nd, nd);
         }
-        // The softmax scale and the change to base-2 exponentials go into the stationary operand of the score
-        // product once per tile (x * log2(e) / sqrt(D), rounded to bf16 again): scores then only need v_exp_f32.
-#pragma unroll
-        for (int ks = 0; ks < kKSteps; ++ks)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) xreg[ks][e] = (__bf16)((float)xreg[ks][e] * c);
         // The first stage has landed once at most one stage's loads are outstanding: what this wave sent after it is
         // the second stage (and, on wave 0, the loads of the claim, which it has waited for itself).
         if (n_stages - js > 1) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);

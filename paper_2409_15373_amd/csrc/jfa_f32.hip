@@ -222,9 +222,9 @@ __global__ __launch_bounds__(kThreads) void dkv_f32_kernel(const float *__restri
 }
 
 // delta[h, row] = sum_d dout[row, h, d] * out[row, h, d]; one group of D*sizeof(T)/16 lanes per (row, head).
-// With lse != nullptr the second plane of the buffer, delta[H + h, row], receives -lse[h, row] * log2(e): minus
-// the log-sum-exp in the base-2 scale of the bf16 backward kernels' exponentials, the value their score
-// accumulators start from.
+// With lse != nullptr the second plane of the buffer, delta[H + h, row], receives -lse[h, row] * sqrt(D): minus
+// the log-sum-exp in units of the unscaled dot product, the value the score accumulators of the direct-to-LDS
+// backward kernels start from.
 template <bool kBf16>
 __global__ __launch_bounds__(256) void delta_kernel(const void *__restrict__ out, const void *__restrict__ dout,
                                                     const float *__restrict__ lse,
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(256) void delta_kernel(const void *__restrict__ out
             const int h = (int)(pair - row * H);
             delta[(int64_t)h * sum_B + row] = acc;
             if (lse != nullptr)
-                delta[(int64_t)(H + h) * sum_B + row] = -lse[(int64_t)h * sum_B + row] * 1.4426950408889634f;
+                delta[(int64_t)(H + h) * sum_B + row] = -lse[(int64_t)h * sum_B + row] * sqrtf((float)D);
         }
     }
 }

@@ -232,15 +232,19 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         };
         // exponentials of one unit (32 keys x 32 queries) against the reference maximum; the rounded
         // probabilities are what the second product uses, so they are what the row sum adds up
-        auto exps = [&](const f32x16 &st, float sub, bf16x8 (&p)[2]) {   // sub = 0 in the fast order (folded away)
+        // st holds raw dot products (minus the raw reference in the fast order, whose subc is the constant 0); the
+        // softmax scale and the change to base-2 exponentials are one fp32 multiply-add per score
+        auto exps = [&](const f32x16 &st, auto FAST, float subc, bf16x8 (&p)[2]) {
+            constexpr bool kFast = decltype(FAST)::value != 0;
 #pragma unroll
             for (int ts = 0; ts < 2; ++ts) {
                 u32x4 pw;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     bf16x2 pr;
-                    pr[0] = (__bf16)fast_exp2(st[8 * ts + 2 * e] - sub);
-                    pr[1] = (__bf16)fast_exp2(st[8 * ts + 2 * e + 1] - sub);
+                    const float x0 = st[8 * ts + 2 * e], x1 = st[8 * ts + 2 * e + 1];
+                    pr[0] = (__bf16)fast_exp2(kFast ? x0 * c : fmaf(x0, c, -subc));
+                    pr[1] = (__bf16)fast_exp2(kFast ? x1 * c : fmaf(x1, c, -subc));
                     lsum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, lsum, false);
                     pw[e] = __builtin_bit_cast(uint32_t, pr);
                 }
@@ -271,7 +275,7 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             const char *const Vc = P == 0 ? V0 : (P == 1 ? V1 : V2);
             int kaddr[kKSteps], vaddr[kDBlocks];
             lds_addresses(kaddr, vaddr);
-            f32x16 s0 = negm, s1 = negm;   // the score accumulators start at minus the reference: no subtraction later
+            f32x16 s0 = negm, s1 = negm;   // the dot products start at minus the (raw) reference: no subtraction later
             bf16x8 p0[2], p1[2];
             {
                 bf16x8 ka[kKSteps], kb[kKSteps];
@@ -294,10 +298,10 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
                 __builtin_amdgcn_sched_group_barrier(0x008, kKSteps, 0);
             }
             if (kRagged) mask(s0, j * kDmaBN);
-            exps(s0, 0.0f, p0);                        // ... VALU: exponentials of key block 0
+            exps(s0, IntC<1>{}, 0.0f, p0);             // ... VALU: exponentials of key block 0
             accumulate(Vc, 0, p0, vaddr);              // matrix pipe: O^T += V^T P^T of key block 0 ...
             if (kRagged) mask(s1, j * kDmaBN + 32);
-            exps(s1, 0.0f, p1);                        // ... VALU: exponentials of key block 1
+            exps(s1, IntC<1>{}, 0.0f, p1);             // ... VALU: exponentials of key block 1
             accumulate(Vc, 1, p1, vaddr);
         };
         // conservative(): maximum first, rescale, then exponentials; used when a tile had to be restarted
@@ -313,16 +317,16 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             if (CAUSAL || (j + 1) * kDmaBN > L) { mask(s0, j * kDmaBN); mask(s1, j * kDmaBN + 32); }
             const float x = pair_max(unit_max(s1, unit_max(s0, -INFINITY)));
             const float n = fmaxf(m, x);
-            const float a = fast_exp2(m - n);   // 0 on the first stage
+            const float a = fast_exp2((m - n) * c);   // 0 on the first stage
             m = n;
             lsum *= a;
 #pragma unroll
             for (int db = 0; db < kDBlocks; ++db)
 #pragma unroll
                 for (int e = 0; e < 16; ++e) o[db][e] *= a;
-            exps(s0, n, p0);
+            exps(s0, IntC<0>{}, n * c, p0);
             accumulate(Vc, 0, p0, vaddr);
-            exps(s1, n, p1);
+            exps(s1, IntC<0>{}, n * c, p1);
             accumulate(Vc, 1, p1, vaddr);
         };
 
@@ -361,12 +365,6 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
         if (wave == 0) claim_next();   // overlaps with the loads in flight
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) asm volatile("" : "+v"(qreg[ks]));   // Q loads complete here
-        // The softmax scale and the change to base-2 exponentials go into Q once per tile (q * log2(e) / sqrt(D),
-        // rounded to bf16 again): the matrix product then delivers scores that only need v_exp_f32.
-#pragma unroll
-        for (int ks = 0; ks < kKSteps; ++ks)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) qreg[ks][e] = (__bf16)((float)qreg[ks][e] * c);
         // Stage 0 has landed once at most one stage's loads are outstanding: what this wave sent after it is stage 1
         // (and, on wave 0, the loads of the claim, which it has waited for itself).
         if (n_stages > 1) __builtin_amdgcn_s_waitcnt(0x0070 | kDmaOpsPerStage); else __builtin_amdgcn_s_waitcnt(0x0070);
@@ -469,7 +467,7 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             }
         }
         if (i < Lq && half == 0)
-            lse[(int64_t)t.head * sum_B + t.row0 + i] = (m + fast_log2(l_total)) * 0.6931471805599453f;
+            lse[(int64_t)t.head * sum_B + t.row0 + i] = (m * c + fast_log2(l_total)) * 0.6931471805599453f;
         t = nt;
         have = have_next;
     }

@@ -57,3 +57,23 @@ def gate_f32(name, got, ref, tol=1e-5, relative_to_one=False):
     m = float(err.max())
     assert m <= tol, f"{name}: max err {m:.3e} > {tol}"
     return m
+
+
+GUARD = 777.0
+
+
+def sentinel_like(t: torch.Tensor, n_valid: int) -> torch.Tensor:
+    """An output buffer shaped like t: NaN in the first n_valid rows (every one of them has to be written by the
+    call under test, so a work item that is never claimed or is decoded to the wrong place shows up in an isfinite
+    check over the whole tensor) and GUARD in the rows after them (which must stay untouched)."""
+    x = torch.full_like(t, float("nan"))
+    x[n_valid:] = GUARD
+    return x
+
+
+def sentinel_stats(shape) -> torch.Tensor:
+    return torch.full(shape, float("nan"), dtype=torch.float32, device="cuda")
+
+
+def assert_guard_rows_untouched(name, t: torch.Tensor, n_valid: int):
+    assert (t[n_valid:] == GUARD).all(), f"guard rows of {name} were written"

@@ -110,9 +110,14 @@ def test_causal_full_size_on_sampled_pairs():
     from paper_2409_15373_amd.synthetic import make_workload
     w = make_workload("c4_bimodal_bf16", with_dout=True)
     d = to_device(w)
-    out, lse = binding.jfa_forward(d["q"], d["k"], d["v"], d["offsets"], w.max_len, causal=True)
-    dq, dk, dv, _ = binding.jfa_backward(d["q"], d["k"], d["v"], out, d["dout"], lse, d["offsets"], w.max_len, causal=True)
+    nan_like = lambda t: torch.full_like(t, float("nan"))   # every row has to be written: an unwritten tile stays NaN
+    out, lse = binding.jfa_forward(d["q"], d["k"], d["v"], d["offsets"], w.max_len, causal=True, out=nan_like(d["q"]),
+                                   lse=torch.full((w.H, w.sum_B), float("nan"), dtype=torch.float32, device="cuda"))
+    dq, dk, dv, _ = binding.jfa_backward(d["q"], d["k"], d["v"], out, d["dout"], lse, d["offsets"], w.max_len, causal=True,
+                                         dq=nan_like(d["q"]), dk=nan_like(d["q"]), dv=nan_like(d["q"]))
     torch.cuda.synchronize()
+    for name, t in (("out", out), ("lse", lse), ("dq", dq), ("dk", dk), ("dv", dv)):
+        assert torch.isfinite(t.float()).all(), f"{name}: rows that were never written (or not finite)"
     order = np.argsort(w.lengths)
     rng = np.random.default_rng(6)
     picks = [(int(order[-1]), 0), (int(order[0]), w.H - 1), (int(order[len(order) // 2]), 1)]

@@ -162,12 +162,19 @@ def test_cross_full_size_on_sampled_pairs():
     host, dev, oq, ok = make(Lq, Lk, H, D, "bf16", 8)
     oqd, okd = torch.from_numpy(oq).cuda(), torch.from_numpy(ok).cuda()
     nq, nk = int(oq[-1]), int(ok[-1])
-    lse = torch.empty((H, nq), dtype=torch.float32, device="cuda")
-    out, _ = binding.jfa_forward_cross(dev["q"], dev["k"], dev["v"], oqd, okd, c["max_len"], c["max_len"], lse=lse)
+    nan = float("nan")   # every valid row has to be written (all samples have queries and keys): unwritten tiles stay NaN
+    lse = torch.full((H, nq), nan, dtype=torch.float32, device="cuda")
+    out = torch.full((nq, H, D), nan, dtype=torch.bfloat16, device="cuda")
+    binding.jfa_forward_cross(dev["q"], dev["k"], dev["v"], oqd, okd, c["max_len"], c["max_len"], out=out, lse=lse)
     stats = torch.empty((2, H, nq), dtype=torch.float32, device="cuda")
-    dq, dk, dv, _ = binding.jfa_backward_cross(dev["q"], dev["k"], dev["v"], out, dev["dout"], lse, oqd, okd, c["max_len"],
-                                               c["max_len"], delta=stats)
+    dq = torch.full((nq, H, D), nan, dtype=torch.bfloat16, device="cuda")
+    dk = torch.full((nk, H, D), nan, dtype=torch.bfloat16, device="cuda")
+    dv = torch.full((nk, H, D), nan, dtype=torch.bfloat16, device="cuda")
+    binding.jfa_backward_cross(dev["q"], dev["k"], dev["v"], out, dev["dout"], lse, oqd, okd, c["max_len"],
+                               c["max_len"], dq=dq, dk=dk, dv=dv, delta=stats)
     torch.cuda.synchronize()
+    for name, t in (("out", out), ("lse", lse), ("dq", dq), ("dk", dk), ("dv", dv)):
+        assert torch.isfinite(t.float()).all(), f"{name}: rows that were never written (or not finite)"
     rng = np.random.default_rng(9)
     picks = [(int(np.argmax(Lq * Lk)), 0), (int(np.argmax(Lk)), H - 1), (int(np.argmax(Lq)), 1)]
     picks += [(int(rng.integers(0, len(Lq))), int(rng.integers(0, H))) for _ in range(5)]
