@@ -33,9 +33,7 @@ def scaled(name, got, ref):
     gate_bf16(name, got, ref, abs_tol=2e-2 * max(1.0, float(np.abs(ref).max()) / 2))
 
 
-@pytest.mark.parametrize("seed", range(12))
-def test_random_self_and_causal(oracle, seed):
-    from paper_2409_15373_amd import binding
+def self_case(seed):
     rng = np.random.default_rng(1000 + seed)
     B, H, D = int(rng.integers(1, 13)), int(rng.integers(1, 5)), int(rng.choice([32, 64, 128]))
     cap = 256 if seed % 2 else 700                      # max_len <= 256 keeps D = 128 on the register-staged kernels
@@ -43,8 +41,45 @@ def test_random_self_and_causal(oracle, seed):
     off = offsets_from_lengths(L); n = int(off[-1])
     if n == 0:
         L[0] = 5; off = offsets_from_lengths(L); n = int(off[-1])
+    tensors = [bf16_tensor(rng, n, H, D, 1.0) for _ in range(4)]
+    return B, H, D, cap, L, off, n, tensors
+
+
+# Seeds of a one-off sweep over seeds 12 .. 331 (640 self / causal runs, 320 cross runs) that end outside the relative
+# gate against the exact oracle: (seed, causal, tensor, measured max error / max |oracle|).  In both, a sample of two
+# rows holds the tensor's largest error: dS = P o (dP - delta) is a small difference of large numbers there (|delta|
+# 6 .. 14) and delta is formed, as the interface defines it, from the bf16 forward output: in fp64 arithmetic with that
+# one substitution (oracle/given_out.py) the gradients are already 1.1 % and 1.3 .. 1.7 % of the maximum away.
+KNOWN_OUTSIDE = [(165, False, "dq", 1.17e-2), (324, True, "dk", 1.35e-2)]
+
+
+@pytest.mark.parametrize("seed,is_causal,tensor,measured", KNOWN_OUTSIDE)
+def test_known_cases_outside_the_gate_are_inherited_from_the_bf16_output(oracle, seed, is_causal, tensor, measured):
+    """Against the backward evaluated in fp64 from the SAME bf16 forward output (what any implementation of the
+    interface is given) the standard gate holds; against the exact oracle the error stays below twice the gate."""
+    from oracle import given_out
+    from paper_2409_15373_amd import binding
+    B, H, D, cap, L, off, n, ((q, qd), (k, kd), (v, vd), (do, dod)) = self_case(seed)
     offd = torch.from_numpy(off).cuda()
-    (q, qd), (k, kd), (v, vd), (do, dod) = (bf16_tensor(rng, n, H, D, s) for s in (1.0, 1.0, 1.0, 1.0))
+    lse = torch.empty((H, n), dtype=torch.float32, device="cuda")
+    stats = torch.empty((2, H, n), dtype=torch.float32, device="cuda")
+    out, _ = binding.jfa_forward(qd, kd, vd, offd, cap, lse=lse, causal=is_causal)
+    dq, dk, dv, _ = binding.jfa_backward(qd, kd, vd, out, dod, lse, offd, cap, delta=stats, causal=is_causal)
+    torch.cuda.synchronize()
+    g_dq, g_dk, g_dv, _ = given_out.backward(q, k, v, f64(out), do, off, causal=is_causal)
+    scaled("dq vs fp64 from the same out", f64(dq), g_dq)
+    scaled("dk vs fp64 from the same out", f64(dk), g_dk)
+    scaled("dv vs fp64 from the same out", f64(dv), g_dv)
+    exact = causal_oracle.backward(q, k, v, do, off) if is_causal else oracle.backward(q, k, v, do, off)
+    for name, got, ref in (("dq", dq, exact[0]), ("dk", dk, exact[1]), ("dv", dv, exact[2])):
+        gate_bf16(name + " vs the exact oracle", f64(got), ref, abs_tol=2e-2 * max(1.0, float(np.abs(ref).max()) / 2), rel_tol=2e-2)
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_self_and_causal(oracle, seed):
+    from paper_2409_15373_amd import binding
+    B, H, D, cap, L, off, n, ((q, qd), (k, kd), (v, vd), (do, dod)) = self_case(seed)
+    offd = torch.from_numpy(off).cuda()
     for is_causal in (False, True):
         lse = torch.empty((H, n), dtype=torch.float32, device="cuda")
         stats = torch.empty((2, H, n), dtype=torch.float32, device="cuda")
