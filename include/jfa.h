@@ -63,6 +63,23 @@ typedef enum {
 int jfa_forward(const void *q, const void *k, const void *v, const int64_t *offsets, int64_t B, int64_t max_len,
                 int H, int D, void *out, float *lse, void *stream);
 
+/*
+ * jfa_forward for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, kernels and results (bit for bit) as jfa_forward, but the private
+ * work table (64 counters and two schedules, 8 (B + 33) bytes up to alignment) lives in a fixed array in device
+ * memory instead of a table allocated per (device, stream): about 1 MiB that every GPU the library runs on holds
+ * until the process ends.  The call allocates and frees nothing and does not synchronise; the array's address is
+ * looked up once per device, on the first call made with that device current.
+ *   B > JFA_NOALLOC_MAX_B returns JFA_ERR_UNSUPPORTED (nothing is launched).
+ *   All calls on one GPU share the one array: calls that overlap in time on a GPU (two streams, two threads) race
+ *   on it and give undefined results; calls that follow each other on one stream are safe (each call's scheduler
+ *   kernel rewrites the counters and the schedule it uses before its attention kernel reads them).
+ *   jfa_timing_enable has no effect on this call (timing events would have to be created).
+ */
+#define JFA_NOALLOC_MAX_B 65536
+int jfa_forward_noalloc(const void *q, const void *k, const void *v, const int64_t *offsets, int64_t B,
+                        int64_t max_len, int H, int D, void *out, float *lse, void *stream);
+
 /* Forward, fp32 end to end (same operation; plain FMA arithmetic, for small-tolerance use). */
 int jfa_forward_f32(const float *q, const float *k, const float *v, const int64_t *offsets, int64_t B,
                     int64_t max_len, int H, int D, float *out, float *lse, void *stream);

@@ -30,7 +30,7 @@ EXPORTS = (
     "jfa_jagged_softmax", "jfa_jagged_softmax_backward", "jfa_forward_cross", "jfa_forward_cross_f32",
     "jfa_backward_cross", "jfa_backward_cross_f32", "jfa_forward_causal", "jfa_forward_causal_f32",
     "jfa_backward_causal", "jfa_backward_causal_f32", "jfa_unfused_product", "jfa_unfused_softmax_backward",
-    "jfa_unfused_apply_transposed",
+    "jfa_unfused_apply_transposed", "jfa_forward_noalloc",
 )
 
 
@@ -54,6 +54,8 @@ def load() -> ctypes.CDLL:
     lib.jfa_forward.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, vp]
     lib.jfa_forward_f32.restype = i32
     lib.jfa_forward_f32.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, vp]
+    lib.jfa_forward_noalloc.restype = i32
+    lib.jfa_forward_noalloc.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, vp]
     lib.jfa_backward.restype = i32
     lib.jfa_backward.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.jfa_backward_f32.restype = i32
@@ -156,6 +158,17 @@ def jfa_forward(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, offsets: torc
     fn = _pick(q.dtype, "jfa_forward_causal" if causal else "jfa_forward")
     _check(fn(_ptr(q), _ptr(k), _ptr(v), _ptr(offsets), B, max_len, H, D, _ptr(out), _ptr(lse), _stream()))
     return out, lse
+
+
+def jfa_forward_noalloc(q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, offsets: torch.Tensor, max_len: int,
+                        out: torch.Tensor, lse: torch.Tensor) -> None:
+    """jfa_forward (bf16) with the library's work table in a fixed device array: the call allocates nothing, so `out`
+    [sum_B, H, D] and `lse` fp32 [H, sum_B] have to be given.  At most JFA_NOALLOC_MAX_B samples; calls that overlap
+    on one GPU race on the shared table."""
+    _, H, D = q.shape
+    assert q.dtype == torch.bfloat16 and k.dtype == q.dtype and v.dtype == q.dtype
+    _check(load().jfa_forward_noalloc(_ptr(q), _ptr(k), _ptr(v), _ptr(offsets), offsets.numel() - 1, max_len, H, D,
+                                      _ptr(out), _ptr(lse), _stream()))
 
 
 def jfa_backward(q, k, v, out, dout, lse, offsets, max_len: int, dq=None, dk=None, dv=None, delta=None,

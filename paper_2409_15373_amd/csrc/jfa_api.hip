@@ -33,9 +33,9 @@ std::mutex g_mu;
 std::map<std::pair<int, hipStream_t>, Table> g_tables;
 std::map<int, int> g_cu_count;
 
-size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
-size_t sched_bytes(int64_t B) { return align_up((size_t)(2 * B + 1) * sizeof(int32_t), 256); }
-size_t table_bytes(int64_t B) { return (size_t)jfa::kNumCounters * sizeof(int32_t) + 2 * sched_bytes(B); }
+constexpr size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+constexpr size_t sched_bytes(int64_t B) { return align_up((size_t)(2 * B + 1) * sizeof(int32_t), 256); }
+constexpr size_t table_bytes(int64_t B) { return (size_t)jfa::kNumCounters * sizeof(int32_t) + 2 * sched_bytes(B); }
 
 struct Views {
     int32_t *counters;
@@ -43,6 +43,17 @@ struct Views {
     int32_t *tile_start[2];
     int cus;
 };
+
+// [counters][order 0, tile_start 0][order 1, tile_start 1] for a batch of B samples, from `base` on
+void lay_out(char *base, int64_t B, Views *v) {
+    v->counters = (int32_t *)base;
+    char *p = base + (size_t)jfa::kNumCounters * sizeof(int32_t);
+    for (int i = 0; i < 2; ++i) {
+        v->order[i] = (int32_t *)p;
+        v->tile_start[i] = v->order[i] + B;
+        p += sched_bytes(B);
+    }
+}
 
 int get_table(int64_t B, hipStream_t stream, Views *v) {
     int dev = 0;
@@ -74,14 +85,42 @@ int get_table(int64_t B, hipStream_t stream, Views *v) {
         t.bytes = need;
     }
     // Views are laid out for the table's capacity in bytes, not for this call's B: recompute from B.
-    v->counters = (int32_t *)t.base;
-    char *p = t.base + (size_t)jfa::kNumCounters * sizeof(int32_t);
-    for (int i = 0; i < 2; ++i) {
-        v->order[i] = (int32_t *)p;
-        v->tile_start[i] = v->order[i] + B;
-        p += sched_bytes(B);
-    }
+    lay_out(t.base, B, v);
     v->cus = cu->second;
+    return JFA_OK;
+}
+
+// ---- the work table of jfa_forward_noalloc: a fixed array in device memory, one copy per GPU ----
+// In host code the array's name is only a handle for hipGetSymbolAddress; every use of its memory goes through the
+// per-device pointer obtained from that call.
+constexpr size_t kScratchBytes = table_bytes(JFA_NOALLOC_MAX_B);
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+struct StaticTable {
+    char *ptr = nullptr;   // device address of `scratch` on this device
+    int cus = 0;
+};
+StaticTable g_static[kMaxDevices];
+
+int get_static_table(int64_t B, Views *v) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(JFA_ERR_HIP, "hipGetDevice: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(JFA_ERR_UNSUPPORTED, "device index %d is beyond the %d this call keeps a table for", dev, kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_mu);
+    StaticTable &t = g_static[dev];
+    if (!t.ptr) {   // first call on this device (which is current): ask for this device's copy of the array
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(JFA_ERR_HIP, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+        int n = 0;
+        e = hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess || n <= 0) return fail(JFA_ERR_HIP, "cannot read the compute-unit count: %s", hipGetErrorString(e));
+        t.cus = n;
+        t.ptr = (char *)p;
+    }
+    lay_out(t.ptr, B, v);
+    v->cus = t.cus;
     return JFA_OK;
 }
 
@@ -107,6 +146,7 @@ struct TimedLaunch {
     hipEvent_t e0, e1;
 };
 thread_local bool g_timing = false;
+thread_local bool g_timing_suppressed = false;   // inside jfa_forward_noalloc: creating events would allocate
 thread_local std::vector<TimedLaunch> g_timed;
 
 // Brackets one kernel launch with events when timing is on; a no-op otherwise.
@@ -114,7 +154,7 @@ struct ScopedTimer {
     TimedLaunch t{nullptr, nullptr, nullptr};
     hipStream_t stream;
     ScopedTimer(const char *name, hipStream_t s) : stream(s) {
-        if (!g_timing) return;
+        if (!g_timing || g_timing_suppressed) return;
         if (hipEventCreate(&t.e0) != hipSuccess) return;
         if (hipEventCreate(&t.e1) != hipSuccess) { (void)hipEventDestroy(t.e0); return; }
         t.name = name;
@@ -228,13 +268,13 @@ hipError_t schedule(const int64_t *offsets, const int64_t *offsets_other, int64_
 
 int forward_impl(const char *who, bool f32, bool causal, const void *q, const void *k, const void *v, const int64_t *offsets,
                  const int64_t *offsets_kv, int64_t B, int64_t max_len, int64_t max_len_kv, int H, int D, void *out,
-                 float *lse, hipStream_t s) {
+                 float *lse, hipStream_t s, bool static_table = false) {
     const void *ptrs[] = {q, k, v, offsets, out, lse};
     int st = check_common(who, B, max_len, H, D, ptrs, 6);
     if (st != JFA_OK || B == 0) return st;
     if (max_len_kv < 0) return fail(JFA_ERR_INVALID_ARG, "%s: max_len_kv = %lld is negative", who, (long long)max_len_kv);
     Views w;
-    if ((st = get_table(B, s, &w)) != JFA_OK) return st;
+    if ((st = static_table ? get_static_table(B, &w) : get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
     const FwdVariant variant = f32 ? kNarrow : forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H);
     e = schedule(offsets, offsets_kv, B, f32 ? jfa::kF32BlockRows : (variant == kNarrow ? jfa::kFwdBlockRows : jfa::kDmaBlockRows), w, 0, s);
@@ -321,6 +361,18 @@ int jfa_backward_f32(const float *q, const float *k, const float *v, const float
 int jfa_forward(const void *q, const void *k, const void *v, const int64_t *offsets, int64_t B, int64_t max_len,
                 int H, int D, void *out, float *lse, void *stream) {
     return forward_impl("jfa_forward", false, false, q, k, v, offsets, nullptr, B, max_len, max_len, H, D, out, lse, (hipStream_t)stream);
+}
+
+int jfa_forward_noalloc(const void *q, const void *k, const void *v, const int64_t *offsets, int64_t B, int64_t max_len,
+                        int H, int D, void *out, float *lse, void *stream) {
+    if (B > JFA_NOALLOC_MAX_B)
+        return fail(JFA_ERR_UNSUPPORTED, "jfa_forward_noalloc: B = %lld exceeds JFA_NOALLOC_MAX_B = %d, the batch the fixed work table holds",
+                    (long long)B, JFA_NOALLOC_MAX_B);
+    g_timing_suppressed = true;
+    const int st = forward_impl("jfa_forward_noalloc", false, false, q, k, v, offsets, nullptr, B, max_len, max_len, H, D, out, lse,
+                                (hipStream_t)stream, true);
+    g_timing_suppressed = false;
+    return st;
 }
 
 int jfa_backward(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
