@@ -14,6 +14,8 @@ Prints ONE JSON line:
   roofline        the kernel with the longest average launch, timed with HIP events on the launch
                   stream inside the timed region; kernels lists all of them
   cpu_baseline    the fp64 oracle timed on this host's cores on a bounded sample of the same workload
+  all_configs     after the timed region: us per call (forward, forward + backward), useful TFLOP/s, % of peak and the
+                  largest errors against the oracle for each of the five configurations
 """
 import argparse
 import json
@@ -39,6 +41,7 @@ def main():
     ap.add_argument("--workload", default="c4_bimodal_bf16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--forward-only", action="store_true", help="time the forward call alone (diagnostic)")
+    ap.add_argument("--no-all-configs", action="store_true", help="skip the per-configuration block (timings and errors of all five)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy kernel (reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -168,7 +171,125 @@ def main():
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, args.forward_only)
+    if not args.no_all_configs:
+        del q, k, v, dout, out, lse, dq, dk, dv, delta
+        torch.cuda.empty_cache()
+        result["all_configs"] = all_configs(w)
     print(json.dumps(result), flush=True)
+
+
+def all_configs(w_timed):
+    """After the timed region: every one of the five configurations on its seeded inputs -- microseconds per call of
+    the forward and of forward + backward (median of 3 timings of >= 20 ms each after 5 warm-up calls; a call is
+    everything the entry point enqueues), useful TFLOP/s and % of the bf16 MFMA peak, cache-cold figures for the two
+    whose tensors fit in the Infinity Cache (calls rotate over > 512 MB of copies), and the largest error against the
+    oracle per tensor (max |gpu - oracle| and that over max |oracle|): whole tensors for c1 and c2, sampled
+    (sample, head) pairs -- longest, shortest, median and random ones -- for the others."""
+    import statistics
+
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2409_15373_amd import binding
+    from paper_2409_15373_amd.synthetic import CONFIGS, make_workload
+
+    def timed_us(fn, n):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(n):
+            fn(i)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e3 / n
+
+    def median_us(fn):
+        for i in range(5):
+            fn(i)
+        torch.cuda.synchronize()
+        n = max(3, int(20e3 / max(timed_us(fn, 3), 1e-3)) + 1)
+        return statistics.median(timed_us(fn, n) for _ in range(3))
+
+    res = {}
+    for name in CONFIGS:
+        w = w_timed if name == w_timed.name else make_workload(name, with_dout=True)
+        is_bf16 = w.dtype == "bf16"
+        H, D, n = w.H, w.D, w.sum_B
+
+        def up(t):
+            if is_bf16:
+                return torch.from_numpy(w.bits[t].view(np.int16)).view(torch.bfloat16).cuda()
+            return torch.from_numpy(getattr(w, t)).cuda()
+
+        base = {t: up(t) for t in ("q", "k", "v", "dout")}
+        footprint = 8 * base["q"].numel() * base["q"].element_size()
+        copies = 1 if footprint >= 256e6 else int(512e6 // footprint) + 2
+        x = {t: base[t].unsqueeze(0).repeat(copies, 1, 1, 1) for t in base}
+        y = {t: torch.empty_like(x["q"]) for t in ("out", "dq", "dk", "dv")}
+        planes = 2 if is_bf16 else 1
+        stride = (planes * H * n + 63) // 64 * 64          # statistics blocks start on 256-byte boundaries
+        lse_flat = torch.empty(copies * stride, device="cuda")
+        st_flat = torch.empty(copies * stride, device="cuda")
+        lse = [lse_flat[j * stride: j * stride + H * n].view(H, n) for j in range(copies)]
+        stats = [st_flat[j * stride: j * stride + planes * H * n].view(planes, H, n) for j in range(copies)]
+        off = torch.from_numpy(w.offsets).cuda()
+
+        def fwd(i, m=1):
+            j = i % m
+            binding.jfa_forward(x["q"][j], x["k"][j], x["v"][j], off, w.max_len, out=y["out"][j], lse=lse[j])
+
+        def step(i, m=1):
+            j = i % m
+            fwd(i, m)
+            binding.jfa_backward(x["q"][j], x["k"][j], x["v"][j], y["out"][j], x["dout"][j], lse[j], off, w.max_len,
+                                 dq=y["dq"][j], dk=y["dk"][j], dv=y["dv"][j], delta=stats[j])
+
+        unit = H * D * float(w.S2)
+        r = {"B": w.B, "H": H, "D": D, "max_len": w.max_len, "dtype": w.dtype, "sum_B": n, "S2": w.S2}
+        for tag, fn, flops in (("fwd", fwd, 4 * unit), ("fwd_bwd", step, 14 * unit)):
+            us = median_us(lambda i: fn(i, 1))
+            r["us_" + tag] = round(us, 2)
+            r["useful_tflops_" + tag] = round(flops / us / 1e6, 3)
+            if is_bf16:
+                r["pct_bf16_mfma_peak_" + tag] = round(100 * flops / us / 1e6 / PEAK_BF16_TFLOPS, 2)
+            if copies > 1:
+                r["us_" + tag + "_cache_cold"] = round(median_us(lambda i: fn(i, copies)), 2)
+        # errors against the oracle on copy 0 (step(0) above left every output of that copy in place)
+        step(0)
+        torch.cuda.synchronize()
+        if n * H <= 40000:
+            pairs, rows, heads = None, slice(None), slice(None)
+            r["error_sample"] = "whole tensors"
+        else:
+            order = np.argsort(w.lengths)
+            rng = np.random.default_rng(3)
+            picks = {(int(order[-1]), 0), (int(order[0]), H - 1), (int(order[len(order) // 2]), 1 % H)}
+            while len(picks) < 12:
+                picks.add((int(rng.integers(0, w.B)), int(rng.integers(0, H))))
+            pairs = sorted(picks)
+            rows = np.concatenate([np.arange(w.offsets[b], w.offsets[b + 1]) for b, _ in pairs])
+            heads = np.concatenate([np.full(int(w.lengths[b]), h) for b, h in pairs])
+            r["error_sample"] = f"{len(pairs)} (sample, head) pairs, lengths {int(min(w.lengths[b] for b, _ in pairs))}..{int(max(w.lengths[b] for b, _ in pairs))}"
+        ref_out, ref_lse = oracle.forward(w.q, w.k, w.v, w.offsets, pairs=pairs)
+        rdq, rdk, rdv, _ = oracle.backward(w.q, w.k, w.v, w.dout, w.offsets, pairs=pairs)
+        g = lambda t: t.double().cpu().numpy()
+
+        def err(got, ref, per_head_first=False):
+            if pairs is None:
+                a, b = got, ref
+            elif per_head_first:
+                a, b = got[heads, rows], ref[heads, rows]
+            else:
+                a, b = got[rows, heads], ref[rows, heads]
+            e = float(np.abs(a - b).max())
+            return {"max_abs_err": float(f"{e:.3e}"), "max_rel_err": float(f"{e / max(float(np.abs(b).max()), 1e-30):.3e}")}
+
+        r["errors"] = {"out": err(g(y["out"][0]), ref_out), "lse": err(g(lse[0]), ref_lse, True),
+                       "dq": err(g(y["dq"][0]), rdq), "dk": err(g(y["dk"][0]), rdk), "dv": err(g(y["dv"][0]), rdv)}
+        res[name] = r
+        print(f"[bench] {name}: fwd {r['us_fwd']} us, fwd+bwd {r['us_fwd_bwd']} us, out err {r['errors']['out']}", file=sys.stderr, flush=True)
+        del x, y, base, lse, stats, lse_flat, st_flat
+        torch.cuda.empty_cache()
+    return res
 
 
 def recorded_traffic(workload, kernel):

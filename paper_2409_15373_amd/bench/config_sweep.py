@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Microseconds per call and useful TFLOP/s of the forward and of forward + backward on all five configurations.
 
-    python -m paper_2409_15373_amd.config_sweep [--configs c1_tiny_f32,...] [--repeats 5]
+    python -m paper_2409_15373_amd.bench.config_sweep [--configs c1_tiny_f32,...] [--repeats 5]
 
 Per configuration: >= 10 warm-up calls, then the median over `repeats` timings of N back-to-back calls on one
 stream bracketed by HIP events (N chosen so that one timing lasts >= 50 ms).  A call is everything the entry point
@@ -48,8 +48,8 @@ def main():
     ap.add_argument("--repeats", type=int, default=5)
     args = ap.parse_args()
     import torch
-    from . import binding
-    from .synthetic import CONFIGS, lengths_for, offsets_from_lengths
+    from .. import binding
+    from ..synthetic import CONFIGS, lengths_for, offsets_from_lengths
     binding.load()
     assert torch.cuda.is_available(), "needs the GPU"
     result = {"data": "synthetic", "peak_bf16_TFLOP_per_s": PEAK_TFLOPS, "configs": {}}

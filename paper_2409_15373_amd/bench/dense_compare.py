@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Jagged versus padded-dense attention on the same GPU and the same kernels.
 
-    python -m paper_2409_15373_amd.dense_compare [--workloads c2_geom_bf16,c3_zipf_bf16,...] [--reps N]
+    python -m paper_2409_15373_amd.bench.dense_compare [--workloads c2_geom_bf16,c3_zipf_bf16,...] [--reps N]
 
 The paper's Section 3 / Figure 2 compares jagged flash attention with dense flash attention on padded
 tensors as a function of the maximum length.  The comparison systems themselves are not available here, so
@@ -37,8 +37,8 @@ def _time(fn, reps):
 
 def _run(lengths, H, D, sigma, max_len, reps):
     import torch
-    from . import binding
-    from .synthetic import offsets_from_lengths
+    from .. import binding
+    from ..synthetic import offsets_from_lengths
     n = int(lengths.sum())
     off = torch.from_numpy(offsets_from_lengths(lengths)).cuda()
     gen = torch.Generator(device="cuda").manual_seed(0)
@@ -56,8 +56,8 @@ def _run(lengths, H, D, sigma, max_len, reps):
 
 def _conversions(lengths, H, D, max_len, reps):
     import torch
-    from . import binding
-    from .synthetic import offsets_from_lengths
+    from .. import binding
+    from ..synthetic import offsets_from_lengths
     n, B = int(lengths.sum()), len(lengths)
     off = torch.from_numpy(offsets_from_lengths(lengths)).cuda()
     x = torch.randn(n, H, D, device="cuda").bfloat16()
@@ -77,8 +77,8 @@ def main():
     ap.add_argument("--reps", type=int, default=5)
     args = ap.parse_args()
     import torch
-    from . import binding
-    from .synthetic import CONFIGS, lengths_for
+    from .. import binding
+    from ..synthetic import CONFIGS, lengths_for
     binding.load()
     assert torch.cuda.is_available(), "needs the GPU"
     result = {"comparison": "jagged vs padded-dense (every sample stretched to max_len) on the same kernels",

@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Timing of the jagged feature operators of the paper's Table 1 against the HBM roofline.
 
-    python -m paper_2409_15373_amd.feature_ops_bench [--B 16384] [--max-len 512] [--D 64] [--T 64] [--reps 10]
+    python -m paper_2409_15373_amd.bench.feature_ops_bench [--B 16384] [--max-len 512] [--D 64] [--T 64] [--reps 10]
 
 Lengths are uniform on [1, max_len] (Table 1's jagged versions do about half the padded work, i.e. a mean length
 of about max_len / 2), values random normals drawn on the device.  For every operator it reports microseconds per
@@ -24,8 +24,8 @@ def main():
     ap.add_argument("--reps", type=int, default=10)
     args = ap.parse_args()
     import torch
-    from . import binding
-    from .synthetic import lengths_for, offsets_from_lengths
+    from .. import binding
+    from ..synthetic import lengths_for, offsets_from_lengths
     binding.load()
     assert torch.cuda.is_available(), "needs the GPU"
     B, N, D, T = args.B, args.max_len, args.D, args.T

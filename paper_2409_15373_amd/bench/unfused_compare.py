@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Fused jagged flash attention versus the unfused jagged attention, forward and backward, on the same GPU.
 
-    python -m paper_2409_15373_amd.unfused_compare [--workloads c2_geom_bf16,c3_zipf_bf16,...] [--reps N]
+    python -m paper_2409_15373_amd.bench.unfused_compare [--workloads c2_geom_bf16,c3_zipf_bf16,...] [--reps N]
 
 The paper's Section 3 compares the fused kernel with "jagged attention": the three jagged operators of its
 Table 1 run one after another, with the L_b x L_b score blocks of every sample and head written to memory
@@ -41,8 +41,8 @@ def main():
     ap.add_argument("--reps", type=int, default=5)
     args = ap.parse_args()
     import torch
-    from . import binding
-    from .synthetic import CONFIGS, lengths_for, offsets_from_lengths
+    from .. import binding
+    from ..synthetic import CONFIGS, lengths_for, offsets_from_lengths
     binding.load()
     assert torch.cuda.is_available(), "needs the GPU"
     result = {"comparison": "fused jagged flash attention vs unfused jagged attention (scores, softmax, apply and their backward operators)",

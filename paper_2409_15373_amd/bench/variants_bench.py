@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Timing of the cross and causal variants of jagged attention against the bf16 MFMA roofline.
 
-    python -m paper_2409_15373_amd.variants_bench [--reps N]
+    python -m paper_2409_15373_amd.bench.variants_bench [--reps N]
 
 The paper's feature interaction attends from a sample's target items to its feature values: few queries, many
 keys.  Two synthetic workloads with B = 512, H = 8, D = 128 and the keys' lengths of the benchmarked self-attention
@@ -37,8 +37,8 @@ def main():
     ap.add_argument("--reps", type=int, default=5)
     args = ap.parse_args()
     import torch
-    from . import binding
-    from .synthetic import CONFIGS, lengths_for, offsets_from_lengths
+    from .. import binding
+    from ..synthetic import CONFIGS, lengths_for, offsets_from_lengths
     binding.load()
     assert torch.cuda.is_available(), "needs the GPU"
     c = CONFIGS["c4_bimodal_bf16"]
