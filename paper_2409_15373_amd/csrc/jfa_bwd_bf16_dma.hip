@@ -14,38 +14,9 @@
 // whose other operand is the transposing LDS read of a streamed tile.  Keeping dK and dV in separate kernels
 // costs one more recomputation of S but lets each of them run two waves per SIMD (their accumulators together
 // need the whole register file), and nothing is accumulated with atomics: results are deterministic.
-#include "jfa_common.h"
-#include "jfa_mfma.h"
+#include "jfa_bwd_dma.h"
 
 namespace jfa {
-
-constexpr int kBdThreads = 512;
-constexpr int kBdBN = 64;             // streamed rows per LDS stage
-constexpr int kBdD = 128;
-constexpr int kBdTile = kBdBN * kBdD * 2;
-
-enum BwdMode { kModeDQ = 0, kModeDK = 1, kModeDV = 2 };
-
-template <int N> using IntB = std::integral_constant<int, N>;
-
-// Row r, 16-byte chunk ch of a streamed tile sits at r * 256 + ((ch ^ swz(r)) << 4): conflict-free for the
-// 16-byte row reads (16 consecutive rows hit 16 different chunk columns) and for the transposing reads
-// (4 consecutive rows hit 4 different 64-byte groups) on the 64-bank LDS.
-__device__ inline int swz(int r) { return ((r & 3) << 2) | ((r >> 2) & 3); }
-
-// Global -> LDS copies of 16 (or 4) bytes per lane: source = `base` (wave-uniform, scalar registers) +
-// `byte_offset` (per lane, unsigned 32 bits), destination = lds_wave_base + 16 (or 4) * lane.  The scalar-base
-// form needs no 64-bit vector address arithmetic and no vector registers for addresses.
-__device__ inline void bd_dma16(const void *base, uint32_t byte_offset, char *lds_wave_base) {
-    const char *src = reinterpret_cast<const char *>(base) + byte_offset;
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                     (__attribute__((address_space(3))) void *)lds_wave_base, 16, 0, 0);
-}
-__device__ inline void bd_dma4(const void *base, uint32_t byte_offset, char *lds_wave_base) {
-    const char *src = reinterpret_cast<const char *>(base) + byte_offset;
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                     (__attribute__((address_space(3))) void *)lds_wave_base, 4, 0, 0);
-}
 
 // CROSS (cross attention): `offsets` belongs to the stationary rows (queries for dQ, keys for dK and dV) and
 // offsets_other to the rows that stream past them; otherwise offsets_other is not looked at.

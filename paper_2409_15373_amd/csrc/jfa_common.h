@@ -369,6 +369,13 @@ hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const voi
                                const int64_t *offsets_other, bool causal, int B, int H, int D, Schedule s, void *grad,
                                int cus, hipStream_t stream);
 
+// dK and dV of self attention in one kernel (pairs of waves share 32 keys; work items are blocks of kDkvBlockRows keys);
+// `stats` is the [2, H, sum_B] buffer the dQ launch has filled.
+constexpr int kDkvBlockRows = 128;
+hipError_t launch_bwd_dkv_dma(const void *q, const void *k, const void *v, const void *dout, const float *stats,
+                              const int64_t *offsets, int B, int H, int D, Schedule s, void *dk, void *dv, int cus,
+                              hipStream_t stream);
+
 // Unfused jagged attention (Table 1): offsets of the jagged square array, then the three operators.
 hipError_t launch_square_offsets(const int64_t *offsets, int B, int64_t *sq, hipStream_t stream);
 hipError_t launch_unfused_scores(const void *q, const void *k, const int64_t *offsets, const int64_t *sq, int B, int H,
