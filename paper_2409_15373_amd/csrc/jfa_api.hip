@@ -179,6 +179,15 @@ FwdVariant forward_variant(int64_t max_len, int D, int H) {
     return max_len > 256 ? kDma : kNarrow;   // 256-query tiles only pay off when samples can be long
 }
 
+// Small problems skip the scheduler launch: the attention kernels build the schedule themselves and deal the work
+// statically (see build_schedule_in_kernel).  max_len bounds every sample's length, so B * blocks(max_len) * H bounds
+// the number of work items; at most four per workgroup is the size up to which static dealing is used anyway.
+bool small_problem(int64_t B, int64_t max_len, int H, int block_rows, int cus) {
+    if (B > jfa::kInlineCap) return false;
+    const int64_t blocks = (max_len + block_rows - 1) / block_rows;
+    return B * (blocks > 0 ? blocks : 1) * (int64_t)H <= 4 * (int64_t)cus;
+}
+
 int hip_fail(const char *what, hipError_t e) { return fail(JFA_ERR_HIP, "%s: %s", what, hipGetErrorString(e)); }
 
 }  // namespace
@@ -277,9 +286,15 @@ int forward_impl(const char *who, bool f32, bool causal, const void *q, const vo
     if ((st = static_table ? get_static_table(B, &w) : get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
     const FwdVariant variant = f32 ? kNarrow : forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H);
-    e = schedule(offsets, offsets_kv, B, f32 ? jfa::kF32BlockRows : (variant == kNarrow ? jfa::kFwdBlockRows : jfa::kDmaBlockRows), w, 0, s);
-    if (e != hipSuccess) return hip_fail("schedule kernel", e);
+    const int block_rows = f32 ? jfa::kF32BlockRows : (variant == kNarrow ? jfa::kFwdBlockRows : jfa::kDmaBlockRows);
     jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
+    if (variant == kNarrow && small_problem(B, max_len, H, block_rows, w.cus)) {
+        sc.build_rows = block_rows;
+        sc.static_only = true;
+    } else {
+        e = schedule(offsets, offsets_kv, B, block_rows, w, 0, s);
+        if (e != hipSuccess) return hip_fail("schedule kernel", e);
+    }
     if (f32) { ScopedTimer tm("fwd_f32", s); e = jfa::launch_fwd_f32((const float *)q, (const float *)k, (const float *)v, offsets, offsets_kv, causal, (int)B, H, D, sc, (float *)out, lse, w.cus, s); }
     else if (variant == kDma) { ScopedTimer tm("fwd_bf16_dma", s); e = jfa::launch_fwd_bf16_dma(q, k, v, offsets, offsets_kv, causal, (int)B, H, D, sc, out, lse, w.cus, s); }
     else { ScopedTimer tm("fwd_bf16", s); e = jfa::launch_fwd_bf16(q, k, v, offsets, offsets_kv, causal, (int)B, H, D, sc, out, lse, w.cus, s); }
@@ -301,16 +316,25 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
     const bool dma = !f32 && D == 128 && forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H) != kNarrow;
     const int block_rows = f32 ? jfa::kF32BlockRows : (dma ? jfa::kDmaBlockRows : jfa::kBwdBlockRows);
     // Schedule 0: blocks of queries.  Schedule 1: blocks of keys, only different from schedule 0 for cross attention.
-    // Both launches clear all work counters, and both run before the first kernel that uses one.
-    e = schedule(offsets, offsets_kv, B, block_rows, w, 0, s);
-    if (e == hipSuccess && offsets_kv) e = schedule(offsets_kv, offsets, B, block_rows, w, 1, s);
-    if (e != hipSuccess) return hip_fail("schedule kernel", e);
+    // Both launches clear all work counters, and both run before the first kernel that uses one.  Small problems on
+    // the register-staged and fp32 kernels have no scheduler launch: those kernels build their schedule themselves.
+    const bool in_kernel = !dma && small_problem(B, max_len > max_len_kv ? max_len : max_len_kv, H, block_rows, w.cus);
+    if (!in_kernel) {
+        e = schedule(offsets, offsets_kv, B, block_rows, w, 0, s);
+        if (e == hipSuccess && offsets_kv) e = schedule(offsets_kv, offsets, B, block_rows, w, 1, s);
+        if (e != hipSuccess) return hip_fail("schedule kernel", e);
+    }
     const int kv = offsets_kv ? 1 : 0;
     const int64_t *const offsets_k = offsets_kv ? offsets_kv : offsets;   // the keys' offsets
     const int64_t *const offsets_q_other = offsets_kv ? offsets : nullptr;   // the queries', as the second array of dK / dV
     if (f32) {
         jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
         jfa::Schedule s_dkv{w.order[kv], w.tile_start[kv], w.counters + jfa::kXcds};
+        if (in_kernel) {   // the dQ kernel runs first and builds schedule 0; dK / dV build their own only when it differs (cross attention)
+            s_dq.static_only = s_dkv.static_only = true;
+            s_dq.build_rows = block_rows;
+            s_dkv.build_rows = kv ? block_rows : 0;
+        }
         ScopedTimer tm_bwd("bwd_f32", s);
         e = jfa::launch_bwd_f32((const float *)q, (const float *)k, (const float *)v, (const float *)out, (const float *)dout, lse,
                                 offsets, offsets_kv, causal, (int)B, H, D, s_dq, s_dkv, (float *)dq, (float *)dk, (float *)dv, delta, w.cus, s);
@@ -342,6 +366,11 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
     }
     jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
     jfa::Schedule s_dkv{w.order[kv], w.tile_start[kv], w.counters + jfa::kXcds};
+    if (in_kernel) {   // the dQ kernel runs first and builds schedule 0; dK / dV build their own only when it differs (cross attention)
+        s_dq.static_only = s_dkv.static_only = true;
+        s_dq.build_rows = block_rows;
+        s_dkv.build_rows = kv ? block_rows : 0;
+    }
     // the dQ kernel goes first: it computes delta = rowsum(dO o O) for its own rows and leaves it for the dK / dV kernel
     { ScopedTimer tm("dq_bf16", s); e = jfa::launch_dq_bf16(q, k, v, out, dout, lse, delta, offsets, offsets_kv, causal, (int)B, H, D, s_dq, dq, w.cus, s); }
     if (e != hipSuccess) return hip_fail("bf16 dQ kernel", e);

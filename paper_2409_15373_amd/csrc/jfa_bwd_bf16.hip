@@ -94,11 +94,16 @@ __global__ __launch_bounds__(kBwdThreads, 2) void dq_bf16_kernel(const __bf16 *_
     const int col = lane & 31, half = lane >> 5;
     const float scale = 1.0f / sqrtf((float)D);
     const float c = 1.4426950408889634f * scale;
+    static_assert(sizeof(Smem) >= kInlineScratchInts * sizeof(int), "the stage buffers double as the scheduler's scratch");
+    if (s.build_rows)   // small problem: no scheduler launch has run
+        build_schedule_in_kernel(offsets, CROSS ? offsets_kv : nullptr, B, s.build_rows, const_cast<int32_t *>(s.order),
+                                 const_cast<int32_t *>(s.tile_start), reinterpret_cast<int *>(&sm));
     const int64_t total = (int64_t)s.tile_start[B] * H;
     const int64_t sum_B = offsets[B];
     const int64_t row_stride = (int64_t)H * D;
 
     WorkCursor cursor;
+    cursor.static_only = s.static_only;
     for (;;) {
         __syncthreads();
         if (tid == 0) sm.slot = next_work(s.counter, cursor, total);
@@ -228,11 +233,16 @@ __global__ __launch_bounds__(kBwdThreads, D <= 64 ? 2 : 1) void dkv_bf16_kernel(
     const int col = lane & 31, half = lane >> 5;
     const float scale = 1.0f / sqrtf((float)D);
     const float c = 1.4426950408889634f * scale;
+    static_assert(sizeof(Smem) >= kInlineScratchInts * sizeof(int), "the stage buffers double as the scheduler's scratch");
+    if (s.build_rows)   // small problem: no scheduler launch has run
+        build_schedule_in_kernel(offsets, CROSS ? offsets_q : nullptr, B, s.build_rows, const_cast<int32_t *>(s.order),
+                                 const_cast<int32_t *>(s.tile_start), reinterpret_cast<int *>(&sm));
     const int64_t total = (int64_t)s.tile_start[B] * H;
     const int64_t sum_B = CROSS ? offsets_q[B] : offsets[B];   // lse and delta are indexed by query rows
     const int64_t row_stride = (int64_t)H * D;
 
     WorkCursor cursor;
+    cursor.static_only = s.static_only;
     for (;;) {
         __syncthreads();
         if (tid == 0) sm.slot = next_work(s.counter, cursor, total);

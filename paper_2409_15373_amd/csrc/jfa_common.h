@@ -16,6 +16,12 @@ struct Schedule {
     const int32_t *order;       // [B]
     const int32_t *tile_start;  // [B+1]
     int32_t *counter;           // kXcds zeroed work counters (one queue per XCD), bumped by the persistent workgroups
+    // Small problems (see build_schedule_in_kernel) run without a scheduler launch: the counters are then not valid
+    // and work is dealt statically (static_only); build_rows > 0 tells the kernel to fill order / tile_start itself for
+    // row blocks of that many rows, 0 that they are filled already (by the scheduler kernel, or by an earlier
+    // attention kernel of the same call that uses the same schedule).
+    int build_rows = 0;
+    bool static_only = false;
 };
 
 // The chip has 8 accelerator dies (XCDs), each with its own L2, and workgroups are dealt to them round-robin
@@ -35,6 +41,7 @@ __device__ inline int64_t work_id(int y, int t) {
 struct WorkCursor {
     bool first = true;
     bool home_done = false;
+    bool static_only = false;   // the counters are not valid (schedule built in the kernel): deal statically whatever the size
     int64_t next = -1;   // small problems: next statically assigned id
     int grid = 0;        // gridDim.x, read once: the dispatch packet it comes from is a slow place to read
 };
@@ -60,7 +67,7 @@ __device__ inline int64_t next_work(int32_t *counters, WorkCursor &cur, int64_t 
     // Small problems (at most four items per workgroup) are dealt round-robin with no atomics at all: the
     // items are sorted longest-first, so the deal is even, and the claim traffic would dominate the run time.
     const int grid = cursor_grid(cur);
-    if (total <= 4 * (int64_t)grid) {
+    if (cur.static_only || total <= 4 * (int64_t)grid) {
         cur.next = cur.next < 0 ? blockIdx.x : cur.next + grid;
         return cur.next < total ? cur.next : -1;
     }
@@ -162,6 +169,98 @@ __device__ inline Work decode_work(const Schedule &s, const int64_t *offsets, in
         t.olen = (int)(offsets_other[t.sample + 1] - t.orow0);
     }
     return t;
+}
+
+// The schedule of a small problem, built inside the attention kernel instead of by a launch of its own (a launch and
+// the scheduler kernel's chain of dependent trips to memory cost more than these problems' whole arithmetic).  Every
+// workgroup computes the same schedule -- samples in descending order of their stream's block count, equal counts in
+// sample order, so the result does not depend on who computes it -- and writes it to the same global arrays: every
+// location receives one value only, the same from every writer, so whichever copy a later read meets is right; the
+// barrier at the end makes the workgroup's own writes visible to all its waves.  Lengths are fetched once, by all
+// threads at once, into LDS; one wave then runs a counting sort over at most kInlineBins keys, in which the ranks
+// inside a bin come from ballots, and a scan of the block counts in sorted order.
+// `scratch`: kInlineScratchInts ints of LDS that nothing else uses until the call returns (the kernels lend a stage
+// buffer).  Called by every thread of the workgroup; B <= kInlineCap.
+constexpr int kInlineCap = 1024;
+constexpr int kInlineBins = 64;
+constexpr int kInlineScratchInts = 2 * kInlineBins + kInlineCap + kInlineCap / 4 + kInlineCap / 2;   // 7.5 KB
+__device__ inline void build_schedule_in_kernel(const int64_t *offsets, const int64_t *offsets_other, int B, int block_rows,
+                                                int32_t *order, int32_t *tile_start, int *scratch) {
+    int *const bins = scratch;                                    // [kInlineBins] counts, then [kInlineBins] next free positions
+    int *const nblk = scratch + 2 * kInlineBins;                  // [kInlineCap] row blocks of sample b
+    uint8_t *const keys = reinterpret_cast<uint8_t *>(nblk + kInlineCap);               // [kInlineCap] sort key of sample b
+    uint16_t *const sorted = reinterpret_cast<uint16_t *>(nblk + kInlineCap + kInlineCap / 4);   // [kInlineCap] sample at position p
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+        const int64_t len = offsets[b + 1] - offsets[b];
+        const int64_t stream = offsets_other ? offsets_other[b + 1] - offsets_other[b] : len;
+        const int64_t key = (stream + block_rows - 1) / block_rows;
+        nblk[b] = (int)((len + block_rows - 1) / block_rows);
+        keys[b] = (uint8_t)(key < kInlineBins - 1 ? key : kInlineBins - 1);
+    }
+    if (threadIdx.x < 2 * kInlineBins) bins[threadIdx.x] = 0;
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        const int lane = threadIdx.x;
+        // 1. samples per key
+        for (int b0 = 0; b0 < B; b0 += 64) {
+            const bool valid = b0 + lane < B;
+            const int key = valid ? keys[b0 + lane] : -1;
+            uint64_t todo = __builtin_amdgcn_ballot_w64(valid);
+            while (todo) {
+                const int leader = __builtin_amdgcn_readfirstlane(__builtin_ctzll(todo));
+                const int kk = __builtin_amdgcn_readlane(key, leader);
+                const uint64_t same = __builtin_amdgcn_ballot_w64(key == kk);
+                if (lane == leader) bins[kk] += __popcll(same);
+                todo &= ~same;
+            }
+        }
+        // 2. first position of each key, keys in descending order: lane l owns key kInlineBins - 1 - l
+        {
+            const int cnt = bins[kInlineBins - 1 - lane];
+            int incl = cnt;
+            for (int d = 1; d < 64; d <<= 1) {
+                const int y = __shfl_up(incl, d, 64);
+                if (lane >= d) incl += y;
+            }
+            bins[kInlineBins + (kInlineBins - 1 - lane)] = incl - cnt;
+        }
+        // 3. scatter in sample order
+        for (int b0 = 0; b0 < B; b0 += 64) {
+            const bool valid = b0 + lane < B;
+            const int b = valid ? b0 + lane : 0;
+            const int key = valid ? keys[b] : -1;
+            uint64_t todo = __builtin_amdgcn_ballot_w64(valid);
+            while (todo) {
+                const int leader = __builtin_amdgcn_readfirstlane(__builtin_ctzll(todo));
+                const int kk = __builtin_amdgcn_readlane(key, leader);
+                const uint64_t same = __builtin_amdgcn_ballot_w64(key == kk);
+                const int base = bins[kInlineBins + kk];
+                if (key == kk) {
+                    const int pos = base + __popcll(same & ((1ull << lane) - 1));
+                    sorted[pos] = (uint16_t)b;
+                    order[pos] = b;
+                }
+                if (lane == leader) bins[kInlineBins + kk] = base + __popcll(same);
+                todo &= ~same;
+            }
+        }
+        // 4. inclusive scan of the block counts in sorted order
+        int carry = 0;
+        if (lane == 0) tile_start[0] = 0;
+        for (int p0 = 0; p0 < B; p0 += 64) {
+            const int p = p0 + lane;
+            int incl = p < B ? nblk[sorted[p]] : 0;
+            for (int d = 1; d < 64; d <<= 1) {
+                const int y = __shfl_up(incl, d, 64);
+                if (lane >= d) incl += y;
+            }
+            incl += carry;
+            if (p < B) tile_start[p + 1] = incl;
+            carry = __shfl(incl, 63, 64);
+        }
+        __threadfence_block();
+    }
+    __syncthreads();
 }
 
 // Persistent-grid size for `kernel`: every compute unit filled to the kernel's occupancy, no more

@@ -10,6 +10,8 @@ namespace jfa {
 constexpr int kRows = kF32BlockRows;  // rows (queries or keys) per tile
 // streamed rows per LDS stage: two [cols][D] fp32 stages stay within 32 KB
 template <int D> constexpr int cols_for() { return 4096 / D < 64 ? 4096 / D : 64; }
+static_assert(cols_for<32>() * 32 >= kInlineScratchInts && cols_for<128>() * 128 >= kInlineScratchInts,
+              "a stage buffer doubles as the in-kernel scheduler's scratch");
 constexpr int kThreads = kRows * 4;
 
 __device__ inline float quad_sum(float x) {
@@ -51,6 +53,10 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(const float *__restri
     WorkCursor probe;
     const int r = threadIdx.x >> 2, c = threadIdx.x & 3;
     const float scale = 1.0f / sqrtf((float)D);
+    if (s.build_rows)   // small problem: no scheduler launch has run
+        build_schedule_in_kernel(offsets, offsets_kv, B, s.build_rows, const_cast<int32_t *>(s.order),
+                                 const_cast<int32_t *>(s.tile_start), reinterpret_cast<int *>(Ks));
+    probe.static_only = s.static_only;
     const int64_t total = (int64_t)s.tile_start[B] * H;
     const int64_t sum_B = offsets[B];
 
@@ -110,6 +116,10 @@ __global__ __launch_bounds__(kThreads) void dq_f32_kernel(const float *__restric
     WorkCursor probe;
     const int r = threadIdx.x >> 2, c = threadIdx.x & 3;
     const float scale = 1.0f / sqrtf((float)D);
+    if (s.build_rows)   // small problem: no scheduler launch has run
+        build_schedule_in_kernel(offsets, offsets_kv, B, s.build_rows, const_cast<int32_t *>(s.order),
+                                 const_cast<int32_t *>(s.tile_start), reinterpret_cast<int *>(Ks));
+    probe.static_only = s.static_only;
     const int64_t total = (int64_t)s.tile_start[B] * H;
     const int64_t sum_B = offsets[B];
 
@@ -171,6 +181,10 @@ __global__ __launch_bounds__(kThreads) void dkv_f32_kernel(const float *__restri
     WorkCursor probe;
     const int r = threadIdx.x >> 2, c = threadIdx.x & 3;
     const float scale = 1.0f / sqrtf((float)D);
+    if (s.build_rows)   // small problem: no scheduler launch has run
+        build_schedule_in_kernel(offsets, offsets_q, B, s.build_rows, const_cast<int32_t *>(s.order),
+                                 const_cast<int32_t *>(s.tile_start), reinterpret_cast<int *>(Qs));
+    probe.static_only = s.static_only;
     const int64_t total = (int64_t)s.tile_start[B] * H;
     const int64_t sum_B = offsets_q ? offsets_q[B] : offsets[B];   // lse and delta are indexed by query rows
 

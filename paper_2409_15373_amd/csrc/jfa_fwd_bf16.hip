@@ -58,6 +58,10 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
     // until then probabilities are taken relative to the stale maximum (at most 256, exact in fp32 and
     // harmless in bf16), which keeps the rescaling of the accumulator off the common path.
     const float tau = 8.0f / c;
+    static_assert(sizeof(Smem) >= kInlineScratchInts * sizeof(int), "the stage buffers double as the scheduler's scratch");
+    if (s.build_rows)   // small problem: no scheduler launch has run
+        build_schedule_in_kernel(offsets, CROSS ? offsets_kv : nullptr, B, s.build_rows, const_cast<int32_t *>(s.order),
+                                 const_cast<int32_t *>(s.tile_start), reinterpret_cast<int *>(&sm));
     const int64_t total = (int64_t)s.tile_start[B] * H;
     const int64_t sum_B = offsets[B];
     const int64_t row_stride = (int64_t)H * D;    // elements between consecutive rows of one head
@@ -69,6 +73,7 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
                      + (((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;        //      feature column of this lane
 
     WorkCursor cursor;
+    cursor.static_only = s.static_only;
     for (;;) {
         __syncthreads();
         if (tid == 0) sm.slot = next_work(s.counter, cursor, total);

@@ -53,3 +53,38 @@ def test_check_offsets_flags():
     assert binding.jfa_check_offsets(good, 7) == 0
     assert binding.jfa_check_offsets(good, 6) == 4
     assert binding.jfa_check_offsets(torch.tensor([1, 3, 2], dtype=torch.int64).cuda(), 100) == 3
+
+
+@pytest.mark.parametrize("dtype,D", [("bf16", 64), ("bf16", 32), ("f32", 32)])
+@pytest.mark.parametrize("mode", ["self", "causal", "cross"])
+def test_small_problems_build_their_schedule_in_the_kernel(dtype, D, mode):
+    """Problems of at most four work items per compute unit (by the bound B * blocks(max_len) * H) run without the
+    scheduler launch: every workgroup builds the schedule itself.  max_len is only a bound, so the same inputs with a
+    huge bound take the scheduler-kernel path; both must give the same bits, forward and backward (a tile's arithmetic
+    does not depend on the order in which tiles are handed out)."""
+    from paper_2409_15373_amd import binding
+    rng = np.random.default_rng(17)
+    B, H = 200, 2
+    Lq = rng.integers(0, 257, size=B); Lq[3] = 256; Lq[10] = 0
+    Lk = rng.integers(0, 257, size=B) if mode == "cross" else Lq
+    oq = np.concatenate([[0], np.cumsum(Lq)]).astype(np.int64); ok = np.concatenate([[0], np.cumsum(Lk)]).astype(np.int64)
+    nq, nk = int(oq[-1]), int(ok[-1])
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    mk = lambda n: torch.randn(n, H, D, device="cuda", generator=gen).to(tdt)
+    q, dout, k, v = mk(nq), mk(nq), mk(nk), mk(nk)
+    oqd, okd = torch.from_numpy(oq).cuda(), torch.from_numpy(ok).cuda()
+    results = []
+    for bound in (256, 1 << 20):       # 200 * 2 * 2 = 800 items <= 4 * 256 compute units; the huge bound is far above
+        if mode == "cross":
+            out, lse = binding.jfa_forward_cross(q, k, v, oqd, okd, bound, bound)
+            dq, dk, dv, delta = binding.jfa_backward_cross(q, k, v, out, dout, lse, oqd, okd, bound, bound)
+        else:
+            out, lse = binding.jfa_forward(q, k, v, oqd, bound, causal=mode == "causal")
+            dq, dk, dv, delta = binding.jfa_backward(q, k, v, out, dout, lse, oqd, bound, causal=mode == "causal")
+        torch.cuda.synchronize()
+        results.append((out, lse, dq, dk, dv, delta))
+    for name, a, b in zip(("out", "lse", "dq", "dk", "dv", "delta"), *results):
+        if mode == "cross" and name == "lse":
+            a, b = torch.nan_to_num(a, neginf=-1e30), torch.nan_to_num(b, neginf=-1e30)
+        assert torch.equal(a, b), f"{name} differs between the in-kernel schedule and the scheduler kernel"
