@@ -27,11 +27,16 @@ constexpr int kPxBlock = 2048;                     // bytes of one 32 x 32 block
 constexpr int kPxStage = 2 * kPxBlock;             // two blocks per stage
 constexpr int kPxPair = 2 * kPxStage;              // two stages in flight (parity of the stage index)
 
-// LDS accesses with explicit instructions (address = byte offset inside the workgroup's LDS).  Every access to LDS
-// that is not the target of a global -> LDS copy goes through these: for such an access the compiler inserts a wait
-// for ALL copies in flight (it cannot prove that the location is not one of their targets), which would stall each
-// stage on the loads that are meant to stay two stages ahead.  An instruction the compiler does not count only makes
-// its own LDS waits more conservative (LDS returns in order); the reads below wait for their results themselves.
+// Issue priorities (s_setprio) of the two roles in the parts of a stage.  The two waves of a pair share a SIMD: where
+// both are ready, the one with the higher priority issues.
+constexpr int kPrioAS0 = 2, kPrioAS1 = 0, kPrioAExp = 0, kPrioAAcc = 0;
+constexpr int kPrioBProd = 1, kPrioBTake = 1, kPrioBAcc = 1;
+template <int P> __device__ inline void set_priority() { __builtin_amdgcn_s_setprio(P); }
+
+// The hand-over of P between the two waves of a pair, with explicit instructions (address = byte offset inside the
+// workgroup's LDS): the block must be written before its sequence number, and the number read before the block.  LDS
+// executes a wave's operations in order, so issuing them in that order is enough; written as ordinary C++ accesses,
+// the compiler would be free to reorder them.  The reads wait for their results themselves.
 __device__ inline uint32_t lds_address(const void *p) {
     return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char *)p;
 }
@@ -42,12 +47,6 @@ __device__ inline uint32_t lds_load_u32(uint32_t addr) {
     uint32_t value;
     asm volatile("ds_read_b32 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=v"(value) : "v"(addr) : "memory");
     return value;
-}
-typedef __attribute__((ext_vector_type(4))) float f32x4;
-__device__ inline void lds_load_4x_b128(uint32_t addr, f32x4 &a, f32x4 &b, f32x4 &c, f32x4 &d) {   // at addr + 0, 32, 64, 96
-    asm volatile("ds_read_b128 %0, %4\n\tds_read_b128 %1, %4 offset:32\n\tds_read_b128 %2, %4 offset:64\n\t"
-                 "ds_read_b128 %3, %4 offset:96\n\ts_waitcnt lgkmcnt(0)"
-                 : "=&v"(a), "=&v"(b), "=&v"(c), "=&v"(d) : "v"(addr) : "memory");
 }
 __device__ inline void lds_store_2x_b128(uint32_t addr, u32x4 lo, u32x4 hi) {   // lo at addr, hi at addr + 1024
     asm volatile("ds_write_b128 %0, %1\n\tds_write_b128 %0, %2 offset:1024" : : "v"(addr), "v"(lo), "v"(hi) : "memory");
@@ -68,19 +67,12 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
     constexpr int D = kBdD;
     constexpr int kKSteps = D / 16;
     constexpr int kDBlocks = D / 32;
-    // Three stages, each the streamed Q rows followed by the streamed dO rows.  One array per stage (not per tile): the
-    // compiler keeps apart only a handful of targets of global -> LDS copies, and reads of a target beyond that number
-    // wait for every copy in flight instead of their own stage's.
-    __shared__ __attribute__((aligned(1024))) char T0[2 * kBdTile];
-    __shared__ __attribute__((aligned(1024))) char T1[2 * kBdTile];
-    __shared__ __attribute__((aligned(1024))) char T2[2 * kBdTile];
-    char *const A0 = T0, *const A1 = T1, *const A2 = T2;
-    char *const B0 = T0 + kBdTile, *const B1 = T1 + kBdTile, *const B2 = T2 + kBdTile;
-    // Per stage: -lse * sqrt(D) [64] and delta [64] of the streamed rows (six targets of global -> LDS copies in all: the
-    // compiler keeps apart only a handful, and reads of a target beyond that number wait for every copy in flight).
-    __shared__ __attribute__((aligned(256))) char S0[512];
-    __shared__ __attribute__((aligned(256))) char S1[512];
-    __shared__ __attribute__((aligned(256))) char S2[512];
+    // Three stages, each the streamed Q rows (kBdTile bytes) followed by the streamed dO rows.
+    constexpr int kStageBytes = 2 * kBdTile;
+    __shared__ __attribute__((aligned(1024))) char T[3 * kStageBytes];
+    // Per stage: -lse * sqrt(D) [64] and delta [64] of the streamed rows.
+    constexpr int kStatBytes = 512;
+    __shared__ __attribute__((aligned(256))) char S[3 * kStatBytes];
     __shared__ __attribute__((aligned(1024))) char Px[kDkvPairs * kPxPair];   // P blocks on their way from A to B
     __shared__ int handed[kDkvPairs];   // per pair: number of P blocks A has written since the kernel started
     __shared__ WorkSlot slot;
@@ -104,6 +96,26 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
         const int chunk_in_group = ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1), byte_in_chunk = (lane & 1) * 8;
         taddr0 = r * 256 + ((chunk_in_group ^ swz(r)) << 4) + byte_in_chunk;
     }
+    // Every LDS read address is a per-lane constant plus a constant of the stage, block and step, which travels in the
+    // instruction's offset field: computed once here, no address arithmetic is left in the stage loop.
+    uint32_t row_at[kKSteps], tr_lo[kDBlocks], tr_hi[kDBlocks];
+#pragma unroll
+    for (int ks = 0; ks < kKSteps; ++ks) row_at[ks] = lds_byte_address(T) + (uint32_t)(raddr0 ^ (ks << 5));
+#pragma unroll
+    for (int db = 0; db < kDBlocks; ++db) {
+        tr_lo[db] = lds_byte_address(T) + (uint32_t)(taddr0 ^ (db << 6));
+        tr_hi[db] = lds_byte_address(T) + (uint32_t)((taddr0 ^ (db << 6) ^ 32) + 2048);
+    }
+    const uint32_t stat_at = lds_byte_address(S) + (uint32_t)(half * 16);
+    // Global -> LDS copies of a full stage: per-lane source offsets that do not depend on the stage (two rows of the
+    // wave's eight per tile), and the lane's row for the statistics.
+    uint32_t dma_off[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int r = 8 * wave + ((tid >> 4) & 3) + 4 * u;
+        dma_off[u] = 2u * (uint32_t)(r * (int)((int64_t)H * D) + (((tid & 15) ^ swz(r)) << 3));
+    }
+    const uint32_t lane4 = 4u * (uint32_t)lane;
     const uint32_t px_pair = lds_address(Px) + pair * kPxPair;
     const uint32_t handed_addr = lds_address(&handed[pair]);
 
@@ -123,11 +135,17 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
         st.lse2_rows = stats + (int64_t)(H + w.head) * sum_B + w.row0;
         return st;
     };
-    // per-lane DMA offsets are rebuilt at every issue (values used once per stage are the first to be spilled)
-    auto issue_from = [&](const Stream &st, const __bf16 *base, char *tile, int stage) {
+    // One stage's copies.  A stage with all 64 rows inside the sample takes the constant offsets; the sample's last,
+    // shorter stage rebuilds them with rows past the end repeating the last row (their P is zeroed).
+    auto issue_from = [&](const Stream &st, const __bf16 *base, char *tile, int stage, bool full) {
         const int L = st.L;
         const int j0 = stage * kBdBN;
         const __bf16 *sbase = base + (int64_t)j0 * row_stride;
+        if (full) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) bd_dma16(sbase, dma_off[u], tile + (8 * wave + 4 * u) * 256);
+            return;
+        }
         int t_opaque = tid;
         asm volatile("" : "+v"(t_opaque));
         const int dma_row0 = 8 * wave + ((t_opaque >> 4) & 3);
@@ -135,27 +153,26 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int r = dma_row0 + 4 * u;
-            const int jr = j0 + r < L ? r : L - 1 - j0;   // rows past the end repeat the last row (their P is zeroed)
+            const int jr = j0 + r < L ? r : L - 1 - j0;
             bd_dma16(sbase, 2u * (uint32_t)(jr * (int)row_stride + ((pc ^ swz(r)) << 3)), tile + (8 * wave + 4 * u) * 256);
         }
     };
     auto issue_stage_from = [&](const Stream &st, auto BUF, int j) {
         constexpr int Bf = decltype(BUF)::value;
-        issue_from(st, st.abase, Bf == 0 ? A0 : (Bf == 1 ? A1 : A2), j);
-        issue_from(st, st.bbase, Bf == 0 ? B0 : (Bf == 1 ? B1 : B2), j);
-        {   // lse and delta of the 64 streamed rows.  Every wave copies them (to the same place, the same values): with
-            // the copies on one wave only, the waves would differ in their count of copies in flight, and the compiler,
-            // which sees one program for all of them, would protect each stage's reads with a wait for everything.
-            // destinations as LDS pointers from the start: a generic pointer plus an offset is cast with a null check,
-            // after which the compiler no longer knows which array the copy goes to
-            typedef __attribute__((address_space(3))) char lds_char;
-            lds_char *st_lds = (lds_char *)(Bf == 0 ? S0 : (Bf == 1 ? S1 : S2));
-            const int j0 = j * kBdBN;
+        const int j0 = j * kBdBN;
+        const bool full = j0 + kBdBN <= st.L;
+        issue_from(st, st.abase, T + Bf * kStageBytes, j, full);
+        issue_from(st, st.bbase, T + Bf * kStageBytes + kBdTile, j, full);
+        // lse and delta of the 64 streamed rows; every wave copies them (to the same place, the same values), so that
+        // all waves have the same number of copies in flight and one wait count serves them all
+        char *st_lds = S + Bf * kStatBytes;
+        if (full) {
+            bd_dma4(st.lse2_rows + j0, lane4, st_lds);
+            bd_dma4(st.delta_rows + j0, lane4, st_lds + 256);
+        } else {
             const uint32_t jj = 4u * (uint32_t)(j0 + lane < st.L ? j0 + lane : st.L - 1);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)((const char *)st.lse2_rows + jj),
-                                             (__attribute__((address_space(3))) void *)st_lds, 4, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)((const char *)st.delta_rows + jj),
-                                             (__attribute__((address_space(3))) void *)(st_lds + 256), 4, 0, 0);
+            bd_dma4(st.lse2_rows, jj, st_lds);
+            bd_dma4(st.delta_rows, jj, st_lds + 256);
         }
     };
     // stationary rows of the pair: K for wave A, V for wave B (rows past the end of the sample repeat its last row)
@@ -204,55 +221,48 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[db][e] = 0.0f;
 
-        auto addresses = [&](int (&ra)[kKSteps], int (&ta)[2][kDBlocks]) {
-            int rb = raddr0, tb = taddr0;
-            asm volatile("" : "+v"(rb), "+v"(tb));   // rebuilt per block, not hoisted and spilled
+        // accumulator <- row statistics of 32 streamed rows (four 16-byte LDS reads at byte STAT of the statistics
+        // array), then the product of the block of streamed rows at byte TILE of the stage array (row reads) with this
+        // wave's stationary rows.  The operand reads run four matrix instructions ahead.
+        auto product = [&](auto TILE, auto STAT, f32x16 &a) {
+            constexpr int far = decltype(TILE)::value >= 65536 ? 65536 : 0;   // beyond the reach of the offset field
+            constexpr int off = decltype(TILE)::value - far;
+            f32x4 x0, x1, x2, x3;
+            lds_fetch_4x_f32x4<decltype(STAT)::value>(stat_at, x0, x1, x2, x3);
+            bf16x8 op[kKSteps];
 #pragma unroll
-            for (int ks = 0; ks < kKSteps; ++ks) ra[ks] = rb ^ (ks << 5);
+            for (int ks = 0; ks < 4; ++ks) op[ks] = lds_fetch_b128<off>(row_at[ks] + far);
+            lds_arrived<4>(x0, x1, x2, x3);
 #pragma unroll
-            for (int db = 0; db < kDBlocks; ++db) {
-                ta[0][db] = tb ^ (db << 6);
-                ta[1][db] = (tb ^ (db << 6) ^ 32) + 2048;
-            }
+            for (int e = 0; e < 4; ++e) { a[e] = x0[e]; a[4 + e] = x1[e]; a[8 + e] = x2[e]; a[12 + e] = x3[e]; }
+            static_assert(kKSteps == 8, "the read-ahead below is written for eight steps");
+            op[4] = lds_fetch_b128<off>(row_at[4] + far); lds_arrived<4>(op[0], a); a = mfma_32x32x16(op[0], sreg[0], a);
+            op[5] = lds_fetch_b128<off>(row_at[5] + far); lds_arrived<4>(op[1], a); a = mfma_32x32x16(op[1], sreg[1], a);
+            op[6] = lds_fetch_b128<off>(row_at[6] + far); lds_arrived<4>(op[2], a); a = mfma_32x32x16(op[2], sreg[2], a);
+            op[7] = lds_fetch_b128<off>(row_at[7] + far); lds_arrived<4>(op[3], a); a = mfma_32x32x16(op[3], sreg[3], a);
+            lds_arrived<3>(op[4], a); a = mfma_32x32x16(op[4], sreg[4], a);
+            lds_arrived<2>(op[5], a); a = mfma_32x32x16(op[5], sreg[5], a);
+            lds_arrived<1>(op[6], a); a = mfma_32x32x16(op[6], sreg[6], a);
+            lds_arrived<0>(op[7], a); a = mfma_32x32x16(op[7], sreg[7], a);
         };
-        // accumulator <- row statistics of the 32 streamed rows of block mb (four 16-byte LDS reads), then the
-        // product of the block's streamed rows (row reads of `tile`) with this wave's stationary rows
-        auto product = [&](const char *tile, const char *st_plane, int mb, f32x16 &a) {
-            int ra[kKSteps], ta[2][kDBlocks];
-            addresses(ra, ta);
-#pragma unroll
-            for (int k4 = 0; k4 < kKSteps; k4 += 4) {
-                bf16x8 op[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) op[u] = lds_read_b128(tile + mb * 32 * 256 + ra[k4 + u]);
-                if (k4 == 0) {   // the first operands are on their way when the statistics are asked for (and waited for)
-                    f32x4 x0, x1, x2, x3;
-                    int h_opaque = half;
-                    asm volatile("" : "+v"(h_opaque));
-                    lds_load_4x_b128(lds_address(st_plane) + mb * 128 + h_opaque * 16, x0, x1, x2, x3);
-                    a = __builtin_shufflevector(__builtin_shufflevector(x0, x1, 0, 1, 2, 3, 4, 5, 6, 7),
-                                                __builtin_shufflevector(x2, x3, 0, 1, 2, 3, 4, 5, 6, 7),
-                                                0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 15);
-                }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) a = mfma_32x32x16(op[u], sreg[k4 + u], a);
-            }
-        };
-        // acc^T += (streamed tile)^T x, contraction over the block's 32 streamed rows in two steps of 16
-        auto accumulate = [&](const char *tile, int mb, const bf16x8 (&x)[2]) {
-            int ra[kKSteps], ta[2][kDBlocks];
-            addresses(ra, ta);
-#pragma unroll
-            for (int ts = 0; ts < 2; ++ts) {
-                bf16x8 top[kDBlocks];
-#pragma unroll
-                for (int db = 0; db < kDBlocks; ++db) {
-                    const char *base = tile + (mb * 32 + ts * 16) * 256;
-                    top[db] = concat(lds_read_tr16(base + ta[0][db]), lds_read_tr16(base + ta[1][db]));
-                }
-#pragma unroll
-                for (int db = 0; db < kDBlocks; ++db) acc[db] = mfma_32x32x16(top[db], x[ts], acc[db]);
-            }
+        // acc^T += (block of streamed rows at byte TILE)^T x, contraction over the block's 32 rows in two steps of 16:
+        // eight matrix instructions, each with an operand of two transposing reads; the reads run four instructions ahead.
+        auto accumulate = [&](auto TILE, const bf16x8 (&x)[2]) {
+            constexpr int far = decltype(TILE)::value >= 65536 ? 65536 : 0;
+            constexpr int off = decltype(TILE)::value - far;
+            bf16x4 lo[2 * kDBlocks], hi[2 * kDBlocks];   // operand i = ts * kDBlocks + db
+            static_assert(kDBlocks == 4, "the read-ahead below is written for eight operands");
+#define JFA_DKV_FETCH(i) lo[i] = lds_fetch_tr16<off + (i / 4) * 4096>(tr_lo[i % 4] + far); hi[i] = lds_fetch_tr16<off + (i / 4) * 4096>(tr_hi[i % 4] + far)
+            JFA_DKV_FETCH(0); JFA_DKV_FETCH(1); JFA_DKV_FETCH(2); JFA_DKV_FETCH(3);
+            JFA_DKV_FETCH(4); lds_arrived<8>(lo[0], hi[0], acc[0]); acc[0] = mfma_32x32x16(concat(lo[0], hi[0]), x[0], acc[0]);
+            JFA_DKV_FETCH(5); lds_arrived<8>(lo[1], hi[1], acc[1]); acc[1] = mfma_32x32x16(concat(lo[1], hi[1]), x[0], acc[1]);
+            JFA_DKV_FETCH(6); lds_arrived<8>(lo[2], hi[2], acc[2]); acc[2] = mfma_32x32x16(concat(lo[2], hi[2]), x[0], acc[2]);
+            JFA_DKV_FETCH(7); lds_arrived<8>(lo[3], hi[3], acc[3]); acc[3] = mfma_32x32x16(concat(lo[3], hi[3]), x[0], acc[3]);
+#undef JFA_DKV_FETCH
+            lds_arrived<6>(lo[4], hi[4], acc[0]); acc[0] = mfma_32x32x16(concat(lo[4], hi[4]), x[1], acc[0]);
+            lds_arrived<4>(lo[5], hi[5], acc[1]); acc[1] = mfma_32x32x16(concat(lo[5], hi[5]), x[1], acc[1]);
+            lds_arrived<2>(lo[6], hi[6], acc[2]); acc[2] = mfma_32x32x16(concat(lo[6], hi[6]), x[1], acc[2]);
+            lds_arrived<0>(lo[7], hi[7], acc[3]); acc[3] = mfma_32x32x16(concat(lo[7], hi[7]), x[1], acc[3]);
         };
         // where block mb of stage j travels: [stage parity][block][half of the lane's sixteen values][lane]
         auto px_slot = [&](int j, int mb) {
@@ -262,10 +272,12 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
         };
 
         // ---- wave A: one block of 32 streamed queries ----
-        auto a_scores = [&](auto RAGGED, const char *At, const char *St, int mb, int j, bf16x8 (&p)[2]) {
+        auto a_scores = [&](auto RAGGED, auto TILE, auto STAT, int mb, int j, bf16x8 (&p)[2]) {
             constexpr bool ragged = decltype(RAGGED)::value != 0;
             f32x16 sc;
-            product(At, St, mb, sc);   // dot products minus lse * sqrt(D) of the streamed rows
+            if (mb == 0) set_priority<kPrioAS0>(); else set_priority<kPrioAS1>();
+            product(TILE, STAT, sc);   // dot products minus lse * sqrt(D) of the streamed rows
+            set_priority<kPrioAExp>();
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 float pe = fast_exp2(sc[e] * c);
@@ -315,29 +327,35 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
             const bool ahead = decltype(SURE)::value != 0 || j + 2 < n_stages;
             if (ahead) issue_stage_from(cur, IntB<(Bf + 2) % 3>{}, j + 2);
             if (wave_active) {
-                const char *At = Bf == 0 ? A0 : (Bf == 1 ? A1 : A2);
-                const char *Bt = Bf == 0 ? B0 : (Bf == 1 ? B1 : B2);
-                const char *St = Bf == 0 ? S0 : (Bf == 1 ? S1 : S2);
+                constexpr int At = Bf * kStageBytes, Bt = At + kBdTile, St = Bf * kStatBytes;   // bytes into T and S
+                constexpr int kBlock = 32 * 256;   // 32 streamed rows
                 const bool second = !ragged || j * kBdBN + 32 < L;   // the sample's last stage may hold one block only
                 if (role_a) {
                     bf16x8 p0[2], p1[2];
-                    a_scores(RAGGED, At, St, 0, j, p0);
-                    if (second) a_scores(RAGGED, At, St, 1, j, p1);
-                    accumulate(Bt, 0, p0);               // dV^T += dO^T P
-                    if (second) accumulate(Bt, 1, p1);
+                    a_scores(RAGGED, IntB<At>{}, IntB<St>{}, 0, j, p0);
+                    if (second) a_scores(RAGGED, IntB<At + kBlock>{}, IntB<St + 128>{}, 1, j, p1);
+                    set_priority<kPrioAAcc>();
+                    accumulate(IntB<Bt>{}, p0);               // dV^T += dO^T P
+                    if (second) accumulate(IntB<Bt + kBlock>{}, p1);
                 } else {
                     f32x16 dp0, dp1;
                     bf16x8 ds[2];
-                    product(Bt, St + 256, 0, dp0);       // delta - dO V^T (V is held negated)
-                    if (second) product(Bt, St + 256, 1, dp1);
+                    set_priority<kPrioBProd>();
+                    product(IntB<Bt>{}, IntB<St + 256>{}, dp0);       // delta - dO V^T (V is held negated)
+                    if (second) product(IntB<Bt + kBlock>{}, IntB<St + 256 + 128>{}, dp1);
+                    set_priority<kPrioBTake>();
                     b_take(0, j, dp0, ds);
-                    accumulate(At, 0, ds);               // dK^T -= Q^T dS
+                    set_priority<kPrioBAcc>();
+                    accumulate(IntB<At>{}, ds);               // dK^T -= Q^T dS
                     if (second) {
+                        set_priority<kPrioBTake>();
                         b_take(1, j, dp1, ds);
-                        accumulate(At, 1, ds);
+                        set_priority<kPrioBAcc>();
+                        accumulate(IntB<At + kBlock>{}, ds);
                     }
                 }
             }
+            set_priority<0>();
             asm volatile("" ::: "memory");
             if (ahead) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);
             __builtin_amdgcn_s_barrier();
@@ -399,7 +417,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
         // no DMA is in flight, the next tile's loads start behind the barrier at the top of the loop); wave w uses 4 KB
         // of the third pair: row r of its block at r * 128, 16-byte chunk ch at (ch ^ (r & 7)) << 4.
         {
-            char *const region = (is_a ? A2 : B2) + pair * 4096;
+            char *const region = T + 2 * kStageBytes + (is_a ? 0 : kBdTile) + pair * 4096;
             const float out_scale = is_a ? 1.0f : -scale;
             int lane_e = lane;
             asm volatile("" : "+v"(lane_e));
