@@ -135,45 +135,63 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
         st.lse2_rows = stats + (int64_t)(H + w.head) * sum_B + w.row0;
         return st;
     };
-    // One stage's copies.  A stage with all 64 rows inside the sample takes the constant offsets; the sample's last,
-    // shorter stage rebuilds them with rows past the end repeating the last row (their P is zeroed).
-    auto issue_from = [&](const Stream &st, const __bf16 *base, char *tile, int stage, bool full) {
-        const int L = st.L;
+    // One stage's copies: six per wave (two of Q rows, two of dO rows, two of row statistics).  A stage with all 64
+    // rows inside the sample takes the constant offsets; the sample's last, shorter stage rebuilds them with rows past
+    // the end repeating the last row (their P is zeroed).  The copies of a stage can be sent in three parts, so that a
+    // wave can send them at different points of the stage before: sent all at once behind the barrier, the copies of
+    // all eight waves queue up in the CU's one vector memory path and every wave stands still until its own have
+    // been accepted.
+    struct Copies {
+        const __bf16 *a, *b;          // first streamed row of the stage in Q and dO (this head)
+        const float *lse2, *delta;    // bases for the statistics copies
+        uint32_t off[2], stat;        // per-lane byte offsets
+    };
+    auto copies_of = [&](const Stream &st, int stage) {
+        Copies cp;
         const int j0 = stage * kBdBN;
-        const __bf16 *sbase = base + (int64_t)j0 * row_stride;
-        if (full) {
+        cp.a = st.abase + (int64_t)j0 * row_stride;
+        cp.b = st.bbase + (int64_t)j0 * row_stride;
+        if (j0 + kBdBN <= st.L) {
+            cp.lse2 = st.lse2_rows + j0;
+            cp.delta = st.delta_rows + j0;
+            cp.off[0] = dma_off[0];
+            cp.off[1] = dma_off[1];
+            cp.stat = lane4;
+        } else {
+            int t_opaque = tid;
+            asm volatile("" : "+v"(t_opaque));
+            const int pc = t_opaque & 15;
 #pragma unroll
-            for (int u = 0; u < 2; ++u) bd_dma16(sbase, dma_off[u], tile + (8 * wave + 4 * u) * 256);
-            return;
+            for (int u = 0; u < 2; ++u) {
+                const int r = 8 * wave + ((t_opaque >> 4) & 3) + 4 * u;
+                const int jr = j0 + r < st.L ? r : st.L - 1 - j0;
+                cp.off[u] = 2u * (uint32_t)(jr * (int)row_stride + ((pc ^ swz(r)) << 3));
+            }
+            cp.lse2 = st.lse2_rows;
+            cp.delta = st.delta_rows;
+            cp.stat = 4u * (uint32_t)(j0 + lane < st.L ? j0 + lane : st.L - 1);
         }
-        int t_opaque = tid;
-        asm volatile("" : "+v"(t_opaque));
-        const int dma_row0 = 8 * wave + ((t_opaque >> 4) & 3);
-        const int pc = t_opaque & 15;
+        return cp;
+    };
+    auto issue_part = [&](const Copies &cp, auto BUF, auto PART) __attribute__((always_inline)) {
+        constexpr int Bf = decltype(BUF)::value;
+        constexpr int part = decltype(PART)::value;
+        if constexpr (part < 2) {
+            char *tile = T + Bf * kStageBytes + part * kBdTile;
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const int r = dma_row0 + 4 * u;
-            const int jr = j0 + r < L ? r : L - 1 - j0;
-            bd_dma16(sbase, 2u * (uint32_t)(jr * (int)row_stride + ((pc ^ swz(r)) << 3)), tile + (8 * wave + 4 * u) * 256);
+            for (int u = 0; u < 2; ++u) bd_dma16(part == 0 ? cp.a : cp.b, cp.off[u], tile + (8 * wave + 4 * u) * 256);
+        } else {
+            // every wave copies the statistics (to the same place, the same values), so that all waves have the
+            // same number of copies in flight and one wait count serves them all
+            bd_dma4(cp.lse2, cp.stat, S + Bf * kStatBytes);
+            bd_dma4(cp.delta, cp.stat, S + Bf * kStatBytes + 256);
         }
     };
     auto issue_stage_from = [&](const Stream &st, auto BUF, int j) {
-        constexpr int Bf = decltype(BUF)::value;
-        const int j0 = j * kBdBN;
-        const bool full = j0 + kBdBN <= st.L;
-        issue_from(st, st.abase, T + Bf * kStageBytes, j, full);
-        issue_from(st, st.bbase, T + Bf * kStageBytes + kBdTile, j, full);
-        // lse and delta of the 64 streamed rows; every wave copies them (to the same place, the same values), so that
-        // all waves have the same number of copies in flight and one wait count serves them all
-        char *st_lds = S + Bf * kStatBytes;
-        if (full) {
-            bd_dma4(st.lse2_rows + j0, lane4, st_lds);
-            bd_dma4(st.delta_rows + j0, lane4, st_lds + 256);
-        } else {
-            const uint32_t jj = 4u * (uint32_t)(j0 + lane < st.L ? j0 + lane : st.L - 1);
-            bd_dma4(st.lse2_rows, jj, st_lds);
-            bd_dma4(st.delta_rows, jj, st_lds + 256);
-        }
+        const Copies cp = copies_of(st, j);
+        issue_part(cp, BUF, IntB<0>{});
+        issue_part(cp, BUF, IntB<1>{});
+        issue_part(cp, BUF, IntB<2>{});
     };
     // stationary rows of the pair: K for wave A, V for wave B (rows past the end of the sample repeat its last row)
     bf16x8 sreg[kKSteps];
@@ -224,7 +242,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
         // accumulator <- row statistics of 32 streamed rows (four 16-byte LDS reads at byte STAT of the statistics
         // array), then the product of the block of streamed rows at byte TILE of the stage array (row reads) with this
         // wave's stationary rows.  The operand reads run four matrix instructions ahead.
-        auto product = [&](auto TILE, auto STAT, f32x16 &a) {
+        auto product = [&](auto TILE, auto STAT, f32x16 &a) __attribute__((always_inline)) {
             constexpr int far = decltype(TILE)::value >= 65536 ? 65536 : 0;   // beyond the reach of the offset field
             constexpr int off = decltype(TILE)::value - far;
             f32x4 x0, x1, x2, x3;
@@ -247,7 +265,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
         };
         // acc^T += (block of streamed rows at byte TILE)^T x, contraction over the block's 32 rows in two steps of 16:
         // eight matrix instructions, each with an operand of two transposing reads; the reads run four instructions ahead.
-        auto accumulate = [&](auto TILE, const bf16x8 (&x)[2]) {
+        auto accumulate = [&](auto TILE, const bf16x8 (&x)[2]) __attribute__((always_inline)) {
             constexpr int far = decltype(TILE)::value >= 65536 ? 65536 : 0;
             constexpr int off = decltype(TILE)::value - far;
             bf16x4 lo[2 * kDBlocks], hi[2 * kDBlocks];   // operand i = ts * kDBlocks + db
@@ -265,14 +283,14 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
             lds_arrived<0>(lo[7], hi[7], acc[3]); acc[3] = mfma_32x32x16(concat(lo[7], hi[7]), x[1], acc[3]);
         };
         // where block mb of stage j travels: [stage parity][block][half of the lane's sixteen values][lane]
-        auto px_slot = [&](int j, int mb) {
+        auto px_slot = [&](int j, int mb) __attribute__((always_inline)) {
             int l_opaque = lane;
             asm volatile("" : "+v"(l_opaque));
             return px_pair + (uint32_t)((j & 1) * kPxStage + mb * kPxBlock + l_opaque * 16);
         };
 
         // ---- wave A: one block of 32 streamed queries ----
-        auto a_scores = [&](auto RAGGED, auto TILE, auto STAT, int mb, int j, bf16x8 (&p)[2]) {
+        auto a_scores = [&](auto RAGGED, auto TILE, auto STAT, int mb, int j, bf16x8 (&p)[2]) __attribute__((always_inline)) {
             constexpr bool ragged = decltype(RAGGED)::value != 0;
             f32x16 sc;
             if (mb == 0) set_priority<kPrioAS0>(); else set_priority<kPrioAS1>();
@@ -292,7 +310,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
             lds_store_u32(handed_addr, blocks_done);
         };
         // ---- wave B: dS of one block from its dP accumulator and the partner's P ----
-        auto b_take = [&](int mb, int j, const f32x16 &dp, bf16x8 (&ds)[2]) {
+        auto b_take = [&](int mb, int j, const f32x16 &dp, bf16x8 (&ds)[2]) __attribute__((always_inline)) {
             ++blocks_done;
             for (;;) {
                 if ((int32_t)(lds_load_u32(handed_addr) - blocks_done) >= 0) break;
@@ -320,12 +338,15 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
         // ROLE_A: the stage as wave A or as wave B runs it.  The role is fixed for the whole tile outside the stage loop:
         // a branch on it inside a stage would merge the two roles' accumulators after every stage, at the price of
         // register copies of all 64 of them.
-        auto run_stage = [&](auto ROLE_A, auto BUF, auto RAGGED, auto SURE, int j) {
+        auto run_stage = [&](auto ROLE_A, auto BUF, auto RAGGED, auto SURE, int j) __attribute__((always_inline)) {
             constexpr bool role_a = decltype(ROLE_A)::value != 0;
             constexpr int Bf = decltype(BUF)::value;
             constexpr bool ragged = decltype(RAGGED)::value != 0;
             const bool ahead = decltype(SURE)::value != 0 || j + 2 < n_stages;
-            if (ahead) issue_stage_from(cur, IntB<(Bf + 2) % 3>{}, j + 2);
+            Copies cp;
+            if (ahead) cp = copies_of(cur, j + 2);
+            auto ahead_part = [&](auto PART) __attribute__((always_inline)) { if (ahead) issue_part(cp, IntB<(Bf + 2) % 3>{}, PART); };
+            if (!wave_active) { ahead_part(IntB<0>{}); ahead_part(IntB<1>{}); ahead_part(IntB<2>{}); }
             if (wave_active) {
                 constexpr int At = Bf * kStageBytes, Bt = At + kBdTile, St = Bf * kStatBytes;   // bytes into T and S
                 constexpr int kBlock = 32 * 256;   // 32 streamed rows
@@ -333,20 +354,26 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
                 if (role_a) {
                     bf16x8 p0[2], p1[2];
                     a_scores(RAGGED, IntB<At>{}, IntB<St>{}, 0, j, p0);
+                    ahead_part(IntB<0>{});
                     if (second) a_scores(RAGGED, IntB<At + kBlock>{}, IntB<St + 128>{}, 1, j, p1);
+                    ahead_part(IntB<1>{});
                     set_priority<kPrioAAcc>();
                     accumulate(IntB<Bt>{}, p0);               // dV^T += dO^T P
+                    ahead_part(IntB<2>{});
                     if (second) accumulate(IntB<Bt + kBlock>{}, p1);
                 } else {
                     f32x16 dp0, dp1;
                     bf16x8 ds[2];
                     set_priority<kPrioBProd>();
                     product(IntB<Bt>{}, IntB<St + 256>{}, dp0);       // delta - dO V^T (V is held negated)
+                    ahead_part(IntB<0>{});
                     if (second) product(IntB<Bt + kBlock>{}, IntB<St + 256 + 128>{}, dp1);
+                    ahead_part(IntB<1>{});
                     set_priority<kPrioBTake>();
                     b_take(0, j, dp0, ds);
                     set_priority<kPrioBAcc>();
                     accumulate(IntB<At>{}, ds);               // dK^T -= Q^T dS
+                    ahead_part(IntB<2>{});
                     if (second) {
                         set_priority<kPrioBTake>();
                         b_take(1, j, dp1, ds);
@@ -375,7 +402,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
         }
         if (n_stages > 1) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);
         __syncthreads();
-        auto all_stages = [&](auto ROLE_A) {
+        auto all_stages = [&](auto ROLE_A) __attribute__((always_inline)) {
             const int n_full = L / kBdBN;   // stages with all 64 streamed rows valid; a ragged one may follow
             int j = 0;
             // Six stages per trip where they exist: the first stage of a loop body is compiled with a wait for every
