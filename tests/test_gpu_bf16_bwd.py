@@ -101,7 +101,8 @@ def test_backward_is_deterministic():
 @pytest.mark.parametrize("is_causal", [False, True])
 def test_many_short_samples_with_dynamic_claims(oracle, is_causal):
     """The direct-to-LDS kernels on a batch of 1300 short samples (some empty) and three long ones: several work items per
-    workgroup, so that items are claimed dynamically and decoded by the two-level search of the schedule."""
+    workgroup, so that items are claimed dynamically (one atomic per item on the die's queue) and, with more than 1024
+    samples, decoded from the schedule in global memory by the wave-wide 64-ary search."""
     from oracle import causal
     from paper_2409_15373_amd import binding
     rng = np.random.default_rng(31)
