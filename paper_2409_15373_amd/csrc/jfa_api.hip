@@ -341,15 +341,16 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
         if (e != hipSuccess) return hip_fail("fp32 backward kernels", e);
         return JFA_OK;
     }
-    if (dma && !offsets_kv && !causal) {
-        // self attention: dQ (which also fills both statistics planes), then dK and dV together on 128-key blocks
+    if (dma && !offsets_kv) {
+        // self attention, with or without the causal mask: dQ (which also fills both statistics planes), then dK and dV
+        // together on 128-key blocks
         e = schedule(offsets, nullptr, B, jfa::kDkvBlockRows, w, 1, s);
         if (e != hipSuccess) return hip_fail("schedule kernel", e);
         jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
         jfa::Schedule s_dkv{w.order[1], w.tile_start[1], w.counters + jfa::kXcds};
-        { ScopedTimer tm("dq_bf16_dma", s); e = jfa::launch_bwd_bf16_dma(0, q, k, v, out, dout, lse, delta, offsets, nullptr, false, (int)B, H, D, s_dq, dq, w.cus, s); }
+        { ScopedTimer tm("dq_bf16_dma", s); e = jfa::launch_bwd_bf16_dma(0, q, k, v, out, dout, lse, delta, offsets, nullptr, causal, (int)B, H, D, s_dq, dq, w.cus, s); }
         if (e != hipSuccess) return hip_fail("dq_bf16_dma", e);
-        { ScopedTimer tm("dkv_bf16_dma", s); e = jfa::launch_bwd_dkv_dma(q, k, v, dout, delta, offsets, (int)B, H, D, s_dkv, dk, dv, w.cus, s); }
+        { ScopedTimer tm("dkv_bf16_dma", s); e = jfa::launch_bwd_dkv_dma(q, k, v, dout, delta, offsets, causal, (int)B, H, D, s_dkv, dk, dv, w.cus, s); }
         if (e != hipSuccess) return hip_fail("dkv_bf16_dma", e);
         return JFA_OK;
     }

@@ -56,6 +56,10 @@ __device__ inline void lds_load_2x_b128(uint32_t addr, u32x4 &lo, u32x4 &hi) {
                  : "=&v"(lo), "=&v"(hi) : "v"(addr) : "memory");
 }
 
+// CAUSAL: query i sees keys 0 .. i.  A tile of keys then streams the queries from its own first key on (stage
+// `js`, in buffer 0); the two stages that cross the diagonal zero P for the queries before the lane's key, in the form
+// of a stage that also handles the sample's ragged end.
+template <bool CAUSAL>
 __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16 *__restrict__ q,
                                                                     const __bf16 *__restrict__ k,
                                                                     const __bf16 *__restrict__ v,
@@ -122,12 +126,14 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
     struct Stream {
         const __bf16 *abase, *bbase;
         const float *delta_rows, *lse2_rows;
-        int L, n_stages;
+        int L, n_stages;   // rows of the sample; its number of 64-row stages
+        int js;            // first stage of the stream (stage j lives in buffer (j - js) % 3)
     };
     auto stream_of = [&](const Work &w) {
         Stream st;
         st.L = w.len;
         st.n_stages = (st.L + kBdBN - 1) / kBdBN;
+        st.js = CAUSAL ? w.block * kDkvBlockRows / kBdBN : 0;
         const int64_t head_off = w.row0 * row_stride + (int64_t)w.head * D;
         st.abase = q + head_off;
         st.bbase = dout + head_off;
@@ -229,9 +235,11 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
         const int tile0 = t.block * kDkvBlockRows;
         const int n_stages = cur.n_stages;
         const bool wave_active = tile0 + pair * 32 < Ls;
+        const int key = tile0 + pair * 32 + col;   // this lane's key (the causal mask compares queries with it)
         load_stationary(t);
-        issue_stage_from(cur, IntB<0>{}, 0);
-        if (n_stages > 1) issue_stage_from(cur, IntB<1>{}, 1);
+        const int js = cur.js;
+        issue_stage_from(cur, IntB<0>{}, js);
+        if (n_stages - js > 1) issue_stage_from(cur, IntB<1>{}, js + 1);
         if (wave == 0) claim_next();   // overlaps with the loads in flight
         f32x16 acc[kDBlocks];
 #pragma unroll
@@ -299,7 +307,8 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 float pe = fast_exp2(sc[e] * c);
-                if (ragged && j * kBdBN + mb * 32 + (e >> 2) * 8 + half * 4 + (e & 3) >= L) pe = 0.0f;   // past the sample's end
+                const int row = j * kBdBN + mb * 32 + (e >> 2) * 8 + half * 4 + (e & 3);   // the query of accumulator register e
+                if (ragged && (row >= L || (CAUSAL && row < key))) pe = 0.0f;   // past the sample's end, or before the lane's key
                 sc[e] = pe;
             }
             p[0] = pack_bf16(sc, 0);
@@ -400,29 +409,32 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
                 sreg[ks] = __builtin_bit_cast(bf16x8, w);
             }
         }
-        if (n_stages > 1) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);
+        if (n_stages - js > 1) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);
         __syncthreads();
         auto all_stages = [&](auto ROLE_A) __attribute__((always_inline)) {
+            constexpr int R0 = CAUSAL ? 2 : 0;   // buffer of the first stage of the unrolled loops
+            constexpr int R1 = (R0 + 1) % 3, R2 = (R0 + 2) % 3;
             const int n_full = L / kBdBN;   // stages with all 64 streamed rows valid; a ragged one may follow
-            int j = 0;
-            // Six stages per trip where they exist: the first stage of a loop body is compiled with a wait for every
-            // copy in flight (the compiler's bookkeeping of copies is at its most cautious where the loop closes), so
-            // the longer body halves how often that wait is met.
-            for (; j + 8 <= n_stages; j += 6) {
-                run_stage(ROLE_A, IntB<0>{}, IntB<0>{}, IntB<1>{}, j);
-                run_stage(ROLE_A, IntB<1>{}, IntB<0>{}, IntB<1>{}, j + 1);
-                run_stage(ROLE_A, IntB<2>{}, IntB<0>{}, IntB<1>{}, j + 2);
-                run_stage(ROLE_A, IntB<0>{}, IntB<0>{}, IntB<1>{}, j + 3);
-                run_stage(ROLE_A, IntB<1>{}, IntB<0>{}, IntB<1>{}, j + 4);
-                run_stage(ROLE_A, IntB<2>{}, IntB<0>{}, IntB<1>{}, j + 5);
+            int j = js;
+            if (CAUSAL) {   // the two stages that cross the diagonal, in buffers 0 and 1, in the masking form
+                if (j < n_stages) { run_stage(ROLE_A, IntB<0>{}, IntB<1>{}, IntB<0>{}, j); ++j; }
+                if (j < n_stages) { run_stage(ROLE_A, IntB<1>{}, IntB<1>{}, IntB<0>{}, j); ++j; }
+            }
+            for (; j + 8 <= n_stages; j += 6) {   // six full stages, and the two after them exist
+                run_stage(ROLE_A, IntB<R0>{}, IntB<0>{}, IntB<1>{}, j);
+                run_stage(ROLE_A, IntB<R1>{}, IntB<0>{}, IntB<1>{}, j + 1);
+                run_stage(ROLE_A, IntB<R2>{}, IntB<0>{}, IntB<1>{}, j + 2);
+                run_stage(ROLE_A, IntB<R0>{}, IntB<0>{}, IntB<1>{}, j + 3);
+                run_stage(ROLE_A, IntB<R1>{}, IntB<0>{}, IntB<1>{}, j + 4);
+                run_stage(ROLE_A, IntB<R2>{}, IntB<0>{}, IntB<1>{}, j + 5);
             }
             for (; j + 5 <= n_stages; j += 3) {   // three full stages, and the two after them exist
-                run_stage(ROLE_A, IntB<0>{}, IntB<0>{}, IntB<1>{}, j);
-                run_stage(ROLE_A, IntB<1>{}, IntB<0>{}, IntB<1>{}, j + 1);
-                run_stage(ROLE_A, IntB<2>{}, IntB<0>{}, IntB<1>{}, j + 2);
+                run_stage(ROLE_A, IntB<R0>{}, IntB<0>{}, IntB<1>{}, j);
+                run_stage(ROLE_A, IntB<R1>{}, IntB<0>{}, IntB<1>{}, j + 1);
+                run_stage(ROLE_A, IntB<R2>{}, IntB<0>{}, IntB<1>{}, j + 2);
             }
-            for (; j < n_stages; ++j) {           // the last stages (at most four), stage j in buffer j % 3
-                const int r = j % 3;
+            for (; j < n_stages; ++j) {           // the last stages (at most four), stage j in buffer (j - js) % 3
+                const int r = (j - js) % 3;
                 if (j < n_full) {
                     if (r == 0) run_stage(ROLE_A, IntB<0>{}, IntB<0>{}, IntB<0>{}, j);
                     else if (r == 1) run_stage(ROLE_A, IntB<1>{}, IntB<0>{}, IntB<0>{}, j);
@@ -479,12 +491,16 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
 }
 
 hipError_t launch_bwd_dkv_dma(const void *q, const void *k, const void *v, const void *dout, const float *stats,
-                              const int64_t *offsets, int B, int H, int D, Schedule s, void *dk, void *dv, int cus,
+                              const int64_t *offsets, bool causal, int B, int H, int D, Schedule s, void *dk, void *dv, int cus,
                               hipStream_t stream) {
     if (D != kBdD) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(bwd_dkv_dma_kernel, dim3(persistent_grid<bwd_dkv_dma_kernel>(kBdThreads, cus)), dim3(kBdThreads), 0,
-                       stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, stats, offsets, B,
-                       H, s, (__bf16 *)dk, (__bf16 *)dv);
+#define JFA_LAUNCH(CAUSAL)                                                                                                  \
+    hipLaunchKernelGGL(bwd_dkv_dma_kernel<CAUSAL>, dim3(persistent_grid<bwd_dkv_dma_kernel<CAUSAL>>(kBdThreads, cus)),      \
+                       dim3(kBdThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,                \
+                       (const __bf16 *)dout, stats, offsets, B, H, s, (__bf16 *)dk, (__bf16 *)dv)
+    if (causal) JFA_LAUNCH(true);
+    else JFA_LAUNCH(false);
+#undef JFA_LAUNCH
     return hipGetLastError();
 }
 
