@@ -321,7 +321,7 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
     const bool in_kernel = !dma && small_problem(B, max_len > max_len_kv ? max_len : max_len_kv, H, block_rows, w.cus);
     if (!in_kernel) {
         e = schedule(offsets, offsets_kv, B, block_rows, w, 0, s);
-        if (e == hipSuccess && offsets_kv) e = schedule(offsets_kv, offsets, B, block_rows, w, 1, s);
+        if (e == hipSuccess && offsets_kv && !dma) e = schedule(offsets_kv, offsets, B, block_rows, w, 1, s);
         if (e != hipSuccess) return hip_fail("schedule kernel", e);
     }
     const int kv = offsets_kv ? 1 : 0;
@@ -341,28 +341,17 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
         if (e != hipSuccess) return hip_fail("fp32 backward kernels", e);
         return JFA_OK;
     }
-    if (dma && !offsets_kv) {
-        // self attention, with or without the causal mask: dQ (which also fills both statistics planes), then dK and dV
-        // together on 128-key blocks
-        e = schedule(offsets, nullptr, B, jfa::kDkvBlockRows, w, 1, s);
+    if (dma) {
+        // long samples at D = 128: dQ (which also fills both statistics planes) on schedule 0, then dK and dV together on
+        // 128-key blocks (schedule 1: blocks of keys, for cross attention from the keys' offsets)
+        e = schedule(offsets_k, offsets_q_other, B, jfa::kDkvBlockRows, w, 1, s);
         if (e != hipSuccess) return hip_fail("schedule kernel", e);
         jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
         jfa::Schedule s_dkv{w.order[1], w.tile_start[1], w.counters + jfa::kXcds};
-        { ScopedTimer tm("dq_bf16_dma", s); e = jfa::launch_bwd_bf16_dma(0, q, k, v, out, dout, lse, delta, offsets, nullptr, causal, (int)B, H, D, s_dq, dq, w.cus, s); }
+        { ScopedTimer tm("dq_bf16_dma", s); e = jfa::launch_bwd_bf16_dma(0, q, k, v, out, dout, lse, delta, offsets, offsets_kv, causal, (int)B, H, D, s_dq, dq, w.cus, s); }
         if (e != hipSuccess) return hip_fail("dq_bf16_dma", e);
-        { ScopedTimer tm("dkv_bf16_dma", s); e = jfa::launch_bwd_dkv_dma(q, k, v, dout, delta, offsets, causal, (int)B, H, D, s_dkv, dk, dv, w.cus, s); }
+        { ScopedTimer tm("dkv_bf16_dma", s); e = jfa::launch_bwd_dkv_dma(q, k, v, dout, delta, offsets_k, offsets_q_other, causal, (int)B, H, D, s_dkv, dk, dv, w.cus, s); }
         if (e != hipSuccess) return hip_fail("dkv_bf16_dma", e);
-        return JFA_OK;
-    }
-    if (dma) {
-        static const char *const names[3] = {"dq_bf16_dma", "dk_bf16_dma", "dv_bf16_dma"};
-        void *const grads[3] = {dq, dk, dv};
-        for (int mode = 0; mode < 3; ++mode) {
-            const int which = mode == 0 ? 0 : kv;
-            jfa::Schedule sc{w.order[which], w.tile_start[which], w.counters + mode * jfa::kXcds};
-            { ScopedTimer tm(names[mode], s); e = jfa::launch_bwd_bf16_dma(mode, q, k, v, out, dout, lse, delta, mode == 0 ? offsets : offsets_k, mode == 0 ? offsets_kv : offsets_q_other, causal, (int)B, H, D, sc, grads[mode], w.cus, s); }
-            if (e != hipSuccess) return hip_fail(names[mode], e);
-        }
         return JFA_OK;
     }
     jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};

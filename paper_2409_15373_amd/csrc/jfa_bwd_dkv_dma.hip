@@ -25,7 +25,7 @@ namespace jfa {
 constexpr int kDkvPairs = 4;                       // pairs of waves per workgroup
 constexpr int kPxBlock = 2048;                     // bytes of one 32 x 32 block of bf16 probabilities
 constexpr int kPxStage = 2 * kPxBlock;             // two blocks per stage
-constexpr int kPxPair = 2 * kPxStage;              // two stages in flight (parity of the stage index)
+constexpr int kPxPair = kPxStage;                  // one stage: B has read a stage's blocks before the stage's barrier, A writes the next behind it
 
 // Issue priorities (s_setprio) of the two roles in the parts of a stage.  The two waves of a pair share a SIMD: where
 // both are ready, the one with the higher priority issues.
@@ -59,13 +59,16 @@ __device__ inline void lds_load_2x_b128(uint32_t addr, u32x4 &lo, u32x4 &hi) {
 // CAUSAL: query i sees keys 0 .. i.  A tile of keys then streams the queries from its own first key on (stage
 // `js`, in buffer 0); the two stages that cross the diagonal zero P for the queries before the lane's key, in the form
 // of a stage that also handles the sample's ragged end.
-template <bool CAUSAL>
+// CROSS (cross attention): `offsets` belongs to the keys (the stationary rows), offsets_other to the queries that
+// stream past them; the row statistics are indexed by query rows.  Otherwise offsets_other is not looked at.
+template <bool CROSS, bool CAUSAL>
 __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16 *__restrict__ q,
                                                                     const __bf16 *__restrict__ k,
                                                                     const __bf16 *__restrict__ v,
                                                                     const __bf16 *__restrict__ dout,
                                                                     const float *__restrict__ stats,   // [2, H, sum_B]: delta, -lse * sqrt(D)
-                                                                    const int64_t *__restrict__ offsets, int B, int H,
+                                                                    const int64_t *__restrict__ offsets,
+                                                                    const int64_t *__restrict__ offsets_other, int B, int H,
                                                                     Schedule s, __bf16 *__restrict__ dk,
                                                                     __bf16 *__restrict__ dv) {
     constexpr int D = kBdD;
@@ -80,7 +83,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
     __shared__ __attribute__((aligned(1024))) char Px[kDkvPairs * kPxPair];   // P blocks on their way from A to B
     __shared__ int handed[kDkvPairs];   // per pair: number of P blocks A has written since the kernel started
     __shared__ WorkSlot slot;
-    __shared__ LdsSchedule<false> tab;
+    __shared__ LdsSchedule<CROSS> tab;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int col = lane & 31, half = lane >> 5;
@@ -89,7 +92,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
     const float scale = 1.0f / sqrtf((float)D);
     const float c = 1.4426950408889634f * scale;
     const int64_t total = (int64_t)s.tile_start[B] * H;
-    const int64_t sum_B = offsets[B];
+    const int64_t sum_B = CROSS ? offsets_other[B] : offsets[B];   // query rows
     const int64_t row_stride = (int64_t)H * D;
 
     // LDS read addresses inside a stage tile: one of each kind is kept, the others differ by constant bit patterns
@@ -131,14 +134,15 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
     };
     auto stream_of = [&](const Work &w) {
         Stream st;
-        st.L = w.len;
+        st.L = CROSS ? w.olen : w.len;
+        const int64_t srow0 = CROSS ? w.orow0 : w.row0;   // first streamed row (a query)
         st.n_stages = (st.L + kBdBN - 1) / kBdBN;
         st.js = CAUSAL ? w.block * kDkvBlockRows / kBdBN : 0;
-        const int64_t head_off = w.row0 * row_stride + (int64_t)w.head * D;
+        const int64_t head_off = srow0 * row_stride + (int64_t)w.head * D;
         st.abase = q + head_off;
         st.bbase = dout + head_off;
-        st.delta_rows = stats + (int64_t)w.head * sum_B + w.row0;
-        st.lse2_rows = stats + (int64_t)(H + w.head) * sum_B + w.row0;
+        st.delta_rows = stats + (int64_t)w.head * sum_B + srow0;
+        st.lse2_rows = stats + (int64_t)(H + w.head) * sum_B + srow0;
         return st;
     };
     // One stage's copies: six per wave (two of Q rows, two of dO rows, two of row statistics).  A stage with all 64
@@ -213,7 +217,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
     WorkCursor cursor;
     auto claim_next = [&]() {   // wave 0, every lane
         if (!tabled) {
-            claim_and_decode(&slot, s, offsets, B, H, total, cursor, nullptr);
+            claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_other : nullptr);
             return;
         }
         int64_t w = -1;
@@ -221,12 +225,12 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
         tab.decode(&slot, B, H, uniform64(w));
     };
     if (tid < kDkvPairs) handed[tid] = 0;
-    if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, nullptr);
-    if (tabled) tab.fill(s, offsets, nullptr, B);
+    if (wave == 0) claim_and_decode(&slot, s, offsets, B, H, total, cursor, CROSS ? offsets_other : nullptr);
+    if (tabled) tab.fill(s, offsets, offsets_other, B);
     __syncthreads();
     uint32_t blocks_done = 0;   // P blocks this wave has written (A) or taken (B) since the kernel started
     Work t;
-    bool have = load_work<false>(&slot, t);
+    bool have = load_work<CROSS>(&slot, t);
     while (have) {
         __syncthreads();   // every wave has read the slot before wave 0 refills it
         const Stream cur = stream_of(t);
@@ -234,6 +238,18 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
         const int L = cur.L;
         const int tile0 = t.block * kDkvBlockRows;
         const int n_stages = cur.n_stages;
+        if (CROSS && L == 0) {   // no query streams past these keys: their gradients are zero
+            if (wave == 0) claim_next();
+            const int i = tile0 + pair * 32 + (lane & 31);
+            if (i < Ls) {
+                __bf16 *grow = (is_a ? dv : dk) + (t.row0 + i) * row_stride + (int64_t)t.head * D + (lane >> 5) * (D / 2);
+#pragma unroll
+                for (int e = 0; e < D / 2; e += 8) *reinterpret_cast<u32x4 *>(grow + e) = u32x4{0, 0, 0, 0};
+            }
+            __syncthreads();   // the slot is written
+            have = load_work<CROSS>(&slot, t);
+            continue;
+        }
         const bool wave_active = tile0 + pair * 32 < Ls;
         const int key = tile0 + pair * 32 + col;   // this lane's key (the causal mask compares queries with it)
         load_stationary(t);
@@ -290,11 +306,11 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
             lds_arrived<2>(lo[6], hi[6], acc[2]); acc[2] = mfma_32x32x16(concat(lo[6], hi[6]), x[1], acc[2]);
             lds_arrived<0>(lo[7], hi[7], acc[3]); acc[3] = mfma_32x32x16(concat(lo[7], hi[7]), x[1], acc[3]);
         };
-        // where block mb of stage j travels: [stage parity][block][half of the lane's sixteen values][lane]
+        // where block mb of a stage travels: [block][half of the lane's sixteen values][lane]
         auto px_slot = [&](int j, int mb) __attribute__((always_inline)) {
             int l_opaque = lane;
             asm volatile("" : "+v"(l_opaque));
-            return px_pair + (uint32_t)((j & 1) * kPxStage + mb * kPxBlock + l_opaque * 16);
+            return px_pair + (uint32_t)(mb * kPxBlock + l_opaque * 16);
         };
 
         // ---- wave A: one block of 32 streamed queries ----
@@ -449,7 +465,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
         if (is_a) all_stages(IntB<1>{}); else all_stages(IntB<0>{});
 
         Work nt;   // the next work item: wave 0 parked it in the slot before this tile's first barrier
-        const bool have_next = load_work<false>(&slot, nt);
+        const bool have_next = load_work<CROSS>(&slot, nt);
 
         // ---- epilogue: scale, transpose the wave's 32 x 128 gradient block through LDS, 64 features at a time, and
         // store whole 128-byte pieces of rows.  The stage buffers are idle (every wave is past the last stage's barrier,
@@ -491,15 +507,17 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
 }
 
 hipError_t launch_bwd_dkv_dma(const void *q, const void *k, const void *v, const void *dout, const float *stats,
-                              const int64_t *offsets, bool causal, int B, int H, int D, Schedule s, void *dk, void *dv, int cus,
-                              hipStream_t stream) {
-    if (D != kBdD) return hipErrorInvalidValue;
-#define JFA_LAUNCH(CAUSAL)                                                                                                  \
-    hipLaunchKernelGGL(bwd_dkv_dma_kernel<CAUSAL>, dim3(persistent_grid<bwd_dkv_dma_kernel<CAUSAL>>(kBdThreads, cus)),      \
-                       dim3(kBdThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,                \
-                       (const __bf16 *)dout, stats, offsets, B, H, s, (__bf16 *)dk, (__bf16 *)dv)
-    if (causal) JFA_LAUNCH(true);
-    else JFA_LAUNCH(false);
+                              const int64_t *offsets, const int64_t *offsets_other, bool causal, int B, int H, int D,
+                              Schedule s, void *dk, void *dv, int cus, hipStream_t stream) {
+    if (D != kBdD || (causal && offsets_other)) return hipErrorInvalidValue;
+#define JFA_LAUNCH(CROSS, CAUSAL)                                                                                           \
+    hipLaunchKernelGGL((bwd_dkv_dma_kernel<CROSS, CAUSAL>),                                                                \
+                       dim3(persistent_grid<bwd_dkv_dma_kernel<CROSS, CAUSAL>>(kBdThreads, cus)), dim3(kBdThreads), 0,      \
+                       stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v, (const __bf16 *)dout, stats,        \
+                       offsets, offsets_other, B, H, s, (__bf16 *)dk, (__bf16 *)dv)
+    if (offsets_other) JFA_LAUNCH(true, false);
+    else if (causal) JFA_LAUNCH(false, true);
+    else JFA_LAUNCH(false, false);
 #undef JFA_LAUNCH
     return hipGetLastError();
 }

@@ -472,7 +472,8 @@ hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const voi
 // `stats` is the [2, H, sum_B] buffer the dQ launch has filled.
 constexpr int kDkvBlockRows = 128;
 hipError_t launch_bwd_dkv_dma(const void *q, const void *k, const void *v, const void *dout, const float *stats,
-                              const int64_t *offsets, bool causal, int B, int H, int D, Schedule s, void *dk, void *dv, int cus,
+                              const int64_t *offsets, const int64_t *offsets_other, bool causal, int B, int H, int D, Schedule s, void *dk,
+                              void *dv, int cus,
                               hipStream_t stream);
 
 // Unfused jagged attention (Table 1): offsets of the jagged square array, then the three operators.
