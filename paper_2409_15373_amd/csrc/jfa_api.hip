@@ -348,7 +348,7 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
         if (e != hipSuccess) return hip_fail("schedule kernel", e);
         jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
         jfa::Schedule s_dkv{w.order[1], w.tile_start[1], w.counters + jfa::kXcds};
-        { ScopedTimer tm("dq_bf16_dma", s); e = jfa::launch_bwd_bf16_dma(0, q, k, v, out, dout, lse, delta, offsets, offsets_kv, causal, (int)B, H, D, s_dq, dq, w.cus, s); }
+        { ScopedTimer tm("dq_bf16_dma", s); e = jfa::launch_bwd_dq_dma(q, k, v, out, dout, lse, delta, offsets, offsets_kv, causal, (int)B, H, D, s_dq, dq, w.cus, s); }
         if (e != hipSuccess) return hip_fail("dq_bf16_dma", e);
         { ScopedTimer tm("dkv_bf16_dma", s); e = jfa::launch_bwd_dkv_dma(q, k, v, dout, delta, offsets_k, offsets_q_other, causal, (int)B, H, D, s_dkv, dk, dv, w.cus, s); }
         if (e != hipSuccess) return hip_fail("dkv_bf16_dma", e);

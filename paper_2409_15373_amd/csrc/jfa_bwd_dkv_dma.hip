@@ -16,7 +16,7 @@
 // before reading it; A never waits for B (the block buffers alternate with the stage's parity and a stage's barrier
 // separates their reuse), so every wait ends.  The dependency also makes the pair alternate: while A takes
 // exponentials B runs matrix products and the other way round.
-// Layouts are those of bwd_bf16_dma_kernel: streamed rows on the MFMA row axis, stationary keys on the lane axis, so
+// Layouts are those of bwd_dq_dma_kernel: streamed rows on the MFMA row axis, stationary keys on the lane axis, so
 // P and dS leave the accumulators in operand position, and A's and B's lanes hold the same (query, key) elements.
 #include "jfa_bwd_dma.h"
 

@@ -1,4 +1,4 @@
-// Pieces shared by the direct-to-LDS backward kernels (jfa_bwd_bf16_dma.hip, jfa_bwd_dkv_dma.hip); not part of the C ABI.
+// Pieces shared by the direct-to-LDS backward kernels (jfa_bwd_dq_dma.hip, jfa_bwd_dkv_dma.hip); not part of the C ABI.
 #pragma once
 #include "jfa_common.h"
 #include "jfa_mfma.h"
@@ -10,8 +10,6 @@ constexpr int kBdThreads = 512;
 constexpr int kBdBN = 64;             // streamed rows per LDS stage
 constexpr int kBdD = 128;
 constexpr int kBdTile = kBdBN * kBdD * 2;
-
-enum BwdMode { kModeDQ = 0, kModeDK = 1, kModeDV = 2 };
 
 template <int N> using IntB = std::integral_constant<int, N>;
 

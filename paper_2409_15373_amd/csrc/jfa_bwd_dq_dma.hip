@@ -1,31 +1,26 @@
-// Jagged flash attention backward, bf16, D = 128, long-sample variant (paper Section 2.2).
+// Jagged flash attention backward, bf16, D = 128, long samples: the dQ kernel (paper Section 2.2).
 //
-//   P = exp(S / sqrt(D) - lse),  dP = dO V^T,  dS = P o (dP - delta),  dV = P^T dO,  dQ = dS K / sqrt(D),  dK = dS^T Q / sqrt(D)
+//   P = exp(S / sqrt(D) - lse),  dP = dO V^T,  dS = P o (dP - delta),  dQ = dS K / sqrt(D)
 //
-// Three kernels of one template, all shaped like the direct-to-LDS forward kernel: a workgroup is eight
-// waves (two per SIMD), a wave owns 32 "stationary" rows whose operands stay in registers and whose gradient
-// it accumulates, and the sample's other rows stream through three XOR-swizzled LDS stage buffers filled by
-// global_load_lds two stages ahead (bare s_barrier + partial vmcnt wait per stage):
-//   dQ  stationary = queries (Q, dO rows, lse, delta per lane); streams K and V;      dQ^T += K^T dS^T
-//   dK  stationary = keys (K, V rows); streams Q, dO and lse, delta per streamed row;  dK^T += Q^T dS
-//   dV  stationary = keys (K rows);    streams Q, dO and lse;                          dV^T += dO^T P
-// In every case the score tile has the streamed rows on the MFMA row axis and the stationary rows on the
-// column (= lane) axis, so P / dS leave the accumulator already in operand position for the last product,
-// whose other operand is the transposing LDS read of a streamed tile.  Keeping dK and dV in separate kernels
-// costs one more recomputation of S but lets each of them run two waves per SIMD (their accumulators together
-// need the whole register file), and nothing is accumulated with atomics: results are deterministic.
+// Shaped like the direct-to-LDS forward kernel: a workgroup is eight waves (two per SIMD), a wave owns 32 queries
+// whose Q and dO rows stay in registers (one query per lane) and whose gradient it accumulates, and the sample's
+// keys and values stream through three XOR-swizzled LDS stage buffers filled by global_load_lds two stages ahead
+// (bare s_barrier + partial vmcnt wait per stage).  The score tile has the keys on the MFMA row axis and the queries
+// on the column (= lane) axis, so dS leaves the accumulator already in operand position for dQ^T += K^T dS^T, whose
+// other operand is the transposing LDS read of the K tile.  The kernel is the first of the backward: it also forms
+// delta = rowsum(dO o O) and -lse * sqrt(D) for its queries and stores them for the dK / dV kernel
+// (jfa_bwd_dkv_dma.hip).  Nothing is accumulated with atomics: results are deterministic.
 #include "jfa_bwd_dma.h"
 
 namespace jfa {
 
-// CROSS (cross attention): `offsets` belongs to the stationary rows (queries for dQ, keys for dK and dV) and
-// offsets_other to the rows that stream past them; otherwise offsets_other is not looked at.
-// CAUSAL (self attention only): query i sees keys 0 .. i.  dQ streams the keys up to the tile's last query and masks
-// above the diagonal in the stages that reach past the tile's first query; dK and dV start their stream of queries at
-// the stage of the tile's first key and zero P for the queries before the lane's key in the four stages that overlap
-// the tile.  Masking stages use the form that also handles the sample's ragged end.
-template <int MODE, bool CROSS, bool CAUSAL>
-__global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf16 *__restrict__ q,
+// CROSS (cross attention): `offsets` belongs to the queries and offsets_other to the keys and values that stream past
+// them; otherwise offsets_other is not looked at.
+// CAUSAL (self attention only): query i sees keys 0 .. i.  A tile streams the keys up to its last query and masks above
+// the diagonal in the stages that reach past the tile's first query, in the form of a stage that also handles the
+// sample's ragged end.
+template <bool CROSS, bool CAUSAL>
+__global__ __launch_bounds__(kBdThreads, 2) void bwd_dq_dma_kernel(const __bf16 *__restrict__ q,
                                                                      const __bf16 *__restrict__ k,
                                                                      const __bf16 *__restrict__ v,
                                                                      const __bf16 *__restrict__ dout,
@@ -38,25 +33,18 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
     constexpr int D = kBdD;
     constexpr int kKSteps = D / 16;
     constexpr int kDBlocks = D / 32;
-    constexpr bool kRowStats = MODE != kModeDQ;   // lse / delta belong to the streamed rows
-    constexpr bool kSecond = MODE != kModeDV;     // dP / dS are needed
-    constexpr bool kLeanAddresses = MODE != kModeDV;
-    // streamed tile A: dQ: K, dK: Q, dV: Q      (16-byte row reads; transposing reads too unless dV)
-    // streamed tile B: dQ: V, dK: dO, dV: dO    (16-byte row reads; dV: transposing reads only)
+    // streamed tile A: K (16-byte row reads and transposing reads); streamed tile B: V (16-byte row reads)
     __shared__ __attribute__((aligned(1024))) char A0[kBdTile];
     __shared__ __attribute__((aligned(1024))) char A1[kBdTile];
     __shared__ __attribute__((aligned(1024))) char A2[kBdTile];
     __shared__ __attribute__((aligned(1024))) char B0[kBdTile];
     __shared__ __attribute__((aligned(1024))) char B1[kBdTile];
     __shared__ __attribute__((aligned(1024))) char B2[kBdTile];
-    __shared__ __attribute__((aligned(256))) char S0[512];   // per stage: lse[64], delta[64] of the streamed rows
-    __shared__ __attribute__((aligned(256))) char S1[512];
-    __shared__ __attribute__((aligned(256))) char S2[512];
-    // dQ only: per lane, four copies each of minus lse * sqrt(D) (the log-sum-exp in units of the raw dot product) and
+    // Per lane, four copies each of minus lse * sqrt(D) (the log-sum-exp in units of the raw dot product) and
     // minus delta of the lane's query.  The score and dP accumulators of every block start from these (four 16-byte
     // LDS reads each, no VALU work, no registers held across the stage): P = exp2(c * acc) with c = log2(e) / sqrt(D)
     // applied in fp32, and dS = P * acc.
-    __shared__ float4 lane_init[MODE == kModeDQ ? kBdThreads * 2 : 1];
+    __shared__ float4 lane_init[kBdThreads * 2];
     __shared__ WorkSlot slot;   // the NEXT work item, claimed and decoded while the current one starts up
     __shared__ LdsSchedule<CROSS> tab;   // the schedule, copied once per workgroup when it fits
 
@@ -65,7 +53,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
     const float scale = 1.0f / sqrtf((float)D);
     const float c = 1.4426950408889634f * scale;
     const int64_t total = (int64_t)s.tile_start[B] * H;
-    const int64_t sum_B = (CROSS && kRowStats) ? offsets_other[B] : offsets[B];   // query rows: lse and delta are indexed by them
+    const int64_t sum_B = offsets[B];   // query rows: lse and delta are indexed by them
     const int64_t row_stride = (int64_t)H * D;
 
     // LDS read addresses inside a tile
@@ -82,8 +70,8 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             for (int db = 0; db < kDBlocks; ++db)
                 taddr[h2][db] = (r + 8 * h2) * 256 + (((db * 4 + chunk_in_group) ^ swz(r + 8 * h2)) << 4) + byte_in_chunk;
     }
-    // What streams past a tile: first rows of the two streamed tensors and of the streamed rows' statistics, number of
-    // streamed rows of the sample, first stage and number of stages (causal tiles need only a part of the sample).
+    // What streams past a tile: first rows of K and V, the tile's queries' statistics, number of keys of the sample
+    // and of stages (causal tiles need only a part of the sample).
     struct Stream {
         const __bf16 *abase, *bbase;
         const float *delta_rows, *lse2_rows;   // plane 0 of the statistics buffer: delta; plane 1: -lse * sqrt(D)
@@ -94,14 +82,14 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         st.L = CROSS ? w.olen : w.len;
         const int64_t srow0 = CROSS ? w.orow0 : w.row0;
         const int w_tile0 = w.block * kDmaBlockRows;   // first stationary row of the tile
-        // causal: the streamed rows a tile needs are keys 0 .. (tile's last query) for dQ, queries (tile's first key) .. L - 1 for dK, dV
-        st.Lc = CAUSAL && !kRowStats && w_tile0 + kDmaBlockRows < st.L ? w_tile0 + kDmaBlockRows : st.L;
-        st.js = CAUSAL && kRowStats ? w_tile0 / kBdBN : 0;
+        // causal: the keys a tile needs are 0 .. (tile's last query)
+        st.Lc = CAUSAL && w_tile0 + kDmaBlockRows < st.L ? w_tile0 + kDmaBlockRows : st.L;
+        st.js = 0;
         st.n_stages = (st.Lc + kBdBN - 1) / kBdBN;
         const int64_t head_off = srow0 * row_stride + (int64_t)w.head * D;
-        st.abase = (MODE == kModeDQ ? k : q) + head_off;
-        st.bbase = (MODE == kModeDQ ? v : dout) + head_off;
-        const int64_t qrow0 = kRowStats ? srow0 : w.row0;   // first query row of the sample
+        st.abase = k + head_off;
+        st.bbase = v + head_off;
+        const int64_t qrow0 = w.row0;   // first query row of the sample
         st.delta_rows = delta + (int64_t)w.head * sum_B + qrow0;
         st.lse2_rows = delta + (int64_t)(H + w.head) * sum_B + qrow0;
         return st;
@@ -133,29 +121,20 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             }
         }
     };
-    auto issue_stats_from = [&](const Stream &st, char *stats, int stage) {   // wave 0 only: lse and delta of the 64 streamed rows
-        const int j0 = stage * kBdBN;
-        const uint32_t j = 4u * (uint32_t)(j0 + lane < st.L ? j0 + lane : st.L - 1);
-        bd_dma4(st.lse2_rows, j, stats);
-        if (kSecond) bd_dma4(st.delta_rows, j, stats + 256);
-    };
     auto issue_stage_from = [&](const Stream &st, auto BUF, int j) {
         constexpr int Bf = decltype(BUF)::value;
         issue_from(st, st.abase, Bf == 0 ? A0 : (Bf == 1 ? A1 : A2), j);
         issue_from(st, st.bbase, Bf == 0 ? B0 : (Bf == 1 ? B1 : B2), j);
-        if (kRowStats && wave == 0) issue_stats_from(st, Bf == 0 ? S0 : (Bf == 1 ? S1 : S2), j);
     };
     // ---- stationary rows: this lane's row as B operands (rows past the end of the sample repeat its last row) ----
-    bf16x8 xreg[kKSteps], yreg[kKSteps];   // dQ: Q, dO rows   dK: K, V rows   dV: K rows
+    bf16x8 xreg[kKSteps], yreg[kKSteps];   // the lane's Q and dO rows
     auto load_stationary = [&](const Work &w) {
         const int iw = w.block * kDmaBlockRows + wave * 32 + col;
         const int64_t off = (w.row0 + (iw < w.len ? iw : w.len - 1)) * row_stride + (int64_t)w.head * D + 8 * half;
-        const __bf16 *xsrc = MODE == kModeDQ ? q : k;
-        const __bf16 *ysrc = MODE == kModeDQ ? dout : v;
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) {
-            xreg[ks] = *reinterpret_cast<const bf16x8 *>(xsrc + off + 16 * ks);
-            if (kSecond) yreg[ks] = *reinterpret_cast<const bf16x8 *>(ysrc + off + 16 * ks);
+            xreg[ks] = *reinterpret_cast<const bf16x8 *>(q + off + 16 * ks);
+            yreg[ks] = *reinterpret_cast<const bf16x8 *>(dout + off + 16 * ks);
         }
     };
 
@@ -193,7 +172,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                 __bf16 *grow = grad + (t.row0 + i) * row_stride + (int64_t)t.head * D + (lane >> 5) * (D / 2);
 #pragma unroll
                 for (int e = 0; e < D / 2; e += 8) *reinterpret_cast<u32x4 *>(grow + e) = u32x4{0, 0, 0, 0};
-                if (!kRowStats && out_fwd != nullptr && lane < 32) {   // out = 0 there: delta = 0; lse = -inf
+                if (out_fwd != nullptr && lane < 32) {   // out = 0 there: delta = 0; lse = -inf
                     delta[(int64_t)t.head * sum_B + t.row0 + i] = 0.0f;
                     delta[(int64_t)(H + t.head) * sum_B + t.row0 + i] = INFINITY;
                 }
@@ -219,14 +198,14 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             for (int e = 0; e < 16; ++e) acc[db][e] = 0.0f;
 
         // ---- one stage: 64 streamed rows in two blocks of 32 ----
-        auto run_block = [&](auto RAGGED, const char *At, const char *Bt, const char *St, int mb, int j0) {
+        auto run_block = [&](auto RAGGED, const char *At, const char *Bt, int mb, int j0) {
             constexpr bool ragged = decltype(RAGGED)::value != 0;
-            // LDS read addresses of this block.  The dQ and dK kernels have no registers to spare for sixteen
-            // loop-invariant addresses: they keep one of each kind and rebuild the others per block with one
-            // XOR each (the swizzle makes them differ by a constant bit pattern); the empty asm keeps the
-            // compiler from hoisting the rebuilt values back out of the loop.
+            // LDS read addresses of this block.  There are no registers to spare for sixteen loop-invariant
+            // addresses: one of each kind is kept and the others are rebuilt per block with one XOR each (the
+            // swizzle makes them differ by a constant bit pattern); the empty asm keeps the compiler from
+            // hoisting the rebuilt values back out of the loop.
             int ra[kKSteps], ta[2][kDBlocks];
-            if (kLeanAddresses) {
+            {
                 int rb = raddr[0], tb = taddr[0][0];
                 asm volatile("" : "+v"(rb), "+v"(tb));
 #pragma unroll
@@ -236,23 +215,11 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                     ta[0][db] = tb ^ (db << 6);
                     ta[1][db] = (tb ^ (db << 6) ^ 32) + 2048;
                 }
-            } else {
-#pragma unroll
-                for (int ks = 0; ks < kKSteps; ++ks) ra[ks] = raddr[ks];
-#pragma unroll
-                for (int db = 0; db < kDBlocks; ++db) { ta[0][db] = taddr[0][db]; ta[1][db] = taddr[1][db]; }
             }
             f32x16 sc, dp;
 #pragma unroll
             for (int e = 0; e < 16; ++e) { sc[e] = 0.0f; dp[e] = 0.0f; }
-            if (kRowStats) {   // the dot products start at minus the streamed rows' lse * sqrt(D): P = exp2(c * acc)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const float4 l4 = *reinterpret_cast<const float4 *>(St + (mb * 32 + g * 8 + half * 4) * 4);
-                    sc[4 * g] = l4.x; sc[4 * g + 1] = l4.y; sc[4 * g + 2] = l4.z; sc[4 * g + 3] = l4.w;
-                }
-            }
-            if (MODE == kModeDQ) {   // both accumulators start at this lane's query's statistics
+            {   // both accumulators start at this lane's query's statistics: P = exp2(c * acc), dS = P * acc
                 int t_opaque = tid;
                 asm volatile("" : "+v"(t_opaque));   // the address is rebuilt here, not carried through the stage
                 int mine = (t_opaque >> 6) * 128 + (t_opaque & 63);   // index of this lane's first 16-byte slot
@@ -261,13 +228,6 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                     asm volatile("" : "+v"(mine));   // four separate loads: one load and twelve register copies would be VALU work
                     const float4 l4 = lane_init[mine], d4 = lane_init[mine + 64];
                     sc[4 * g] = l4.x; sc[4 * g + 1] = l4.y; sc[4 * g + 2] = l4.z; sc[4 * g + 3] = l4.w;
-                    dp[4 * g] = d4.x; dp[4 * g + 1] = d4.y; dp[4 * g + 2] = d4.z; dp[4 * g + 3] = d4.w;
-                }
-            }
-            if (MODE == kModeDK) {   // dP accumulator starts at the streamed rows' delta
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const float4 d4 = *reinterpret_cast<const float4 *>(St + 256 + (mb * 32 + g * 8 + half * 4) * 4);
                     dp[4 * g] = d4.x; dp[4 * g + 1] = d4.y; dp[4 * g + 2] = d4.z; dp[4 * g + 3] = d4.w;
                 }
             }
@@ -280,35 +240,31 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
 #pragma unroll
                 for (int u = 0; u < 4; ++u) sc = mfma_32x32x16(aop[u], xreg[k4 + u], sc);
             }
-            if (kSecond) {
 #pragma unroll
-                for (int k4 = 0; k4 < kKSteps; k4 += 4) {
-                    bf16x8 bop[4];
+            for (int k4 = 0; k4 < kKSteps; k4 += 4) {
+                bf16x8 bop[4];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) bop[u] = lds_read_b128(Bt + mb * 32 * 256 + ra[k4 + u]);
+                for (int u = 0; u < 4; ++u) bop[u] = lds_read_b128(Bt + mb * 32 * 256 + ra[k4 + u]);
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) dp = mfma_32x32x16(bop[u], yreg[k4 + u], dp);
-                }
+                for (int u = 0; u < 4; ++u) dp = mfma_32x32x16(bop[u], yreg[k4 + u], dp);
             }
-            // P (and dS, up to the sign in the dK kernel) for this lane's stationary row and its 16 streamed rows
+            // P and dS for this lane's query and its 16 keys
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     float p = fast_exp2(sc[4 * g + e] * c);   // the scale is applied in fp32: operands stay exact
                     const int r = j0 + mb * 32 + g * 8 + half * 4 + e;   // this register's streamed row
-                    if (ragged && (r >= (CAUSAL && !kRowStats && ic + 1 < L ? ic + 1 : L) || (CAUSAL && kRowStats && r < ic)))
-                        p = 0.0f;   // past the sample's end, or on the wrong side of the diagonal
+                    if (ragged && r >= (CAUSAL && ic + 1 < L ? ic + 1 : L)) p = 0.0f;   // past the sample's end, or above the diagonal
                     sc[4 * g + e] = p;
-                    if (MODE == kModeDK) dp[4 * g + e] = p * dp[4 * g + e];                  // = -dS
-                    if (MODE == kModeDQ) dp[4 * g + e] = p * dp[4 * g + e];
+                    dp[4 * g + e] = p * dp[4 * g + e];
                 }
             }
             // gradient accumulation: contraction over the 32 streamed rows in two steps of 16
-            const char *Tt = MODE == kModeDV ? Bt : At;
+            const char *Tt = At;
 #pragma unroll
             for (int ts = 0; ts < 2; ++ts) {
-                const bf16x8 pb = pack_bf16(kSecond ? dp : sc, 8 * ts);
+                const bf16x8 pb = pack_bf16(dp, 8 * ts);
                 bf16x8 top[kDBlocks];
 #pragma unroll
                 for (int db = 0; db < kDBlocks; ++db) {
@@ -320,14 +276,8 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             }
         };
         auto issue_stage = [&](auto BUF, int j) { issue_stage_from(cur, BUF, j); };
-        // DMA operations per wave per stage: 4 tile chunks, plus the row statistics on wave 0
-        auto wait_one_stage_outstanding = [&]() {
-            if (kRowStats && wave == 0) {
-                if (kSecond) __builtin_amdgcn_s_waitcnt(0x0070 | 6); else __builtin_amdgcn_s_waitcnt(0x0070 | 5);
-            } else {
-                __builtin_amdgcn_s_waitcnt(0x0070 | 4);
-            }
-        };
+        // DMA operations per wave per stage: 4 tile chunks
+        auto wait_one_stage_outstanding = [&]() { __builtin_amdgcn_s_waitcnt(0x0070 | 4); };
         auto run_stage = [&](auto BUF, auto RAGGED, int j) {
             constexpr int Bf = decltype(BUF)::value;
             constexpr bool ragged = decltype(RAGGED)::value != 0;   // only the sample's last stage can be
@@ -336,7 +286,6 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
             if (wave_active) {
                 const char *At = Bf == 0 ? A0 : (Bf == 1 ? A1 : A2);
                 const char *Bt = Bf == 0 ? B0 : (Bf == 1 ? B1 : B2);
-                const char *St = Bf == 0 ? S0 : (Bf == 1 ? S1 : S2);
                 const int j0 = j * kBdBN;
                 if (CAUSAL && ragged) {
                     // A masking stage of a causal tile, seen by one wave: its 32 stationary rows against each block of 32
@@ -346,11 +295,11 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                     for (int mb = 0; mb < 2; ++mb) {
                         const int theirs = j0 / 32 + mb;
                         if (theirs * 32 >= Lc) continue;
-                        if (kRowStats ? theirs >= mine : theirs <= mine) run_block(RAGGED, At, Bt, St, mb, j0);
+                        if (theirs <= mine) run_block(RAGGED, At, Bt, mb, j0);
                     }
                 } else {
-                    run_block(RAGGED, At, Bt, St, 0, j0);
-                    if (!ragged || j0 + 32 < Lc) run_block(RAGGED, At, Bt, St, 1, j0);
+                    run_block(RAGGED, At, Bt, 0, j0);
+                    if (!ragged || j0 + 32 < Lc) run_block(RAGGED, At, Bt, 1, j0);
                 }
             }
             asm volatile("" ::: "memory");
@@ -362,18 +311,9 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
 #pragma unroll
         for (int ks = 0; ks < kKSteps; ++ks) {
             asm volatile("" : "+v"(xreg[ks]));   // stationary-row loads complete here
-            if (kSecond) asm volatile("" : "+v"(yreg[ks]));
+            asm volatile("" : "+v"(yreg[ks]));
         }
-        if (MODE == kModeDK) {   // V enters negated: the dP accumulator starts at delta and ends as delta - dP
-#pragma unroll
-            for (int ks = 0; ks < kKSteps; ++ks) {
-                u32x4 w = __builtin_bit_cast(u32x4, yreg[ks]);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] ^= 0x80008000u;
-                yreg[ks] = __builtin_bit_cast(bf16x8, w);
-            }
-        }
-        if (!kRowStats) {
+        {
             // This lane's query's statistics: minus lse * sqrt(D) and minus delta = rowsum(dO o O).  With out_fwd given,
             // this kernel is the first of the backward and computes them itself from the rows it holds (each lane of
             // a pair has half of the row), leaving both planes of the statistics buffer for the dK and dV kernels;
@@ -407,8 +347,8 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         // the second stage (and, on wave 0, the loads of the claim, which it has waited for itself).
         if (n_stages - js > 1) wait_one_stage_outstanding(); else __builtin_amdgcn_s_waitcnt(0x0070);
         __syncthreads();
-        if (CAUSAL && !kRowStats) {
-            // dQ: keys 0 .. tile0 lie below every query of the tile (full stages, as without the mask); the stages that
+        if (CAUSAL) {
+            // keys 0 .. tile0 lie below every query of the tile (full stages, as without the mask); the stages that
             // reach past the tile's first query follow in the masking form
             const int n_full = (tile0 + 1 < L ? tile0 + 1 : L) / kBdBN;
             int j = 0;
@@ -424,32 +364,6 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
                 if (r == 0) run_stage(IntB<0>{}, IntB<1>{}, j);
                 else if (r == 1) run_stage(IntB<1>{}, IntB<1>{}, j);
                 else run_stage(IntB<2>{}, IntB<1>{}, j);
-            }
-        } else if (CAUSAL) {
-            // dK, dV: the stream of queries starts at the tile's first key; stage j lives in buffer (j - js) % 3.  Its first
-            // four stages cross the diagonal (buffers 0, 1, 2, 0) and mask, full stages follow from buffer 1 on, and the
-            // sample's ragged last stage masks again: one copy of the masking stages serves both ends.
-            const int diagonal_end = js + kDmaBlockRows / kBdBN < n_stages ? js + kDmaBlockRows / kBdBN : n_stages;
-            const int n_full = L / kBdBN;
-            int j = js;
-#pragma nounroll
-            for (int part = 0; part < 2; ++part) {
-                const int masking_end = part == 0 ? diagonal_end : n_stages;
-                for (; j < masking_end; ++j) {
-                    const int r = (j - js) % 3;
-                    if (r == 0) run_stage(IntB<0>{}, IntB<1>{}, j);
-                    else if (r == 1) run_stage(IntB<1>{}, IntB<1>{}, j);
-                    else run_stage(IntB<2>{}, IntB<1>{}, j);
-                }
-                if (part == 0) {
-                    for (; j + 3 <= n_full; j += 3) {
-                        run_stage(IntB<1>{}, IntB<0>{}, j);
-                        run_stage(IntB<2>{}, IntB<0>{}, j + 1);
-                        run_stage(IntB<0>{}, IntB<0>{}, j + 2);
-                    }
-                    if (j < n_full) { run_stage(IntB<1>{}, IntB<0>{}, j); ++j; }
-                    if (j < n_full) { run_stage(IntB<2>{}, IntB<0>{}, j); ++j; }
-                }
             }
         } else {
             const int n_full = L / kBdBN;   // stages with all 64 streamed rows valid; a ragged one may follow
@@ -478,7 +392,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
         // the loop); wave w uses 4 KB of the third pair: row r of its block at r * 128, 16-byte chunk ch at (ch ^ (r & 7)) << 4.
         {
             char *const region = (wave < 4 ? A2 : B2) + (wave & 3) * 4096;
-            const float out_scale = MODE == kModeDV ? 1.0f : (MODE == kModeDK ? -scale : scale);
+            const float out_scale = scale;
             int lane_e = lane;   // every address below derives from this copy, which the compiler cannot see
             asm volatile("" : "+v"(lane_e));   // through: otherwise they are computed at tile start and spilled
             const int col_e = lane_e & 31, half_e = lane_e >> 5;
@@ -511,33 +425,19 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_bf16_dma_kernel(const __bf1
     }
 }
 
-template <int MODE>
-static hipError_t launch_mode(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
-                              float *delta, const int64_t *offsets, const int64_t *offsets_other, bool causal, int B,
-                              int H, Schedule s, void *grad, int cus, hipStream_t stream) {
-    if (causal && offsets_other) return hipErrorInvalidValue;
+hipError_t launch_bwd_dq_dma(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
+                             float *delta, const int64_t *offsets, const int64_t *offsets_other, bool causal, int B, int H,
+                             int D, Schedule s, void *dq, int cus, hipStream_t stream) {
+    if (D != kBdD || (causal && offsets_other)) return hipErrorInvalidValue;
 #define JFA_LAUNCH(CROSS, CAUSAL)                                                                                           \
-    hipLaunchKernelGGL((bwd_bf16_dma_kernel<MODE, CROSS, CAUSAL>), dim3(persistent_grid<bwd_bf16_dma_kernel<MODE, CROSS, CAUSAL>>(kBdThreads, cus)), \
+    hipLaunchKernelGGL((bwd_dq_dma_kernel<CROSS, CAUSAL>), dim3(persistent_grid<bwd_dq_dma_kernel<CROSS, CAUSAL>>(kBdThreads, cus)), \
                        dim3(kBdThreads), 0, stream, (const __bf16 *)q, (const __bf16 *)k, (const __bf16 *)v,                \
-                       (const __bf16 *)dout, lse, (const __bf16 *)out, delta, offsets, offsets_other, B, H, s, (__bf16 *)grad)
+                       (const __bf16 *)dout, lse, (const __bf16 *)out, delta, offsets, offsets_other, B, H, s, (__bf16 *)dq)
     if (offsets_other) JFA_LAUNCH(true, false);
     else if (causal) JFA_LAUNCH(false, true);
     else JFA_LAUNCH(false, false);
 #undef JFA_LAUNCH
     return hipGetLastError();
-}
-
-hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const void *v, const void *out, const void *dout,
-                               const float *lse, float *delta, const int64_t *offsets,
-                               const int64_t *offsets_other, bool causal, int B, int H, int D, Schedule s, void *grad,
-                               int cus, hipStream_t stream) {
-    if (D != kBdD) return hipErrorInvalidValue;
-    switch (mode) {
-        case kModeDQ: return launch_mode<kModeDQ>(q, k, v, out, dout, lse, delta, offsets, offsets_other, causal, B, H, s, grad, cus, stream);
-        case kModeDK: return launch_mode<kModeDK>(q, k, v, nullptr, dout, lse, delta, offsets, offsets_other, causal, B, H, s, grad, cus, stream);
-        case kModeDV: return launch_mode<kModeDV>(q, k, v, nullptr, dout, lse, delta, offsets, offsets_other, causal, B, H, s, grad, cus, stream);
-        default: return hipErrorInvalidValue;
-    }
 }
 
 }  // namespace jfa

@@ -461,12 +461,11 @@ constexpr int kDmaBlockRows = 256;
 hipError_t launch_fwd_bf16_dma(const void *q, const void *k, const void *v, const int64_t *offsets,
                                const int64_t *offsets_kv, bool causal, int B, int H, int D, Schedule s, void *out, float *lse,
                                int cus, hipStream_t stream);
-// mode: 0 = dQ, 1 = dK, 2 = dV.  The dQ launch has to come first: with `out` given (the forward's output) it computes
-// delta = rowsum(dout o out) and -lse * sqrt(D) itself and leaves them in `delta` [2, H, sum_B] for the others.
-hipError_t launch_bwd_bf16_dma(int mode, const void *q, const void *k, const void *v, const void *out, const void *dout,
-                               const float *lse, float *delta, const int64_t *offsets,
-                               const int64_t *offsets_other, bool causal, int B, int H, int D, Schedule s, void *grad,
-                               int cus, hipStream_t stream);
+// The dQ launch has to come first: with `out` given (the forward's output) it computes delta = rowsum(dout o out) and
+// -lse * sqrt(D) itself and leaves them in `delta` [2, H, sum_B] for the dK / dV kernel.
+hipError_t launch_bwd_dq_dma(const void *q, const void *k, const void *v, const void *out, const void *dout, const float *lse,
+                             float *delta, const int64_t *offsets, const int64_t *offsets_other, bool causal, int B, int H,
+                             int D, Schedule s, void *dq, int cus, hipStream_t stream);
 
 // dK and dV of self attention in one kernel (pairs of waves share 32 keys; work items are blocks of kDkvBlockRows keys);
 // `stats` is the [2, H, sum_B] buffer the dQ launch has filled.
