@@ -94,25 +94,29 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dq_dma_kernel(const __bf16 
         st.lse2_rows = delta + (int64_t)(H + w.head) * sum_B + qrow0;
         return st;
     };
-    // The per-lane byte offsets of the two DMA chunks of a stage are rebuilt from the thread id at every
-    // issue (a handful of VALU operations per stage) instead of living in registers across the stage: values
-    // used once per stage are the first the register allocator spills, and a reload from scratch memory
-    // would wait on the vector-memory counter, i.e. on the very loads that are meant to stay in flight.
+    // The per-lane byte offsets of the two DMA chunks of a full stage are the same for every stage and both tensors:
+    // two registers for the whole kernel.  The sample's last, shorter stage rebuilds them from the thread id with
+    // rows past the end repeating the last row; so does every stage of the cross-attention instance, which has no
+    // registers left for them (values used once per stage are the first to be spilled, and a reload from scratch
+    // waits on the vector-memory counter, i.e. on the very loads that are meant to stay in flight).
+    uint32_t dma_off[2];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int r = 8 * wave + ((tid >> 4) & 3) + 4 * u;
+        dma_off[u] = 2u * (uint32_t)(r * (int)row_stride + (((tid & 15) ^ swz(r)) << 3));
+    }
     auto issue_from = [&](const Stream &st, const __bf16 *base, char *tile, int stage) {
         const int L = st.L;
         const int j0 = stage * kBdBN;
         const __bf16 *sbase = base + (int64_t)j0 * row_stride;
-        int t_opaque = tid;
-        asm volatile("" : "+v"(t_opaque));
-        const int dma_row0 = 8 * wave + ((t_opaque >> 4) & 3);
-        const int pc = t_opaque & 15;
-        if (j0 + kBdBN <= L) {
+        if (!CROSS && j0 + kBdBN <= L) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int r = dma_row0 + 4 * u;
-                bd_dma16(sbase, 2u * (uint32_t)(r * (int)row_stride + ((pc ^ swz(r)) << 3)), tile + (8 * wave + 4 * u) * 256);
-            }
+            for (int u = 0; u < 2; ++u) bd_dma16(sbase, dma_off[u], tile + (8 * wave + 4 * u) * 256);
         } else {
+            int t_opaque = tid;
+            asm volatile("" : "+v"(t_opaque));
+            const int dma_row0 = 8 * wave + ((t_opaque >> 4) & 3);
+            const int pc = t_opaque & 15;
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 const int r = dma_row0 + 4 * u;
