@@ -29,8 +29,8 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2516.6     # 256 CUs x 2.4 GHz x 4096 flop/clk/CU (dense bf16 MFMA)
 # flops each kernel's definition requires per (query, key) pair, per head, per unit of D (2 per MAC):
 #   forward: S and PV; dK/dV: S, dP, dV, dK; dQ: S, dP, dQ.  The delta / schedule kernels are bandwidth work.
-KERNEL_GEMMS = {"fwd_bf16": 2, "fwd_bf16_dma": 2, "dkv_bf16": 4, "dq_bf16": 3, "dq_bf16_dma": 3,
-                "dk_bf16_dma": 3, "dv_bf16_dma": 2, "dkv_bf16_dma": 4, "fwd_f32": 2}
+KERNEL_GEMMS = {"fwd_bf16": 2, "fwd_bf16_dma": 2, "dkv_bf16": 4, "dq_bf16": 3, "dq_bf16_dma": 3, "dkv_bf16_dma": 4,
+                "fwd_f32": 2}
 
 
 def main():
