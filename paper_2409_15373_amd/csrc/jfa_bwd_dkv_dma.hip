@@ -357,9 +357,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dkv_dma_kernel(const __bf16
 
         // vmcnt(copies of one stage) lgkmcnt(0): four tile copies and two statistics copies per wave and stage
         auto wait_one_stage_outstanding = [&]() { __builtin_amdgcn_s_waitcnt(0x0070 | 6); };
-        // SURE: the caller knows that stage j + 2 exists (the copies are then sent unconditionally, and the compiler,
-        // which counts copies in flight along every path, does not have to protect this stage's reads against the
-        // path on which they were not sent with a wait for everything)
+        // SURE: the caller knows that stage j + 2 exists (no test for the sample's end in the stage).
         // ROLE_A: the stage as wave A or as wave B runs it.  The role is fixed for the whole tile outside the stage loop:
         // a branch on it inside a stage would merge the two roles' accumulators after every stage, at the price of
         // register copies of all 64 of them.
