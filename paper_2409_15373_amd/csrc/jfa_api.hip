@@ -313,6 +313,23 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
+    if (!f32 && D == 128 && offsets_kv && max_len <= jfa::kFewqRows) {
+        // Few queries per sample against their keys (target attention): one kernel, one pass over K and V.  Its work
+        // items are whole (sample, head) pairs, claimed longest key list first: only the schedule's sample order is
+        // used (sorted by the keys' 32-row block count).  Small problems are dealt in sample order without it.
+        jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
+        if (B * H <= 4 * (int64_t)w.cus) {
+            sc.order = nullptr;
+            sc.static_only = true;
+        } else {
+            e = schedule(offsets, offsets_kv, B, jfa::kFewqRows, w, 0, s);
+            if (e != hipSuccess) return hip_fail("schedule kernel", e);
+        }
+        ScopedTimer tm("bwd_cross_fewq", s);
+        e = jfa::launch_bwd_cross_fewq(q, k, v, out, dout, lse, delta, offsets, offsets_kv, (int)B, H, D, sc, dq, dk, dv, w.cus, s);
+        if (e != hipSuccess) return hip_fail("bwd_cross_fewq", e);
+        return JFA_OK;
+    }
     const bool dma = !f32 && D == 128 && forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H) != kNarrow;
     const int block_rows = f32 ? jfa::kF32BlockRows : (dma ? jfa::kDmaBlockRows : jfa::kBwdBlockRows);
     // Schedule 0: blocks of queries.  Schedule 1: blocks of keys, only different from schedule 0 for cross attention.

@@ -320,7 +320,7 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dq_dma_kernel(const __bf16 
         {
             // This lane's query's statistics: minus lse * sqrt(D) and minus delta = rowsum(dO o O).  With out_fwd given,
             // this kernel is the first of the backward and computes them itself from the rows it holds (each lane of
-            // a pair has half of the row), leaving both planes of the statistics buffer for the dK and dV kernels;
+            // a pair has half of the row), leaving both planes of the statistics buffer for the dK / dV kernel;
             // otherwise an earlier kernel has filled the buffer.
             float nl, nd;
             if (out_fwd != nullptr) {

@@ -106,6 +106,30 @@ def test_cross_bf16_direct_to_lds_kernels():
     compare(got, ref, "bf16", oq, ok, Lq, Lk)
 
 
+@pytest.mark.parametrize("Lq,Lk", [
+    ([1, 32, 0, 5, 32, 17, 8, 3], [513, 64, 40, 0, 65, 1000, 31, 1]),     # every kind of block: full, ragged, one key; no queries; no keys
+    ([8] * 40, [300 + 7 * i for i in range(40)]),                          # ragged last blocks of every residue
+    ([32, 1], [2100, 4096]),                                               # many blocks per wave: both buffers in turn, partial sums of all four waves
+    ([5] * 12, [1, 31, 32, 33, 64, 96, 127, 128, 129, 160, 161, 256]),     # fewer blocks than waves, as many, one more
+])
+def test_cross_few_queries_backward_in_one_pass(Lq, Lk):
+    """At most 32 queries per sample at D = 128: the backward is one kernel that reads K and V once (dQ from the sum of
+    the waves' partial blocks, dK and dV complete per block of keys)."""
+    got, ref, oq, ok = run(Lq, Lk, 2, 128, "bf16", 5, 32, max(Lk))
+    compare(got, ref, "bf16", oq, ok, Lq, Lk)
+
+
+def test_cross_few_queries_many_items_per_workgroup():
+    """3600 (sample, head) items for at most 256 workgroups: every workgroup runs a dozen items one after the other,
+    with samples without queries and without keys among them (the LDS tiles, the copy buffers and the partial sums
+    of one item are reused by the next)."""
+    rng = np.random.default_rng(3)
+    B = 900
+    Lq, Lk = rng.integers(0, 33, B), rng.integers(0, 200, B)
+    got, ref, oq, ok = run(Lq, Lk, 4, 128, "bf16", 6, 32, 199)
+    compare(got, ref, "bf16", oq, ok, Lq, Lk)
+
+
 @pytest.mark.parametrize("max_len", [256, 1024])
 def test_cross_with_equal_offsets_is_self_attention(max_len):
     """Bit for bit wherever both entry points run the same kernels."""
