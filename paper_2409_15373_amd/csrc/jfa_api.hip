@@ -275,6 +275,25 @@ hipError_t schedule(const int64_t *offsets, const int64_t *offsets_other, int64_
     return jfa::launch_schedule(offsets, offsets_other, (int)B, block_rows, w.order[which], w.tile_start[which], w.counters, jfa::kNumCounters, s);
 }
 
+// Cross attention with few queries per sample against their keys (target attention: at most kFewqRows queries,
+// D = 128, bf16) has one kernel per direction, bound by one pass over K and V.  Their work items are whole
+// (sample, head) pairs, claimed longest key list first: only the schedule's sample order is used (sorted by the keys'
+// 32-row block count).  Small problems are dealt in sample order without it.
+bool few_queries(bool f32, int D, const int64_t *offsets_kv, int64_t max_len_q) {
+    return !f32 && D == 128 && offsets_kv && max_len_q <= jfa::kFewqRows;
+}
+int few_queries_schedule(const int64_t *offsets, const int64_t *offsets_kv, int64_t B, int H, const Views &w, hipStream_t s,
+                         jfa::Schedule *sc) {
+    *sc = jfa::Schedule{w.order[0], w.tile_start[0], w.counters};
+    if (B * H <= 4 * (int64_t)w.cus) {
+        sc->order = nullptr;
+        sc->static_only = true;
+        return JFA_OK;
+    }
+    const hipError_t e = schedule(offsets, offsets_kv, B, jfa::kFewqRows, w, 0, s);
+    return e == hipSuccess ? JFA_OK : hip_fail("schedule kernel", e);
+}
+
 int forward_impl(const char *who, bool f32, bool causal, const void *q, const void *k, const void *v, const int64_t *offsets,
                  const int64_t *offsets_kv, int64_t B, int64_t max_len, int64_t max_len_kv, int H, int D, void *out,
                  float *lse, hipStream_t s, bool static_table = false) {
@@ -285,6 +304,13 @@ int forward_impl(const char *who, bool f32, bool causal, const void *q, const vo
     Views w;
     if ((st = static_table ? get_static_table(B, &w) : get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
+    if (few_queries(f32, D, offsets_kv, max_len)) {
+        jfa::Schedule sc;
+        if ((st = few_queries_schedule(offsets, offsets_kv, B, H, w, s, &sc)) != JFA_OK) return st;
+        ScopedTimer tm("fwd_cross_fewq", s);
+        e = jfa::launch_fwd_cross_fewq(q, k, v, offsets, offsets_kv, (int)B, H, D, sc, out, lse, w.cus, s);
+        return e == hipSuccess ? JFA_OK : hip_fail("fwd_cross_fewq", e);
+    }
     const FwdVariant variant = f32 ? kNarrow : forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H);
     const int block_rows = f32 ? jfa::kF32BlockRows : (variant == kNarrow ? jfa::kFwdBlockRows : jfa::kDmaBlockRows);
     jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
@@ -313,22 +339,12 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
-    if (!f32 && D == 128 && offsets_kv && max_len <= jfa::kFewqRows) {
-        // Few queries per sample against their keys (target attention): one kernel, one pass over K and V.  Its work
-        // items are whole (sample, head) pairs, claimed longest key list first: only the schedule's sample order is
-        // used (sorted by the keys' 32-row block count).  Small problems are dealt in sample order without it.
-        jfa::Schedule sc{w.order[0], w.tile_start[0], w.counters};
-        if (B * H <= 4 * (int64_t)w.cus) {
-            sc.order = nullptr;
-            sc.static_only = true;
-        } else {
-            e = schedule(offsets, offsets_kv, B, jfa::kFewqRows, w, 0, s);
-            if (e != hipSuccess) return hip_fail("schedule kernel", e);
-        }
+    if (few_queries(f32, D, offsets_kv, max_len)) {
+        jfa::Schedule sc;
+        if ((st = few_queries_schedule(offsets, offsets_kv, B, H, w, s, &sc)) != JFA_OK) return st;
         ScopedTimer tm("bwd_cross_fewq", s);
         e = jfa::launch_bwd_cross_fewq(q, k, v, out, dout, lse, delta, offsets, offsets_kv, (int)B, H, D, sc, dq, dk, dv, w.cus, s);
-        if (e != hipSuccess) return hip_fail("bwd_cross_fewq", e);
-        return JFA_OK;
+        return e == hipSuccess ? JFA_OK : hip_fail("bwd_cross_fewq", e);
     }
     const bool dma = !f32 && D == 128 && forward_variant(max_len > max_len_kv ? max_len : max_len_kv, D, H) != kNarrow;
     const int block_rows = f32 ? jfa::kF32BlockRows : (dma ? jfa::kDmaBlockRows : jfa::kBwdBlockRows);

@@ -25,14 +25,10 @@
 // w % H), so that the samples with thousands of keys do not end up on a few workgroups; a problem of at most four
 // items per workgroup is dealt in turn in sample order, with no schedule.  Every sample is visited, so samples
 // without queries get their dK = dV = 0 and samples without keys their dQ = 0.
-#include "jfa_bwd_dma.h"
+#include "jfa_fewq.h"
 
 namespace jfa {
 
-constexpr int kFqThreads = 256;
-constexpr int kFqWaves = kFqThreads / 64;
-constexpr int kFqRows = kFewqRows;                    // queries per item (at most), keys per block
-constexpr int kFqTile = kFqRows * kBdD * 2;      // bytes of 32 rows
 constexpr int kFqStores = 16;                    // global store instructions of one full block (dK and dV, 8 KB each)
 
 __global__ __launch_bounds__(kFqThreads) void bwd_cross_fewq_kernel(const __bf16 *__restrict__ q,
@@ -57,62 +53,17 @@ __global__ __launch_bounds__(kFqThreads) void bwd_cross_fewq_kernel(const __bf16
     __shared__ __attribute__((aligned(16))) float row_delta[kFqRows];           // delta per query
     __shared__ int64_t slot;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int col = lane & 31, half = lane >> 5;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const FqLane ln;
+    const int lane = ln.lane, col = ln.col, half = ln.half;
     const float scale = 1.0f / sqrtf((float)D);
     const float c = 1.4426950408889634f * scale;
     const int64_t sum_Bq = offsets_q[B];
     const int64_t row_stride = (int64_t)H * D;
-
-    // LDS read addresses inside a 32-row tile (row r, 16-byte chunk ch at r * 256 + ((ch ^ swz(r)) << 4))
-    int raddr[kKSteps];   // row reads: this lane's row `col`, chunk 2 ks + half
-#pragma unroll
-    for (int ks = 0; ks < kKSteps; ++ks) raddr[ks] = col * 256 + (((2 * ks + half) ^ swz(col)) << 4);
-    int taddr[2][kDBlocks];   // transposing reads: row = 4 half + (lane & 15) / 4 (+8 for the operand's second half)
-    {
-        const int r = half * 4 + ((lane & 15) >> 2);
-        const int chunk_in_group = ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1), byte_in_chunk = (lane & 1) * 8;
-        const int t0 = r * 256 + ((chunk_in_group ^ swz(r)) << 4) + byte_in_chunk;
-#pragma unroll
-        for (int db = 0; db < kDBlocks; ++db) {
-            taddr[0][db] = t0 ^ (db << 6);
-            taddr[1][db] = (t0 ^ (db << 6) ^ 32) + 2048;
-        }
-    }
-    // copies of 32 rows (8 KB) by one wave: eight instructions of four rows each; rows past `valid` repeat the last one
-    auto copy_rows = [&](const __bf16 *base, int valid, char *tile) {
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int r = 4 * u + (lane >> 4);
-            const int rr = r < valid ? r : valid - 1;
-            bd_dma16(base, 2u * (uint32_t)(rr * (int)row_stride + (((lane & 15) ^ swz(r)) << 3)), tile + u * 1024);
-        }
-    };
-    // this lane's operand registers of a tile: its row `col`, the halves of every 16-feature step
-    auto fragments = [&](const char *tile, bf16x8 (&f)[kKSteps]) {
-#pragma unroll
-        for (int ks = 0; ks < kKSteps; ++ks) f[ks] = lds_read_b128(tile + raddr[ks]);
-    };
-    // acc[row of a][lane of b] += a . b over the 128 features
-    auto product = [&](const bf16x8 (&a)[kKSteps], const bf16x8 (&b)[kKSteps], f32x16 &acc) {
-#pragma unroll
-        for (int ks = 0; ks < kKSteps; ++ks) acc = mfma_32x32x16(a[ks], b[ks], acc);
-    };
-    // g^T += (tile)^T x, contraction over the tile's 32 rows in two steps of 16
-    auto accumulate = [&](const char *tile, const f32x16 &x, f32x16 (&g)[kDBlocks]) {
-#pragma unroll
-        for (int ts = 0; ts < 2; ++ts) {
-            const bf16x8 xb = pack_bf16(x, 8 * ts);
-            bf16x8 top[kDBlocks];
-#pragma unroll
-            for (int db = 0; db < kDBlocks; ++db) {
-                const char *base = tile + ts * 16 * 256;
-                top[db] = concat(lds_read_tr16(base + taddr[0][db]), lds_read_tr16(base + taddr[1][db]));
-            }
-#pragma unroll
-            for (int db = 0; db < kDBlocks; ++db) g[db] = mfma_32x32x16(top[db], xb, g[db]);
-        }
-    };
+    auto copy_rows = [&](const __bf16 *base, int valid, char *tile) { ln.copy_rows(base, (int)row_stride, valid, tile); };
+    auto fragments = [&](const char *tile, bf16x8 (&f)[kKSteps]) { ln.fragments(tile, f); };
+    auto product = [&](const bf16x8 (&a)[kKSteps], const bf16x8 (&b)[kKSteps], f32x16 &acc) { fq_product(a, b, acc); };
+    auto accumulate = [&](const char *tile, const f32x16 &x, f32x16 (&g)[kDBlocks]) { ln.accumulate(tile, x, g); };
     // One half (64 features: d-blocks 2 f and 2 f + 1) of a 128 x 32 gradient block that is complete after one block of
     // keys: g^T = (tile)^T x over the tile's 32 rows, scaled, transposed through 4 KB of LDS and stored as whole
     // 128-byte pieces of rows (this lane's column = row `col` of the result; rows >= valid are not stored).  Half a
@@ -130,7 +81,7 @@ __global__ __launch_bounds__(kFqThreads) void bwd_cross_fewq_kernel(const __bf16
 #pragma unroll
             for (int dl = 0; dl < 2; ++dl) {
                 const char *base = tile + ts * 16 * 256;
-                top[dl] = concat(lds_read_tr16(base + taddr[0][2 * f + dl]), lds_read_tr16(base + taddr[1][2 * f + dl]));
+                top[dl] = concat(lds_read_tr16(base + ln.taddr[0][2 * f + dl]), lds_read_tr16(base + ln.taddr[1][2 * f + dl]));
             }
 #pragma unroll
             for (int dl = 0; dl < 2; ++dl) g[dl] = mfma_32x32x16(top[dl], xb, g[dl]);

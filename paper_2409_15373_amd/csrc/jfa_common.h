@@ -470,10 +470,13 @@ hipError_t launch_bwd_dq_dma(const void *q, const void *k, const void *v, const 
 // dK and dV of self attention in one kernel (pairs of waves share 32 keys; work items are blocks of kDkvBlockRows keys);
 // `stats` is the [2, H, sum_B] buffer the dQ launch has filled.
 constexpr int kDkvBlockRows = 128;
-// Cross attention with at most 32 queries per sample, D = 128: the whole backward (statistics, dQ, dK, dV) in one
-// kernel and one pass over K and V.  `sched`: only `order` (the samples by their number of 32-key blocks, longest
+// Cross attention with at most 32 queries per sample, D = 128: a forward kernel bound by reading K and V once, and the
+// whole backward (statistics, dQ, dK, dV) in one kernel and one pass over K and V.  `sched`: only `order` (the samples by their number of 32-key blocks, longest
 // first; nullptr = sample order), `counter` and `static_only` are used; a work item is a whole (sample, head).
 constexpr int kFewqRows = 32;
+hipError_t launch_fwd_cross_fewq(const void *q, const void *k, const void *v, const int64_t *offsets_q,
+                                 const int64_t *offsets_kv, int B, int H, int D, Schedule sched, void *out, float *lse, int cus,
+                                 hipStream_t stream);
 hipError_t launch_bwd_cross_fewq(const void *q, const void *k, const void *v, const void *out, const void *dout,
                                  const float *lse, float *stats, const int64_t *offsets_q, const int64_t *offsets_kv, int B,
                                  int H, int D, Schedule sched, void *dq, void *dk, void *dv, int cus, hipStream_t stream);
