@@ -114,6 +114,10 @@ int jfa_backward_f32(const float *q, const float *k, const float *v, const float
  *   lse     fp32 [H, sum_Bq];  delta as for jfa_backward with sum_B = sum_Bq
  * A sample without keys gives out = 0, lse = -inf and dq = 0 for its queries; a sample without queries gives
  * dk = dv = 0 for its keys.  Everything else (alignment, streams, errors, ownership) as for the calls above.
+ * max_len_q also selects kernels: with max_len_q <= 32 (a few target items per sample) and D = 128 the bf16 calls
+ * run one kernel each that passes over K and V once (the backward writes dq, dk, dv and delta in that pass), so a
+ * tight bound is worth passing; as everywhere, a sample with more queries than max_len_q is undefined (no access
+ * leaves the buffers, the results are wrong).
  */
 int jfa_forward_cross(const void *q, const void *k, const void *v, const int64_t *offsets_q, const int64_t *offsets_kv,
                       int64_t B, int64_t max_len_q, int64_t max_len_kv, int H, int D, void *out, float *lse, void *stream);
