@@ -176,7 +176,7 @@ def jfa_backward(q, k, v, out, dout, lse, offsets, max_len: int, dq=None, dk=Non
     """dq, dk, dv [sum_B, H, D] (dtype of q) and delta fp32 [H, sum_B].
 
     The statistics buffer handed to the library is fp32 [H, sum_B] for fp32 inputs and fp32 [2, H, sum_B] for
-    bf16 inputs (plane 0: delta, plane 1: the library's scratch copy of -lse in base 2).  A caller-provided `delta` must
+    bf16 inputs (plane 0: delta, plane 1: -lse * sqrt(D), which the gradient kernels' score products start from).  A caller-provided `delta` must
     have that size and is returned as it is; otherwise one is allocated here and plane 0 is returned.
     """
     sum_B, H, D = q.shape
