@@ -1,4 +1,4 @@
-"""Check of the hand-placed LDS waits in the fused dK/dV kernel, on the compiler's assembly listing.
+"""Check of the hand-placed waits in the fused dK/dV kernel and the few-query cross backward, on the compiler's assembly listing.
 
     python -m paper_2409_15373_amd.check_lds_waits [source.hip ...]
 
@@ -65,6 +65,40 @@ def scan(listing: str) -> dict:
     return {"lds_reads": reads, "lgkmcnt_waits": waits, "deepest_queue": deepest, "violations": violations}
 
 
+def behind_partial_vmcnt_wait(listing: str, count: int) -> list:
+    """For every hand-written `s_waitcnt vmcnt(count) ...` in the listing: the vector-memory instructions in the program
+    text between it and the next s_barrier, as (global -> LDS copies, global stores, anything else).
+
+    The few-query cross backward waits for a block's K and V rows with vmcnt(16): the rows were requested a block ago
+    and the only vector-memory instructions issued since are the previous block's stores of dK and dV, which may stay
+    in flight.  That is right only if the loop body between two such waits holds exactly `count` store instructions
+    (a full block executes them all) and nothing else that the counter counts but the 16 copies of the next block,
+    which come first: fewer stores would let the wait pass with copies still in flight, and a scratch access or any
+    other load would shift the count.
+    """
+    lines = listing.splitlines()
+    found = []
+    for i, line in enumerate(lines):
+        if not re.search(r"s_waitcnt\s+vmcnt\(%d\)" % count, line.split(";")[0]):
+            continue
+        copies = stores = other = 0
+        for later in lines[i + 1:]:
+            t = later.split(";")[0].strip()
+            if not t:
+                continue
+            op = t.split()[0]
+            if op == "s_barrier":
+                break
+            if op.startswith("global_load_lds"):
+                copies += 1
+            elif op.startswith("global_store"):
+                stores += 1
+            elif op.startswith(("global_", "buffer_", "scratch_", "flat_")):
+                other += 1
+        found.append((copies, stores, other))
+    return found
+
+
 def listing_of(source: str) -> str:
     """The device assembly of one .hip source, compiled with the library's own flags."""
     with tempfile.TemporaryDirectory() as tmp:
@@ -87,6 +121,10 @@ def main(argv) -> int:
         for ln, text, at in r["violations"][:20]:
             print(f"  line {ln}: {text}   touches the registers of the read at line {at}")
         bad += len(r["violations"]) + (r["deepest_queue"] > 15)
+    if not argv:
+        found = behind_partial_vmcnt_wait(listing_of(os.path.join(_build.CSRC, "jfa_bwd_cross_fewq.hip")), 16)
+        print(f"jfa_bwd_cross_fewq.hip: vmcnt(16) waits followed by (copies, stores, other vector-memory instructions) = {found}")
+        bad += found != [(16, 16, 0)]
     return 1 if bad else 0
 
 

@@ -56,3 +56,24 @@ def test_the_fused_kernel_reads_no_register_in_flight():
     r = check_lds_waits.scan(check_lds_waits.listing_of(os.path.join(build.CSRC, "jfa_bwd_dkv_dma.hip")))
     assert r["lds_reads"] > 1000 and r["violations"] == [], r["violations"][:5]
     assert r["deepest_queue"] <= 15   # the counter has four bits
+
+
+def test_partial_vmcnt_model_counts_what_follows_a_wait():
+    text = """
+        s_waitcnt vmcnt(2) lgkmcnt(0)
+        global_load_lds_dwordx4 v1, s[2:3]
+        global_store_dwordx4 v[2:3], v[4:7], off
+        scratch_load_dword v9, off, off
+        global_store_dwordx4 v[2:3], v[4:7], off
+        s_barrier
+        global_store_dwordx4 v[2:3], v[4:7], off
+    """
+    assert check_lds_waits.behind_partial_vmcnt_wait(text, 2) == [(1, 2, 1)]
+    assert check_lds_waits.behind_partial_vmcnt_wait(text, 3) == []
+
+
+def test_the_few_query_backward_leaves_exactly_its_stores_in_flight():
+    """Its wait for a block's K and V rows is vmcnt(16): sixteen copies of the next block, then the sixteen stores of
+    dK and dV that may stay in flight, and no other vector-memory instruction (no scratch) in the block loop."""
+    listing = check_lds_waits.listing_of(os.path.join(build.CSRC, "jfa_bwd_cross_fewq.hip"))
+    assert check_lds_waits.behind_partial_vmcnt_wait(listing, 16) == [(16, 16, 0)]
