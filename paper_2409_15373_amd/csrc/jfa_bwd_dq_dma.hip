@@ -205,19 +205,20 @@ __global__ __launch_bounds__(kBdThreads, 2) void bwd_dq_dma_kernel(const __bf16 
         auto run_block = [&](auto RAGGED, const char *At, const char *Bt, int mb, int j0) {
             constexpr bool ragged = decltype(RAGGED)::value != 0;
             // LDS read addresses of this block.  There are no registers to spare for sixteen loop-invariant
-            // addresses: one of each kind is kept and the others are rebuilt per block with one XOR each (the
-            // swizzle makes them differ by a constant bit pattern); the empty asm keeps the compiler from
-            // hoisting the rebuilt values back out of the loop.
+            // addresses: the eight of the transposing reads are kept, of the row reads only one, and the others are
+            // rebuilt per block with one XOR each (the swizzle makes them differ by a constant bit pattern); the empty
+            // asm keeps the compiler from hoisting the rebuilt values back out of the loop.  (Keeping the row
+            // addresses too, or this lane's address in lane_init, spills in the stages and costs 10 %.)
             int ra[kKSteps], ta[2][kDBlocks];
             {
-                int rb = raddr[0], tb = taddr[0][0];
-                asm volatile("" : "+v"(rb), "+v"(tb));
+                int rb = raddr[0];
+                asm volatile("" : "+v"(rb));
 #pragma unroll
                 for (int ks = 0; ks < kKSteps; ++ks) ra[ks] = rb ^ (ks << 5);
 #pragma unroll
                 for (int db = 0; db < kDBlocks; ++db) {
-                    ta[0][db] = tb ^ (db << 6);
-                    ta[1][db] = (tb ^ (db << 6) ^ 32) + 2048;
+                    ta[0][db] = taddr[0][db];
+                    ta[1][db] = taddr[1][db];
                 }
             }
             f32x16 sc, dp;
