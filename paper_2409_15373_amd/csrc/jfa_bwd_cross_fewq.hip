@@ -20,11 +20,12 @@
 // and V and once per item for Q and dO): only which side of the matrix instruction they go to differs.
 // The waves' partial dQ blocks are added in a fixed order through LDS at the end of the item: results are
 // deterministic.  The kernel also writes both planes of the statistics buffer (delta = rowsum(dO o O), -lse * sqrt(D)).
-// Work items are claimed by the persistent workgroups from the library's work counters in the order of a schedule
+// Work items are taken by the persistent workgroups, by tickets from a work counter, in the order of a schedule
 // that lists the samples by their number of key blocks, longest first (item w = position w / H of that list, head
-// w % H), so that the samples with thousands of keys do not end up on a few workgroups; a problem of at most four
-// items per workgroup is dealt in turn in sample order, with no schedule.  Every sample is visited, so samples
-// without queries get their dK = dV = 0 and samples without keys their dQ = 0.
+// w % H), so that the samples with thousands of keys do not end up on a few workgroups, and are decoded one item ahead
+// of the work (FqAhead); a problem of at most four items per workgroup is dealt in turn in sample order, with no
+// schedule.  Every sample is visited, so samples without queries get their dK = dV = 0 and samples without keys
+// their dQ = 0.
 #include "jfa_fewq.h"
 
 namespace jfa {
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(kFqThreads) void bwd_cross_fewq_kernel(const __bf16
     __shared__ __attribute__((aligned(1024))) char KV[kFqWaves][2][2 * kFqTile];   // per wave, two buffers: a block's K rows, then its V rows
     __shared__ __attribute__((aligned(16))) float row_lse2[kFqRows];            // -lse * sqrt(D) per query
     __shared__ __attribute__((aligned(16))) float row_delta[kFqRows];           // delta per query
-    __shared__ int64_t slot;
+    __shared__ FqSlot slot[2];
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const FqLane ln;
@@ -107,17 +108,24 @@ __global__ __launch_bounds__(kFqThreads) void bwd_cross_fewq_kernel(const __bf16
     };
 
     const int64_t total = (int64_t)B * H;
-    WorkCursor cur;
-    cur.static_only = sched.static_only;
-    for (;;) {
-        // (the claim's barriers also say: the previous item's reads of the shared tiles and partial sums are done)
-        const int64_t w = fetch_item(sched.counter, cur, total, &slot);
-        if (w < 0) break;
-        const int pos = (int)(w / H), head = (int)(w % H);
-        const int b = sched.order ? __builtin_amdgcn_readfirstlane(sched.order[pos]) : pos;
-        const int64_t q0 = offsets_q[b], k0 = offsets_kv[b];
-        const int Lq = (int)(offsets_q[b + 1] - q0), Lk = (int)(offsets_kv[b + 1] - k0);
+    FqAhead ahead;   // thread 0's
+    if (tid == 0) fq_walk_begin(ahead, slot, sched, offsets_q, offsets_kv, H, total);
+    for (int it = 0;; ++it) {
+        __syncthreads();   // this item's slot is written; the previous item's reads of the shared tiles and partial sums are done
+        const FqSlot *const item = &slot[it & 1];
+        if (__builtin_amdgcn_readfirstlane(item->valid) == 0) break;
+        const int head = __builtin_amdgcn_readfirstlane(item->head);
+        const int Lq = __builtin_amdgcn_readfirstlane(item->Lq), Lk = __builtin_amdgcn_readfirstlane(item->Lk);
+        const int64_t q0 = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane(item->q0_hi) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane(item->q0_lo));
+        const int64_t k0 = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane(item->k0_hi) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane(item->k0_lo));
         const int n_blocks = (Lk + kFqRows - 1) / kFqRows;
+        if (tid == 0) fq_walk_ahead(ahead, sched, H, total);
+        auto walk_on_at_once = [&]() {   // an item without blocks to hide the loads behind
+            if (tid == 0) {
+                fq_walk_offsets(ahead, offsets_q, offsets_kv, total);
+                fq_walk_publish(ahead, slot, it, H, total);
+            }
+        };
         if (Lq == 0) {     // no query attends to these keys: their gradients are zero
             for (int blk = wave; blk < n_blocks; blk += kFqWaves) {
                 const int j = blk * kFqRows + col;
@@ -130,6 +138,7 @@ __global__ __launch_bounds__(kFqThreads) void bwd_cross_fewq_kernel(const __bf16
                     }
                 }
             }
+            walk_on_at_once();
             continue;
         }
         const __bf16 *const kbase = k + k0 * row_stride + (int64_t)head * D;
@@ -178,8 +187,10 @@ __global__ __launch_bounds__(kFqThreads) void bwd_cross_fewq_kernel(const __bf16
 #pragma unroll
                 for (int e = 0; e < D / 2; e += 8) *reinterpret_cast<u32x4 *>(dq + off + e) = u32x4{0, 0, 0, 0};
             }
+            walk_on_at_once();
             continue;
         }
+        if (tid == 0) fq_walk_offsets(ahead, offsets_q, offsets_kv, total);   // in flight during the item's blocks
         // per item: the lane's operand registers of Q and dO, and the statistics in both orientations
         bf16x8 Qf[kKSteps], Of[kKSteps];
         fragments(Qt, Qf);
@@ -286,6 +297,7 @@ __global__ __launch_bounds__(kFqThreads) void bwd_cross_fewq_kernel(const __bf16
                 }
             }
         }
+        if (tid == 0) fq_walk_publish(ahead, slot, it, H, total);
     }
 }
 

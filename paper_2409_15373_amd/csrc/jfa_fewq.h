@@ -65,6 +65,72 @@ struct FqLane {
     }
 };
 
+// The walk of a workgroup through the work items ((sample, head) pairs: item w = position w / H of the schedule's
+// sample order, head w % H), kept ONE ITEM AHEAD of the work by thread 0 so that neither the claim nor the decoding
+// of an item -- an atomic and two dependent loads, microseconds for items that may hold a block or two of keys --
+// is waited for: while item i is worked on, the parameters of item i + 1 are fetched and left in `slot[(i + 1) & 1]`,
+// and the work id of item i + 2 is requested.  The first item of a workgroup is its own index; further ids are
+// tickets from one work counter (items are independent of each other: nothing is gained by keeping neighbours on
+// one die), or, without a schedule (sched.static_only), every gridDim-th item.
+struct FqSlot {
+    int valid;   // 0: no such item, the workgroup is done
+    int sample, head, Lq, Lk;
+    int q0_lo, q0_hi, k0_lo, k0_hi;   // first query row and first key row of the sample
+};
+struct FqAhead {       // thread 0's registers
+    int64_t w1 = 0;    // work id of the item after the current one
+    int64_t w2 = 0;    // and of the one after that (requested; its arrival is waited for an item later)
+    int b1 = 0;        // sample of item w1
+    int64_t q0 = 0, q1 = 0, k0 = 0, k1 = 0;   // its offsets
+};
+__device__ inline int64_t fq_next_id(const Schedule &sched, int64_t after) {
+    return sched.static_only ? after + (int64_t)gridDim.x : (int64_t)gridDim.x + atomicAdd(sched.counter, 1);
+}
+__device__ inline int fq_sample_of(const Schedule &sched, int64_t w, int H) {
+    const int pos = (int)(w / H);
+    return sched.order ? sched.order[pos] : pos;
+}
+__device__ inline void fq_store_slot(FqSlot *slot, bool valid, int b, int head, int64_t q0, int64_t q1, int64_t k0, int64_t k1) {
+    slot->valid = valid ? 1 : 0;
+    slot->sample = b;
+    slot->head = head;
+    slot->Lq = (int)(q1 - q0);
+    slot->Lk = (int)(k1 - k0);
+    slot->q0_lo = (int)(uint32_t)q0;
+    slot->q0_hi = (int)(uint32_t)((uint64_t)q0 >> 32);
+    slot->k0_lo = (int)(uint32_t)k0;
+    slot->k0_hi = (int)(uint32_t)((uint64_t)k0 >> 32);
+}
+// thread 0, before the first item: the workgroup's own item into slot[0], and the id of the one after it
+__device__ inline void fq_walk_begin(FqAhead &a, FqSlot *slot, const Schedule &sched, const int64_t *offsets_q,
+                                     const int64_t *offsets_kv, int H, int64_t total) {
+    const int64_t w0 = blockIdx.x;
+    if (w0 < total) {
+        const int b = fq_sample_of(sched, w0, H);
+        fq_store_slot(&slot[0], true, b, (int)(w0 % H), offsets_q[b], offsets_q[b + 1], offsets_kv[b], offsets_kv[b + 1]);
+    } else {
+        slot[0].valid = 0;
+    }
+    a.w1 = fq_next_id(sched, w0);
+}
+// thread 0, at the start of an item: request the id of the item two ahead, start decoding the next one
+__device__ inline void fq_walk_ahead(FqAhead &a, const Schedule &sched, int H, int64_t total) {
+    a.w2 = fq_next_id(sched, a.w1);
+    if (a.w1 < total) a.b1 = fq_sample_of(sched, a.w1, H);
+}
+// thread 0, somewhat later (the sample's index has arrived by then): its offsets
+__device__ inline void fq_walk_offsets(FqAhead &a, const int64_t *offsets_q, const int64_t *offsets_kv, int64_t total) {
+    if (a.w1 < total) {
+        a.q0 = offsets_q[a.b1]; a.q1 = offsets_q[a.b1 + 1];
+        a.k0 = offsets_kv[a.b1]; a.k1 = offsets_kv[a.b1 + 1];
+    }
+}
+// thread 0, at the end of item `it`: leave the next item's parameters for the whole workgroup, move on by one
+__device__ inline void fq_walk_publish(FqAhead &a, FqSlot *slot, int it, int H, int64_t total) {
+    fq_store_slot(&slot[(it + 1) & 1], a.w1 < total, a.b1, (int)(a.w1 % H), a.q0, a.q1, a.k0, a.k1);
+    a.w1 = a.w2;
+}
+
 // acc[row of a][lane of b] += a . b over the 128 features
 __device__ inline void fq_product(const bf16x8 (&a)[kFqKSteps], const bf16x8 (&b)[kFqKSteps], f32x16 &acc) {
 #pragma unroll

@@ -11,8 +11,9 @@
 // is computed), forms S^T = K Q^T (keys on the MFMA row axis, a query per lane), keeps a running maximum and sum
 // per query (online softmax, Section 2.1) and adds V^T P^T to its partial output.  At the end of the item the waves'
 // partial results (maximum, sum, output block) are merged in wave order through LDS: results are deterministic.
-// Work items are claimed as in the few-query backward kernel: from the library's work counters, samples with the
-// longest key lists first; a problem of at most four items per workgroup is dealt in turn in sample order.
+// Work items are taken as in the few-query backward kernel: samples with the longest key lists first, by tickets from
+// a work counter, and decoded one item ahead of the work (FqAhead); a problem of at most four items per workgroup is
+// dealt in turn in sample order.
 #include "jfa_fewq.h"
 
 namespace jfa {
@@ -29,7 +30,7 @@ __global__ __launch_bounds__(kFqThreads) void fwd_cross_fewq_kernel(const __bf16
     __shared__ __attribute__((aligned(1024))) char KV[kFqWaves][2][2 * kFqTile];   // per wave, two buffers: a block's K rows, then its V rows
     __shared__ float part_m[kFqWaves][kFqRows];   // per wave and query: maximum of the raw dot products of its blocks
     __shared__ float part_l[kFqWaves][kFqRows];   //                     sum of its probabilities against that maximum
-    __shared__ int64_t slot;
+    __shared__ FqSlot slot[2];
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const FqLane ln;
@@ -39,24 +40,28 @@ __global__ __launch_bounds__(kFqThreads) void fwd_cross_fewq_kernel(const __bf16
     const int64_t row_stride = (int64_t)H * D;
 
     const int64_t total = (int64_t)B * H;
-    WorkCursor cur;
-    cur.static_only = sched.static_only;
-    for (;;) {
-        // (the claim's barriers also say: the previous item's reads of the Q tile and the partial results are done)
-        const int64_t w = fetch_item(sched.counter, cur, total, &slot);
-        if (w < 0) break;
-        const int pos = (int)(w / H), head = (int)(w % H);
-        const int b = sched.order ? __builtin_amdgcn_readfirstlane(sched.order[pos]) : pos;
-        const int64_t q0 = offsets_q[b], k0 = offsets_kv[b];
-        const int Lq = (int)(offsets_q[b + 1] - q0), Lk = (int)(offsets_kv[b + 1] - k0);
+    FqAhead ahead;   // thread 0's
+    if (tid == 0) fq_walk_begin(ahead, slot, sched, offsets_q, offsets_kv, H, total);
+    for (int it = 0;; ++it) {
+        __syncthreads();   // this item's slot is written; the previous item's reads of the Q tile and the partial results are done
+        const FqSlot *const item = &slot[it & 1];
+        if (__builtin_amdgcn_readfirstlane(item->valid) == 0) break;
+        const int head = __builtin_amdgcn_readfirstlane(item->head);
+        const int Lq = __builtin_amdgcn_readfirstlane(item->Lq), Lk = __builtin_amdgcn_readfirstlane(item->Lk);
+        const int64_t q0 = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane(item->q0_hi) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane(item->q0_lo));
+        const int64_t k0 = (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane(item->k0_hi) << 32) | (uint32_t)__builtin_amdgcn_readfirstlane(item->k0_lo));
         const int n_blocks = (Lk + kFqRows - 1) / kFqRows;
-        if (Lq == 0) continue;   // nothing to write
-        if (Lk == 0) {           // no keys: an empty softmax, out = 0 and lse = -inf
-            if (wave == 0 && col < Lq) {
+        if (tid == 0) fq_walk_ahead(ahead, sched, H, total);
+        if (Lq == 0 || Lk == 0) {
+            if (Lq > 0 && wave == 0 && col < Lq) {   // no keys: an empty softmax, out = 0 and lse = -inf
                 const int64_t off = (q0 + col) * row_stride + (int64_t)head * D + half * (D / 2);
 #pragma unroll
                 for (int e = 0; e < D / 2; e += 8) *reinterpret_cast<u32x4 *>(out + off + e) = u32x4{0, 0, 0, 0};
                 if (half == 0) lse[(int64_t)head * sum_Bq + q0 + col] = -INFINITY;
+            }
+            if (tid == 0) {
+                fq_walk_offsets(ahead, offsets_q, offsets_kv, total);
+                fq_walk_publish(ahead, slot, it, H, total);
             }
             continue;
         }
@@ -72,6 +77,7 @@ __global__ __launch_bounds__(kFqThreads) void fwd_cross_fewq_kernel(const __bf16
         if (wave < n_blocks) fetch_block(wave, 0);
         __builtin_amdgcn_s_waitcnt(0x0070);   // this wave's copies have landed
         __syncthreads();                      // the Q tile is there for every wave
+        if (tid == 0) fq_walk_offsets(ahead, offsets_q, offsets_kv, total);   // in flight during the item's blocks
         bf16x8 Qf[kFqKSteps];
         ln.fragments(Qt, Qf);
         float m = -INFINITY, l = 0.0f;   // raw-score maximum and probability sum of this lane's query over this wave's blocks
@@ -167,6 +173,7 @@ __global__ __launch_bounds__(kFqThreads) void fwd_cross_fewq_kernel(const __bf16
                 if (d0 == 0) lse[(int64_t)head * sum_Bq + q0 + qi] = (mx * c + fast_log2(total_l)) * 0.6931471805599453f;
             }
         }
+        if (tid == 0) fq_walk_publish(ahead, slot, it, H, total);
     }
 }
 
