@@ -279,8 +279,8 @@ hipError_t schedule(const int64_t *offsets, const int64_t *offsets_other, int64_
 // D = 128, bf16) has one kernel per direction, bound by one pass over K and V.  Their work items are whole
 // (sample, head) pairs, claimed longest key list first: only the schedule's sample order is used (sorted by the keys'
 // 32-row block count).  Small problems are dealt in sample order without it.
-bool few_queries(bool f32, int D, const int64_t *offsets_kv, int64_t max_len_q) {
-    return !f32 && D == 128 && offsets_kv && max_len_q <= jfa::kFewqRows;
+bool few_queries(bool f32, int D, int H, const int64_t *offsets_kv, int64_t max_len_q) {
+    return !f32 && D == 128 && (int64_t)H * D <= (1 << 20) && offsets_kv && max_len_q <= jfa::kFewqRows;   // 32-bit row offsets inside a block
 }
 int few_queries_schedule(const int64_t *offsets, const int64_t *offsets_kv, int64_t B, int H, const Views &w, hipStream_t s,
                          jfa::Schedule *sc) {
@@ -304,7 +304,7 @@ int forward_impl(const char *who, bool f32, bool causal, const void *q, const vo
     Views w;
     if ((st = static_table ? get_static_table(B, &w) : get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
-    if (few_queries(f32, D, offsets_kv, max_len)) {
+    if (few_queries(f32, D, H, offsets_kv, max_len)) {
         jfa::Schedule sc;
         if ((st = few_queries_schedule(offsets, offsets_kv, B, H, w, s, &sc)) != JFA_OK) return st;
         ScopedTimer tm("fwd_cross_fewq", s);
@@ -339,7 +339,7 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
     Views w;
     if ((st = get_table(B, s, &w)) != JFA_OK) return st;
     hipError_t e;
-    if (few_queries(f32, D, offsets_kv, max_len)) {
+    if (few_queries(f32, D, H, offsets_kv, max_len)) {
         jfa::Schedule sc;
         if ((st = few_queries_schedule(offsets, offsets_kv, B, H, w, s, &sc)) != JFA_OK) return st;
         ScopedTimer tm("bwd_cross_fewq", s);
