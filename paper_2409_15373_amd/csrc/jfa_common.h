@@ -434,9 +434,7 @@ hipError_t launch_bwd_f32(const float *q, const float *k, const float *v, const 
                           const float *lse, const int64_t *offsets, const int64_t *offsets_kv, bool causal, int B, int H,
                           int D, Schedule s_dq, Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int cus,
                           hipStream_t stream);
-// delta[h, row] = sum_d dout * out, for T = float or bf16 (is_bf16)
-hipError_t launch_delta(const void *out, const void *dout, const float *lse, const int64_t *offsets, int B, int H,
-                        int D, bool is_bf16, float *delta, int cus, hipStream_t stream);
+// (the dQ kernel of every path runs first and computes delta[h, row] = sum_d dout * out for the kernels after it)
 
 // bf16 attention, register-staged kernels (any supported D, short samples)
 constexpr int kFwdBlockRows = 128;

@@ -98,13 +98,16 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(const float *__restri
     }
 }
 
-// dQ: tile = 64 queries, stream the sample's keys.
+// dQ: tile = 64 queries, stream the sample's keys.  The kernel is the first of the backward: it holds each query's dO
+// row anyway, reads the matching row of the forward's output, and computes delta = rowsum(dO o O) for its own use
+// and for the dK / dV kernel (no separate pass over dO and O, one launch less).
 template <int D>
 __global__ __launch_bounds__(kThreads) void dq_f32_kernel(const float *__restrict__ q, const float *__restrict__ k,
                                                           const float *__restrict__ v,
+                                                          const float *__restrict__ out_fwd,
                                                           const float *__restrict__ dout,
                                                           const float *__restrict__ lse,
-                                                          const float *__restrict__ delta,
+                                                          float *__restrict__ delta,
                                                           const int64_t *__restrict__ offsets,
                                                           const int64_t *__restrict__ offsets_kv, bool causal,
                                                           int B, int H, Schedule s, float *__restrict__ dq) {
@@ -128,14 +131,17 @@ __global__ __launch_bounds__(kThreads) void dq_f32_kernel(const float *__restric
         const int i = t.block * kRows + r;
         const int iq = i < t.len ? i : t.len - 1;
         float qr[kPer], dor[kPer], acc[kPer];
+        float dot = 0.0f;
         for (int e = 0; e < kPer; ++e) {
             const int64_t idx = ((t.row0 + iq) * H + t.head) * (int64_t)D + 4 * e + c;
             qr[e] = q[idx];
             dor[e] = dout[idx];
+            dot = fmaf(dor[e], out_fwd[idx], dot);
             acc[e] = 0.0f;
         }
         const float lse_i = lse[(int64_t)t.head * sum_B + t.row0 + iq];
-        const float delta_i = delta[(int64_t)t.head * sum_B + t.row0 + iq];
+        const float delta_i = quad_sum(dot);   // the four lanes of a row hold a quarter of its features each
+        if (i < t.len && c == 0) delta[(int64_t)t.head * sum_B + t.row0 + i] = delta_i;
         // causal (self attention only): query i sees keys 0 .. i, so the tile needs the keys up to its last query
         const int kend = causal && (t.block + 1) * kRows < t.olen ? (t.block + 1) * kRows : t.olen;
         for (int j0 = 0; j0 < kend; j0 += kCols) {
@@ -235,57 +241,6 @@ __global__ __launch_bounds__(kThreads) void dkv_f32_kernel(const float *__restri
     }
 }
 
-// delta[h, row] = sum_d dout[row, h, d] * out[row, h, d]; one group of D*sizeof(T)/16 lanes per (row, head).
-// With lse != nullptr the second plane of the buffer, delta[H + h, row], receives -lse[h, row] * sqrt(D): minus
-// the log-sum-exp in units of the unscaled dot product, the value the score accumulators of the direct-to-LDS
-// backward kernels start from.
-template <bool kBf16>
-__global__ __launch_bounds__(256) void delta_kernel(const void *__restrict__ out, const void *__restrict__ dout,
-                                                    const float *__restrict__ lse,
-                                                    const int64_t *__restrict__ offsets, int B, int H, int D,
-                                                    float *__restrict__ delta) {
-    const int64_t sum_B = offsets[B];
-    const int lanes = kBf16 ? D / 8 : D / 4;  // 16 bytes per lane; a power of two in [4, 32]
-    const int groups_per_block = 256 / lanes;
-    const int g = threadIdx.x / lanes, ln = threadIdx.x - g * lanes;
-    const int64_t n_pairs = sum_B * H;
-    for (int64_t pair = (int64_t)blockIdx.x * groups_per_block + g; pair < n_pairs;
-         pair += (int64_t)gridDim.x * groups_per_block) {
-        float acc = 0.0f;
-        if (kBf16) {
-            const uint4 a = reinterpret_cast<const uint4 *>(out)[pair * lanes + ln];
-            const uint4 b = reinterpret_cast<const uint4 *>(dout)[pair * lanes + ln];
-            const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
-            for (int e = 0; e < 4; ++e) {
-                acc = fmaf(__uint_as_float(aw[e] << 16), __uint_as_float(bw[e] << 16), acc);
-                acc = fmaf(__uint_as_float(aw[e] & 0xffff0000u), __uint_as_float(bw[e] & 0xffff0000u), acc);
-            }
-        } else {
-            const float4 a = reinterpret_cast<const float4 *>(out)[pair * lanes + ln];
-            const float4 b = reinterpret_cast<const float4 *>(dout)[pair * lanes + ln];
-            acc = fmaf(a.x, b.x, fmaf(a.y, b.y, fmaf(a.z, b.z, a.w * b.w)));
-        }
-        for (int d = 1; d < lanes; d <<= 1) acc += __shfl_xor(acc, d, 64);
-        if (ln == 0) {
-            const int64_t row = pair / H;
-            const int h = (int)(pair - row * H);
-            delta[(int64_t)h * sum_B + row] = acc;
-            if (lse != nullptr)
-                delta[(int64_t)(H + h) * sum_B + row] = -lse[(int64_t)h * sum_B + row] * sqrtf((float)D);
-        }
-    }
-}
-
-hipError_t launch_delta(const void *out, const void *dout, const float *lse, const int64_t *offsets, int B, int H,
-                        int D, bool is_bf16, float *delta, int cus, hipStream_t stream) {
-    const int grid = cus * 8;
-    if (is_bf16)
-        hipLaunchKernelGGL(delta_kernel<true>, dim3(grid), dim3(256), 0, stream, out, dout, lse, offsets, B, H, D, delta);
-    else
-        hipLaunchKernelGGL(delta_kernel<false>, dim3(grid), dim3(256), 0, stream, out, dout, lse, offsets, B, H, D, delta);
-    return hipGetLastError();
-}
-
 hipError_t launch_fwd_f32(const float *q, const float *k, const float *v, const int64_t *offsets,
                           const int64_t *offsets_kv, bool causal, int B, int H, int D, Schedule s, float *out, float *lse,
                           int cus, hipStream_t stream) {
@@ -306,11 +261,9 @@ hipError_t launch_bwd_f32(const float *q, const float *k, const float *v, const 
                           const float *lse, const int64_t *offsets, const int64_t *offsets_kv, bool causal, int B, int H,
                           int D, Schedule s_dq, Schedule s_dkv, float *dq, float *dk, float *dv, float *delta, int cus,
                           hipStream_t stream) {
-    hipError_t e = launch_delta(out, dout, nullptr, offsets, B, H, D, false, delta, cus, stream);
-    if (e != hipSuccess) return e;
 #define JFA_CASE(DD)                                                                                               \
     case DD:                                                                                                       \
-        hipLaunchKernelGGL(dq_f32_kernel<DD>, dim3(persistent_grid<dq_f32_kernel<DD>>(kThreads, cus)), dim3(kThreads), 0, stream, q, k, v, dout, lse, delta,   \
+        hipLaunchKernelGGL(dq_f32_kernel<DD>, dim3(persistent_grid<dq_f32_kernel<DD>>(kThreads, cus)), dim3(kThreads), 0, stream, q, k, v, out, dout, lse, delta,   \
                            offsets, offsets_kv, causal, B, H, s_dq, dq);                                           \
         hipLaunchKernelGGL(dkv_f32_kernel<DD>, dim3(persistent_grid<dkv_f32_kernel<DD>>(kThreads, cus)), dim3(kThreads), 0, stream, q, k, v, dout, lse, delta,  \
                            offsets_kv ? offsets_kv : offsets, offsets_kv ? offsets : nullptr, causal, B, H, s_dkv, dk, dv);  \
