@@ -122,3 +122,37 @@ def test_random_cross(seed):
     assert np.isneginf(f64(lse)[:, ~fin]).all()
     scaled(tag + "out", f64(out), r_out); scaled(tag + "lse", f64(lse)[:, fin], r_lse[:, fin])
     scaled(tag + "dq", f64(dq), r_dq); scaled(tag + "dk", f64(dk), r_dk); scaled(tag + "dv", f64(dv), r_dv)
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_cross_with_few_queries(seed):
+    """At most 32 queries per sample at D = 128 (the few-query kernels): B up to 400 so that some draws take the
+    schedule and tickets (more than four items per workgroup) and others the static deal; key lists of 0 .. 700 rows
+    with the boundary lengths mixed in."""
+    from paper_2409_15373_amd import binding
+    rng = np.random.default_rng(3000 + seed)
+    B, H, D = int(rng.choice([1, 3, 40, 400])), int(rng.integers(1, 5)), 128
+    Lq = np.where(rng.random(B) < 0.3, rng.choice([0, 1, 31, 32], B), rng.integers(0, 33, B))
+    Lk = draw_lengths(rng, B, 700)
+    Lq[0] = max(Lq[0], 3); Lk[0] = max(Lk[0], 3)
+    oq, ok = offsets_from_lengths(Lq), offsets_from_lengths(Lk)
+    nq, nk = int(oq[-1]), int(ok[-1])
+    oqd, okd = torch.from_numpy(oq).cuda(), torch.from_numpy(ok).cuda()
+    (q, qd), (do, dod) = (bf16_tensor(rng, nq, H, D, 1.0) for _ in range(2))
+    (k, kd), (v, vd) = (bf16_tensor(rng, nk, H, D, 1.0) for _ in range(2))
+    nan = float("nan")   # rows of samples that have both queries and keys must all be written
+    lse = torch.full((H, nq), nan, dtype=torch.float32, device="cuda")
+    out = torch.full((nq, H, D), nan, dtype=torch.bfloat16, device="cuda")
+    stats = torch.empty((2, H, nq), dtype=torch.float32, device="cuda")
+    dq = torch.full((nq, H, D), nan, dtype=torch.bfloat16, device="cuda")
+    dk, dv = (torch.full((nk, H, D), nan, dtype=torch.bfloat16, device="cuda") for _ in range(2))
+    binding.jfa_forward_cross(qd, kd, vd, oqd, okd, 32, 700, out=out, lse=lse)
+    binding.jfa_backward_cross(qd, kd, vd, out, dod, lse, oqd, okd, 32, 700, dq=dq, dk=dk, dv=dv, delta=stats)
+    torch.cuda.synchronize()
+    r_out, r_lse = cross_oracle.forward(q, k, v, oq, ok)
+    r_dq, r_dk, r_dv, _ = cross_oracle.backward(q, k, v, do, oq, ok)
+    fin = np.isfinite(r_lse[0])
+    tag = f"seed {seed} B {B} H {H}: "
+    assert np.isneginf(f64(lse)[:, ~fin]).all()
+    scaled(tag + "out", f64(out), r_out); scaled(tag + "lse", f64(lse)[:, fin], r_lse[:, fin])
+    scaled(tag + "dq", f64(dq), r_dq); scaled(tag + "dk", f64(dk), r_dk); scaled(tag + "dv", f64(dv), r_dv)
