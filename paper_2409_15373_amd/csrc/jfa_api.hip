@@ -180,7 +180,7 @@ FwdVariant forward_variant(int64_t max_len, int D, int H) {
 }
 
 // Small problems skip the scheduler launch: the attention kernels build the schedule themselves and deal the work
-// statically (see build_schedule_in_kernel).  max_len bounds every sample's length, so B * blocks(max_len) * H bounds
+// statically (see build_small_work).  max_len bounds every sample's length, so B * blocks(max_len) * H bounds
 // the number of work items; at most four per workgroup is the size up to which static dealing is used anyway.
 bool small_problem(int64_t B, int64_t max_len, int H, int block_rows, int cus) {
     if (B > jfa::kInlineCap) return false;
@@ -363,10 +363,10 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
     if (f32) {
         jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
         jfa::Schedule s_dkv{w.order[kv], w.tile_start[kv], w.counters + jfa::kXcds};
-        if (in_kernel) {   // the dQ kernel runs first and builds schedule 0; dK / dV build their own only when it differs (cross attention)
+        if (in_kernel) {   // every kernel builds the schedule of its own work items, in LDS
             s_dq.static_only = s_dkv.static_only = true;
             s_dq.build_rows = block_rows;
-            s_dkv.build_rows = kv ? block_rows : 0;
+            s_dkv.build_rows = block_rows;
         }
         ScopedTimer tm_bwd("bwd_f32", s);
         e = jfa::launch_bwd_f32((const float *)q, (const float *)k, (const float *)v, (const float *)out, (const float *)dout, lse,
@@ -389,10 +389,10 @@ int backward_impl(const char *who, bool f32, bool causal, const void *q, const v
     }
     jfa::Schedule s_dq{w.order[0], w.tile_start[0], w.counters};
     jfa::Schedule s_dkv{w.order[kv], w.tile_start[kv], w.counters + jfa::kXcds};
-    if (in_kernel) {   // the dQ kernel runs first and builds schedule 0; dK / dV build their own only when it differs (cross attention)
+    if (in_kernel) {   // every kernel builds the schedule of its own work items, in LDS
         s_dq.static_only = s_dkv.static_only = true;
         s_dq.build_rows = block_rows;
-        s_dkv.build_rows = kv ? block_rows : 0;
+        s_dkv.build_rows = block_rows;
     }
     // the dQ kernel goes first: it computes delta = rowsum(dO o O) for its own rows and leaves it for the dK / dV kernel
     { ScopedTimer tm("dq_bf16", s); e = jfa::launch_dq_bf16(q, k, v, out, dout, lse, delta, offsets, offsets_kv, causal, (int)B, H, D, s_dq, dq, w.cus, s); }

@@ -95,22 +95,28 @@ __global__ __launch_bounds__(kBwdThreads, 2) void dq_bf16_kernel(const __bf16 *_
     const float scale = 1.0f / sqrtf((float)D);
     const float c = 1.4426950408889634f * scale;
     static_assert(sizeof(Smem) >= kInlineScratchInts * sizeof(int), "the stage buffers double as the scheduler's scratch");
-    if (s.build_rows)   // small problem: no scheduler launch has run
-        build_schedule_in_kernel(offsets, CROSS ? offsets_kv : nullptr, B, s.build_rows, const_cast<int32_t *>(s.order),
-                                 const_cast<int32_t *>(s.tile_start), reinterpret_cast<int *>(&sm));
-    const int64_t total = (int64_t)s.tile_start[B] * H;
+    __shared__ SmallWork mine;
+    const bool small = s.build_rows != 0;   // small problem: no scheduler launch has run, the schedule is built here, in LDS
+    if (small) build_small_work(offsets, CROSS ? offsets_kv : nullptr, B, H, s.build_rows, reinterpret_cast<int *>(&sm), &mine);
+    const int64_t total = small ? 0 : (int64_t)s.tile_start[B] * H;
     const int64_t sum_B = offsets[B];
     const int64_t row_stride = (int64_t)H * D;
 
     WorkCursor cursor;
     cursor.static_only = s.static_only;
-    for (;;) {
-        __syncthreads();
-        if (tid == 0) sm.slot = next_work(s.counter, cursor, total);
-        __syncthreads();
-        const int64_t w = uniform64(sm.slot);
-        if (w < 0) break;
-        const Work t = decode_work(s, offsets, B, H, w, CROSS ? offsets_kv : nullptr);
+    for (int n = 0;; ++n) {
+        Work t;
+        if (small) {   // the workgroup's items were decoded when the schedule was built
+            __syncthreads();   // the previous item's use of the stage buffers is over
+            if (n >= __builtin_amdgcn_readfirstlane(mine.count) || !load_work<CROSS>(&mine.item[n], t)) break;
+        } else {
+            __syncthreads();
+            if (tid == 0) sm.slot = next_work(s.counter, cursor, total);
+            __syncthreads();
+            const int64_t w = uniform64(sm.slot);
+            if (w < 0) break;
+            t = decode_work(s, offsets, B, H, w, CROSS ? offsets_kv : nullptr);
+        }
         const int Lq = t.len;                      // queries of the sample
         const int L = CROSS ? t.olen : t.len;      // keys of the sample
         const int64_t krow0 = CROSS ? t.orow0 : t.row0;
@@ -234,22 +240,28 @@ __global__ __launch_bounds__(kBwdThreads, D <= 64 ? 2 : 1) void dkv_bf16_kernel(
     const float scale = 1.0f / sqrtf((float)D);
     const float c = 1.4426950408889634f * scale;
     static_assert(sizeof(Smem) >= kInlineScratchInts * sizeof(int), "the stage buffers double as the scheduler's scratch");
-    if (s.build_rows)   // small problem: no scheduler launch has run
-        build_schedule_in_kernel(offsets, CROSS ? offsets_q : nullptr, B, s.build_rows, const_cast<int32_t *>(s.order),
-                                 const_cast<int32_t *>(s.tile_start), reinterpret_cast<int *>(&sm));
-    const int64_t total = (int64_t)s.tile_start[B] * H;
+    __shared__ SmallWork mine;
+    const bool small = s.build_rows != 0;   // small problem: no scheduler launch has run, the schedule is built here, in LDS
+    if (small) build_small_work(offsets, CROSS ? offsets_q : nullptr, B, H, s.build_rows, reinterpret_cast<int *>(&sm), &mine);
+    const int64_t total = small ? 0 : (int64_t)s.tile_start[B] * H;
     const int64_t sum_B = CROSS ? offsets_q[B] : offsets[B];   // lse and delta are indexed by query rows
     const int64_t row_stride = (int64_t)H * D;
 
     WorkCursor cursor;
     cursor.static_only = s.static_only;
-    for (;;) {
-        __syncthreads();
-        if (tid == 0) sm.slot = next_work(s.counter, cursor, total);
-        __syncthreads();
-        const int64_t w = uniform64(sm.slot);
-        if (w < 0) break;
-        const Work t = decode_work(s, offsets, B, H, w, CROSS ? offsets_q : nullptr);
+    for (int n = 0;; ++n) {
+        Work t;
+        if (small) {   // the workgroup's items were decoded when the schedule was built
+            __syncthreads();   // the previous item's use of the stage buffers is over
+            if (n >= __builtin_amdgcn_readfirstlane(mine.count) || !load_work<CROSS>(&mine.item[n], t)) break;
+        } else {
+            __syncthreads();
+            if (tid == 0) sm.slot = next_work(s.counter, cursor, total);
+            __syncthreads();
+            const int64_t w = uniform64(sm.slot);
+            if (w < 0) break;
+            t = decode_work(s, offsets, B, H, w, CROSS ? offsets_q : nullptr);
+        }
         const int Lk = t.len;                      // keys of the sample
         const int L = CROSS ? t.olen : t.len;      // queries of the sample
         const int64_t qrow0 = CROSS ? t.orow0 : t.row0;

@@ -16,10 +16,9 @@ struct Schedule {
     const int32_t *order;       // [B]
     const int32_t *tile_start;  // [B+1]
     int32_t *counter;           // kXcds zeroed work counters (one queue per XCD), bumped by the persistent workgroups
-    // Small problems (see build_schedule_in_kernel) run without a scheduler launch: the counters are then not valid
-    // and work is dealt statically (static_only); build_rows > 0 tells the kernel to fill order / tile_start itself for
-    // row blocks of that many rows, 0 that they are filled already (by the scheduler kernel, or by an earlier
-    // attention kernel of the same call that uses the same schedule).
+    // Small problems (see build_small_work) run without a scheduler launch: the counters are then not valid
+    // and work is dealt statically (static_only); build_rows > 0 tells the kernel to build the schedule itself, in LDS, for
+    // row blocks of that many rows (order and tile_start are then not looked at), 0 that the scheduler kernel has filled them.
     int build_rows = 0;
     bool static_only = false;
 };
@@ -171,25 +170,41 @@ __device__ inline Work decode_work(const Schedule &s, const int64_t *offsets, in
     return t;
 }
 
+// A decoded work item parked in LDS for the whole workgroup.
+struct WorkSlot {
+    int valid;   // 0: nothing left
+    int sample, head, block, len;
+    int row0_lo, row0_hi;
+    int olen, orow0_lo, orow0_hi;   // the other side's rows (cross attention only)
+};
+
 // The schedule of a small problem, built inside the attention kernel instead of by a launch of its own (a launch and
-// the scheduler kernel's chain of dependent trips to memory cost more than these problems' whole arithmetic).  Every
-// workgroup computes the same schedule -- samples in descending order of their stream's block count, equal counts in
-// sample order, so the result does not depend on who computes it -- and writes it to the same global arrays: every
-// location receives one value only, the same from every writer, so whichever copy a later read meets is right; the
-// barrier at the end makes the workgroup's own writes visible to all its waves.  Lengths are fetched once, by all
-// threads at once, into LDS; one wave then runs a counting sort over at most kInlineBins keys, in which the ranks
-// inside a bin come from ballots, and a scan of the block counts in sorted order.
+// the scheduler kernel's chain of dependent trips to memory cost more than these problems' whole arithmetic), and
+// kept in LDS: every workgroup computes the same schedule -- samples in descending order of their stream's block
+// count, equal counts in sample order, the order the scheduler kernel produces (samples in their own order when there
+// is at most one item per workgroup) -- and decodes from it the at most
+// kSmallItems work items that the static deal gives it (item blockIdx + n * gridDim), so that nothing of the
+// schedule is written to or read back from memory: after the one trip for the lengths, an item costs one more for
+// its sample's offsets.  Lengths are fetched once, by all threads at once, into LDS; one wave then runs a counting
+// sort over at most kInlineBins keys, in which the ranks inside a bin come from ballots, a scan of the block counts
+// in sorted order, and the search for the workgroup's items.
 // `scratch`: kInlineScratchInts ints of LDS that nothing else uses until the call returns (the kernels lend a stage
-// buffer).  Called by every thread of the workgroup; B <= kInlineCap.
+// buffer); `mine` is LDS that lasts.  Called by every thread of the workgroup; B <= kInlineCap; ends with a barrier.
 constexpr int kInlineCap = 1024;
 constexpr int kInlineBins = 64;
-constexpr int kInlineScratchInts = 2 * kInlineBins + kInlineCap + kInlineCap / 4 + kInlineCap / 2;   // 7.5 KB
-__device__ inline void build_schedule_in_kernel(const int64_t *offsets, const int64_t *offsets_other, int B, int block_rows,
-                                                int32_t *order, int32_t *tile_start, int *scratch) {
+constexpr int kSmallItems = 4;
+constexpr int kInlineScratchInts = 2 * kInlineBins + kInlineCap + kInlineCap / 4 + kInlineCap / 2 + kInlineCap + 4;   // 11.6 KB
+struct SmallWork {
+    int count;                     // items of this workgroup
+    WorkSlot item[kSmallItems];
+};
+__device__ inline void build_small_work(const int64_t *offsets, const int64_t *offsets_other, int B, int H, int block_rows,
+                                        int *scratch, SmallWork *mine) {
     int *const bins = scratch;                                    // [kInlineBins] counts, then [kInlineBins] next free positions
     int *const nblk = scratch + 2 * kInlineBins;                  // [kInlineCap] row blocks of sample b
     uint8_t *const keys = reinterpret_cast<uint8_t *>(nblk + kInlineCap);               // [kInlineCap] sort key of sample b
     uint16_t *const sorted = reinterpret_cast<uint16_t *>(nblk + kInlineCap + kInlineCap / 4);   // [kInlineCap] sample at position p
+    int *const start = nblk + kInlineCap + kInlineCap / 4 + kInlineCap / 2;             // [kInlineCap + 1] first tile of position p
     for (int b = threadIdx.x; b < B; b += blockDim.x) {
         const int64_t len = offsets[b + 1] - offsets[b];
         const int64_t stream = offsets_other ? offsets_other[b + 1] - offsets_other[b] : len;
@@ -201,6 +216,28 @@ __device__ inline void build_schedule_in_kernel(const int64_t *offsets, const in
     __syncthreads();
     if (threadIdx.x < 64) {
         const int lane = threadIdx.x;
+        // inclusive scan of the block counts, samples taken in the order `at(p)`, into start[1 .. B]; returns the total
+        auto scan_blocks = [&](auto at) {
+            int carry = 0;
+            if (lane == 0) start[0] = 0;
+            for (int p0 = 0; p0 < B; p0 += 64) {
+                const int p = p0 + lane;
+                int incl = p < B ? nblk[at(p)] : 0;
+                for (int d = 1; d < 64; d <<= 1) {
+                    const int y = __shfl_up(incl, d, 64);
+                    if (lane >= d) incl += y;
+                }
+                incl += carry;
+                if (p < B) start[p + 1] = incl;
+                carry = __shfl(incl, 63, 64);
+            }
+            return carry;
+        };
+        // 0. With at most one item per workgroup the order of the deal is of no consequence: the samples stay in their
+        //    own order and the sort (steps 1 to 3, most of this function's time) is skipped.
+        int blocks = scan_blocks([](int p) { return p; });
+        const bool in_sample_order = (int64_t)blocks * H <= (int64_t)gridDim.x;
+        if (!in_sample_order) {
         // 1. samples per key
         for (int b0 = 0; b0 < B; b0 += 64) {
             const bool valid = b0 + lane < B;
@@ -235,30 +272,55 @@ __device__ inline void build_schedule_in_kernel(const int64_t *offsets, const in
                 const int kk = __builtin_amdgcn_readlane(key, leader);
                 const uint64_t same = __builtin_amdgcn_ballot_w64(key == kk);
                 const int base = bins[kInlineBins + kk];
-                if (key == kk) {
-                    const int pos = base + __popcll(same & ((1ull << lane) - 1));
-                    sorted[pos] = (uint16_t)b;
-                    order[pos] = b;
-                }
+                if (key == kk) sorted[base + __popcll(same & ((1ull << lane) - 1))] = (uint16_t)b;
                 if (lane == leader) bins[kInlineBins + kk] = base + __popcll(same);
                 todo &= ~same;
             }
         }
         // 4. inclusive scan of the block counts in sorted order
-        int carry = 0;
-        if (lane == 0) tile_start[0] = 0;
-        for (int p0 = 0; p0 < B; p0 += 64) {
-            const int p = p0 + lane;
-            int incl = p < B ? nblk[sorted[p]] : 0;
-            for (int d = 1; d < 64; d <<= 1) {
-                const int y = __shfl_up(incl, d, 64);
-                if (lane >= d) incl += y;
-            }
-            incl += carry;
-            if (p < B) tile_start[p + 1] = incl;
-            carry = __shfl(incl, 63, 64);
+        blocks = scan_blocks([&](int p) { return (int)sorted[p]; });
         }
-        __threadfence_block();
+        // 5. this workgroup's items: the position of each in the sorted order (64 probes per round), then, a lane per
+        //    item, the sample's offsets -- the only trip to memory, all items at once
+        const int64_t total = (int64_t)blocks * H;
+        int my_p = 0, my_r = 0, n_items = 0;
+        for (int n = 0; n < kSmallItems; ++n) {
+            const int64_t w = (int64_t)blockIdx.x + (int64_t)n * gridDim.x;
+            if (w >= total) break;
+            int lo = 0, hi = B;   // invariant: start[lo] * H <= w < start[hi] * H
+            while (hi - lo > 1) {
+                const int step = (hi - lo + 63) / 64;
+                const int idx = lo + (lane + 1) * step;
+                const bool ok = idx < hi && (int64_t)start[idx] * H <= w;   // true for a prefix of the lanes
+                const int cnt = __popcll(__builtin_amdgcn_ballot_w64(ok));
+                lo += cnt * step;
+                hi = hi < lo + step ? hi : lo + step;
+            }
+            if (lane == n) {
+                my_p = lo;
+                my_r = (int)(w - (int64_t)start[lo] * H);
+            }
+            n_items = n + 1;
+        }
+        if (lane == 0) mine->count = n_items;
+        if (lane < n_items) {
+            const int sample = in_sample_order ? my_p : (int)sorted[my_p];
+            const int per_head = start[my_p + 1] - start[my_p];
+            const int64_t row0 = offsets[sample];
+            WorkSlot *slot = &mine->item[lane];
+            slot->valid = 1;
+            slot->sample = sample;
+            slot->head = my_r / per_head;
+            slot->block = my_r - (my_r / per_head) * per_head;
+            slot->len = (int)(offsets[sample + 1] - row0);
+            slot->row0_lo = (int)(uint32_t)row0;
+            slot->row0_hi = (int)(uint32_t)((uint64_t)row0 >> 32);
+            const int64_t *const oo = offsets_other ? offsets_other : offsets;   // the other side's rows: the same without a second array
+            const int64_t orow0 = oo[sample];
+            slot->olen = (int)(oo[sample + 1] - orow0);
+            slot->orow0_lo = (int)(uint32_t)orow0;
+            slot->orow0_hi = (int)(uint32_t)((uint64_t)orow0 >> 32);
+        }
     }
     __syncthreads();
 }
@@ -277,13 +339,6 @@ inline int persistent_grid(int threads, int cus) {
     return (grid + kXcds - 1) / kXcds * kXcds;  // next_work() relies on a multiple of 8
 }
 
-// A decoded work item parked in LDS for the whole workgroup.
-struct WorkSlot {
-    int valid;   // 0: nothing left
-    int sample, head, block, len;
-    int row0_lo, row0_hi;
-    int olen, orow0_lo, orow0_hi;   // the other side's rows (cross attention only)
-};
 
 // Claim the next work item and decode it into `slot`.  Called by every lane of ONE wave (the claim itself is
 // made by its lane 0, whose registers hold `cur`); meant to be issued right after a tile's first loads so

@@ -10,8 +10,8 @@ namespace jfa {
 constexpr int kRows = kF32BlockRows;  // rows (queries or keys) per tile
 // streamed rows per LDS stage: two [cols][D] fp32 stages stay within 32 KB
 template <int D> constexpr int cols_for() { return 4096 / D < 64 ? 4096 / D : 64; }
-static_assert(cols_for<32>() * 32 >= kInlineScratchInts && cols_for<128>() * 128 >= kInlineScratchInts,
-              "a stage buffer doubles as the in-kernel scheduler's scratch");
+static_assert(2 * cols_for<32>() * 32 >= kInlineScratchInts && 2 * cols_for<128>() * 128 >= kInlineScratchInts,
+              "the two stage buffers double as the in-kernel scheduler's scratch");
 constexpr int kThreads = kRows * 4;
 
 __device__ inline float quad_sum(float x) {
@@ -47,21 +47,29 @@ __global__ __launch_bounds__(kThreads) void fwd_f32_kernel(const float *__restri
                                                            float *__restrict__ lse) {
     constexpr int kPer = D / 4;
     constexpr int kCols = cols_for<D>();
-    __shared__ float Ks[kCols * D];
-    __shared__ float Vs[kCols * D];
+    __shared__ float KVs[2 * kCols * D];   // staged K rows, then V rows (the schedule build borrows all of it)
+    float *const Ks = KVs, *const Vs = KVs + kCols * D;
     __shared__ int64_t slot;
     WorkCursor probe;
     const int r = threadIdx.x >> 2, c = threadIdx.x & 3;
     const float scale = 1.0f / sqrtf((float)D);
-    if (s.build_rows)   // small problem: no scheduler launch has run
-        build_schedule_in_kernel(offsets, offsets_kv, B, s.build_rows, const_cast<int32_t *>(s.order),
-                                 const_cast<int32_t *>(s.tile_start), reinterpret_cast<int *>(Ks));
+    __shared__ SmallWork mine;
+    const bool small = s.build_rows != 0;   // small problem: no scheduler launch has run, the schedule is built here, in LDS
+    if (small) build_small_work(offsets, offsets_kv, B, H, s.build_rows, reinterpret_cast<int *>(KVs), &mine);
     probe.static_only = s.static_only;
-    const int64_t total = (int64_t)s.tile_start[B] * H;
+    const int64_t total = small ? 0 : (int64_t)s.tile_start[B] * H;
     const int64_t sum_B = offsets[B];
 
-    for (int64_t w = fetch_work(s.counter, probe, total, &slot); w >= 0; w = fetch_work(s.counter, probe, total, &slot)) {
-        const Work t = decode_work(s, offsets, B, H, w, offsets_kv);   // keys: rows orow0 .. orow0 + olen - 1
+    for (int n = 0;; ++n) {
+        Work t;   // keys: rows orow0 .. orow0 + olen - 1
+        if (small) {   // the workgroup's items were decoded when the schedule was built
+            __syncthreads();   // the previous item's use of the staging arrays is over
+            if (n >= __builtin_amdgcn_readfirstlane(mine.count) || !load_work<true>(&mine.item[n], t)) break;
+        } else {
+            const int64_t w = fetch_work(s.counter, probe, total, &slot);
+            if (w < 0) break;
+            t = decode_work(s, offsets, B, H, w, offsets_kv);
+        }
         const int i = t.block * kRows + r;                    // query index inside the sample
         const int iq = i < t.len ? i : t.len - 1;             // rows past the end recompute the last row
         float qr[kPer], acc[kPer];
@@ -113,21 +121,29 @@ __global__ __launch_bounds__(kThreads) void dq_f32_kernel(const float *__restric
                                                           int B, int H, Schedule s, float *__restrict__ dq) {
     constexpr int kPer = D / 4;
     constexpr int kCols = cols_for<D>();
-    __shared__ float Ks[kCols * D];
-    __shared__ float Vs[kCols * D];
+    __shared__ float KVs[2 * kCols * D];   // staged K rows, then V rows (the schedule build borrows all of it)
+    float *const Ks = KVs, *const Vs = KVs + kCols * D;
     __shared__ int64_t slot;
     WorkCursor probe;
     const int r = threadIdx.x >> 2, c = threadIdx.x & 3;
     const float scale = 1.0f / sqrtf((float)D);
-    if (s.build_rows)   // small problem: no scheduler launch has run
-        build_schedule_in_kernel(offsets, offsets_kv, B, s.build_rows, const_cast<int32_t *>(s.order),
-                                 const_cast<int32_t *>(s.tile_start), reinterpret_cast<int *>(Ks));
+    __shared__ SmallWork mine;
+    const bool small = s.build_rows != 0;   // small problem: no scheduler launch has run, the schedule is built here, in LDS
+    if (small) build_small_work(offsets, offsets_kv, B, H, s.build_rows, reinterpret_cast<int *>(KVs), &mine);
     probe.static_only = s.static_only;
-    const int64_t total = (int64_t)s.tile_start[B] * H;
+    const int64_t total = small ? 0 : (int64_t)s.tile_start[B] * H;
     const int64_t sum_B = offsets[B];
 
-    for (int64_t w = fetch_work(s.counter, probe, total, &slot); w >= 0; w = fetch_work(s.counter, probe, total, &slot)) {
-        const Work t = decode_work(s, offsets, B, H, w, offsets_kv);
+    for (int n = 0;; ++n) {
+        Work t;
+        if (small) {   // the workgroup's items were decoded when the schedule was built
+            __syncthreads();   // the previous item's use of the staging arrays is over
+            if (n >= __builtin_amdgcn_readfirstlane(mine.count) || !load_work<true>(&mine.item[n], t)) break;
+        } else {
+            const int64_t w = fetch_work(s.counter, probe, total, &slot);
+            if (w < 0) break;
+            t = decode_work(s, offsets, B, H, w, offsets_kv);
+        }
         const int i = t.block * kRows + r;
         const int iq = i < t.len ? i : t.len - 1;
         float qr[kPer], dor[kPer], acc[kPer];
@@ -179,23 +195,31 @@ __global__ __launch_bounds__(kThreads) void dkv_f32_kernel(const float *__restri
                                                            float *__restrict__ dv) {
     constexpr int kPer = D / 4;
     constexpr int kCols = cols_for<D>();
-    __shared__ float Qs[kCols * D];
-    __shared__ float Os[kCols * D];
+    __shared__ float QOs[2 * kCols * D];   // staged Q rows, then dO rows (the schedule build borrows all of it)
+    float *const Qs = QOs, *const Os = QOs + kCols * D;
     __shared__ float lse_s[kCols];
     __shared__ float delta_s[kCols];
     __shared__ int64_t slot;
     WorkCursor probe;
     const int r = threadIdx.x >> 2, c = threadIdx.x & 3;
     const float scale = 1.0f / sqrtf((float)D);
-    if (s.build_rows)   // small problem: no scheduler launch has run
-        build_schedule_in_kernel(offsets, offsets_q, B, s.build_rows, const_cast<int32_t *>(s.order),
-                                 const_cast<int32_t *>(s.tile_start), reinterpret_cast<int *>(Qs));
+    __shared__ SmallWork mine;
+    const bool small = s.build_rows != 0;   // small problem: no scheduler launch has run, the schedule is built here, in LDS
+    if (small) build_small_work(offsets, offsets_q, B, H, s.build_rows, reinterpret_cast<int *>(QOs), &mine);
     probe.static_only = s.static_only;
-    const int64_t total = (int64_t)s.tile_start[B] * H;
+    const int64_t total = small ? 0 : (int64_t)s.tile_start[B] * H;
     const int64_t sum_B = offsets_q ? offsets_q[B] : offsets[B];   // lse and delta are indexed by query rows
 
-    for (int64_t w = fetch_work(s.counter, probe, total, &slot); w >= 0; w = fetch_work(s.counter, probe, total, &slot)) {
-        const Work t = decode_work(s, offsets, B, H, w, offsets_q);   // queries: rows orow0 .. orow0 + olen - 1
+    for (int n = 0;; ++n) {
+        Work t;   // queries: rows orow0 .. orow0 + olen - 1
+        if (small) {   // the workgroup's items were decoded when the schedule was built
+            __syncthreads();   // the previous item's use of the staging arrays is over
+            if (n >= __builtin_amdgcn_readfirstlane(mine.count) || !load_work<true>(&mine.item[n], t)) break;
+        } else {
+            const int64_t w = fetch_work(s.counter, probe, total, &slot);
+            if (w < 0) break;
+            t = decode_work(s, offsets, B, H, w, offsets_q);
+        }
         const int j = t.block * kRows + r;
         const int jk = j < t.len ? j : t.len - 1;
         float kr[kPer], vr[kPer], acck[kPer], accv[kPer];

@@ -59,10 +59,10 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
     // harmless in bf16), which keeps the rescaling of the accumulator off the common path.
     const float tau = 8.0f / c;
     static_assert(sizeof(Smem) >= kInlineScratchInts * sizeof(int), "the stage buffers double as the scheduler's scratch");
-    if (s.build_rows)   // small problem: no scheduler launch has run
-        build_schedule_in_kernel(offsets, CROSS ? offsets_kv : nullptr, B, s.build_rows, const_cast<int32_t *>(s.order),
-                                 const_cast<int32_t *>(s.tile_start), reinterpret_cast<int *>(&sm));
-    const int64_t total = (int64_t)s.tile_start[B] * H;
+    __shared__ SmallWork mine;
+    const bool small = s.build_rows != 0;   // small problem: no scheduler launch has run, the schedule is built here, in LDS
+    if (small) build_small_work(offsets, CROSS ? offsets_kv : nullptr, B, H, s.build_rows, reinterpret_cast<int *>(&sm), &mine);
+    const int64_t total = small ? 0 : (int64_t)s.tile_start[B] * H;
     const int64_t sum_B = offsets[B];
     const int64_t row_stride = (int64_t)H * D;    // elements between consecutive rows of one head
     const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
@@ -74,13 +74,19 @@ __global__ __launch_bounds__(kFwdThreads, 2) void fwd_bf16_kernel(const __bf16 *
 
     WorkCursor cursor;
     cursor.static_only = s.static_only;
-    for (;;) {
-        __syncthreads();
-        if (tid == 0) sm.slot = next_work(s.counter, cursor, total);
-        __syncthreads();
-        const int64_t w = uniform64(sm.slot);
-        if (w < 0) break;
-        const Work t = decode_work(s, offsets, B, H, w, CROSS ? offsets_kv : nullptr);
+    for (int n = 0;; ++n) {
+        Work t;
+        if (small) {   // the workgroup's items were decoded when the schedule was built
+            __syncthreads();   // the previous item's use of the stage buffers is over
+            if (n >= __builtin_amdgcn_readfirstlane(mine.count) || !load_work<CROSS>(&mine.item[n], t)) break;
+        } else {
+            __syncthreads();
+            if (tid == 0) sm.slot = next_work(s.counter, cursor, total);
+            __syncthreads();
+            const int64_t w = uniform64(sm.slot);
+            if (w < 0) break;
+            t = decode_work(s, offsets, B, H, w, CROSS ? offsets_kv : nullptr);
+        }
         const int Lq = t.len;                      // queries of the sample
         const int L = CROSS ? t.olen : t.len;      // keys of the sample
         const int64_t krow0 = CROSS ? t.orow0 : t.row0;
