@@ -218,17 +218,18 @@ __global__ __launch_bounds__(kDmaThreads, 2) void fwd_bf16_dma_kernel(const __bf
             for (int ks = 0; ks < kKSteps; ++ks) a = mfma_32x32x16(kop[ks], qreg[ks], a);
         };
         auto accumulate = [&](const char *tile, int mb, const bf16x8 (&p)[2], const int (&vaddr)[kDBlocks]) {
+            bf16x8 vop[2][kDBlocks];
 #pragma unroll
-            for (int ts = 0; ts < 2; ++ts) {
-                bf16x8 vop[kDBlocks];
+            for (int ts = 0; ts < 2; ++ts)
 #pragma unroll
                 for (int db = 0; db < kDBlocks; ++db) {
                     const char *pvp = tile + (mb * 32 + ts * 16) * 256 + vaddr[db];
-                    vop[db] = concat(lds_read_tr16(pvp), lds_read_tr16(pvp + 8 * 256));
+                    vop[ts][db] = concat(lds_read_tr16(pvp), lds_read_tr16(pvp + 8 * 256));
                 }
 #pragma unroll
-                for (int db = 0; db < kDBlocks; ++db) o[db] = mfma_32x32x16(vop[db], p[ts], o[db]);
-            }
+            for (int ts = 0; ts < 2; ++ts)
+#pragma unroll
+                for (int db = 0; db < kDBlocks; ++db) o[db] = mfma_32x32x16(vop[ts][db], p[ts], o[db]);
         };
         // exponentials of one unit (32 keys x 32 queries) against the reference maximum; the rounded
         // probabilities are what the second product uses, so they are what the row sum adds up
